@@ -1,0 +1,391 @@
+"""CPU oracle for one MSLT stage step (TEST INFRASTRUCTURE, not a product path).
+
+Plain numpy float64 implementation of what a stage step of Multi-Stage Layerwise
+Training computes (paper Section 3.2): a BERT encoder stack (BERT by citation,
+Section 4.1) with a tied masked-LM head, ordinary reverse-mode differentiation of the
+masked-LM loss, from which the gradients of the trainable tensors (the top layers
+and the output layer; everything in the first stage / the retraining stage) are
+kept, and a textbook Adam / LAMB update (Sections 4.1 and 5 name the optimizers).
+
+The method is exact: a stage step yields, for the tensors it trains, the very
+gradients plain back-propagation would give, and simply omits the others (Section
+3.1, last paragraph).  So this file is the plain definition written out; nothing is
+blocked, fused or reordered.  Matrix products go through one hook (`Ops.mm`) that is
+either numpy's matmul or a pure-Python triple loop for tiny cross-checks.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+file.  It imports nothing from the GPU package and shares no code with it.
+
+Pins (tests/test_oracle_*.py): central finite differences of every tensor;
+triple-loop products; softmax/LayerNorm invariants; loss = ln V closed form;
+uniform-attention and S=1 special cases; stage-step gradients equal the full-step
+gradients of the same tensors; Adam and LAMB one-step closed forms.  The paper
+prints no worked numerical example, so absolute values have no published pin.
+"""
+from __future__ import annotations
+
+import math
+import numpy as np
+
+LAYER_TENSORS = ("wq", "wk", "wv", "bq", "bk", "bv", "wo", "bo", "ln1_g", "ln1_b",
+                 "w1", "b1", "w2", "b2", "ln2_g", "ln2_b")
+EMB_TENSORS = ("emb.word", "emb.pos", "emb.type", "emb.ln_g", "emb.ln_b")
+HEAD_TENSORS = ("head.wt", "head.bt", "head.ln_g", "head.ln_b", "head.b_out")
+IGNORE_LABEL = -100
+
+
+class Ops:
+    """Matrix-product hook: numpy matmul (host BLAS) or a literal triple loop."""
+
+    def __init__(self, naive: bool = False):
+        self.naive = naive
+
+    def mm(self, a, b):
+        if not self.naive:
+            return a @ b
+        m, k = a.shape
+        k2, n = b.shape
+        assert k == k2
+        out = np.zeros((m, n), dtype=np.float64)
+        for i in range(m):
+            for j in range(n):
+                s = 0.0
+                for t in range(k):
+                    s += float(a[i, t]) * float(b[t, j])
+                out[i, j] = s
+        return out
+
+
+try:
+    from scipy.special import erf as _erf   # library erf, exact to float64 rounding
+except ImportError:  # pragma: no cover
+    _erf = np.vectorize(math.erf, otypes=[np.float64])
+
+
+def gelu(u):
+    """erf form: u * Phi(u)."""
+    return 0.5 * u * (1.0 + _erf(u / math.sqrt(2.0)))
+
+
+def gelu_grad(u):
+    """d/du [u Phi(u)] = Phi(u) + u phi(u)."""
+    cdf = 0.5 * (1.0 + _erf(u / math.sqrt(2.0)))
+    pdf = np.exp(-0.5 * u * u) / math.sqrt(2.0 * math.pi)
+    return cdf + u * pdf
+
+
+def layer_norm(z, g, b, eps):
+    """Row-wise LayerNorm with biased variance. Returns y and (xhat, rstd) for the backward."""
+    mu = z.mean(axis=-1, keepdims=True)
+    var = ((z - mu) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = (z - mu) * rstd
+    return xhat * g + b, (xhat, rstd)
+
+
+def layer_norm_backward(dy, g, cache):
+    xhat, rstd = cache
+    dg = (dy * xhat).sum(axis=0)
+    db = dy.sum(axis=0)
+    dxh = dy * g
+    dz = (dxh - dxh.mean(axis=-1, keepdims=True) - xhat * (dxh * xhat).mean(axis=-1, keepdims=True)) * rstd
+    return dz, dg, db
+
+
+def softmax_rows(a):
+    m = a.max(axis=-1, keepdims=True)
+    e = np.exp(a - m)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def to_f64(params):
+    return {k: np.asarray(v, dtype=np.float64) for k, v in params.items()}
+
+
+# ----------------------------------------------------------------------------------------------
+# forward
+# ----------------------------------------------------------------------------------------------
+def embed_forward(cfg, P, batch):
+    ids = np.asarray(batch["input_ids"]).reshape(-1)
+    tt = np.asarray(batch["token_type_ids"]).reshape(-1)
+    B, S = np.asarray(batch["input_ids"]).shape
+    pos = np.tile(np.arange(S), B)
+    z = P["emb.word"][ids] + P["emb.pos"][pos] + P["emb.type"][tt]
+    x0, ln = layer_norm(z, P["emb.ln_g"], P["emb.ln_b"], cfg.ln_eps)
+    return x0, {"ids": ids, "tt": tt, "pos": pos, "ln": ln}
+
+
+def layer_forward(cfg, P, i, X, key_bias, B, S, ops):
+    """One post-LN encoder layer. X is [T, H]; key_bias is [B, S] (0 for tokens, mask_bias for padding)."""
+    p = f"layer{i}."
+    H, nh = cfg.hidden, cfg.n_heads
+    dh = H // nh
+    Q = ops.mm(X, P[p + "wq"].T) + P[p + "bq"]
+    K = ops.mm(X, P[p + "wk"].T) + P[p + "bk"]
+    V = ops.mm(X, P[p + "wv"].T) + P[p + "bv"]
+    C = np.empty_like(X)
+    Pr = np.empty((B, nh, S, S), dtype=np.float64)
+    scale = 1.0 / math.sqrt(dh)
+    for b in range(B):
+        rows = slice(b * S, (b + 1) * S)
+        for h in range(nh):
+            cols = slice(h * dh, (h + 1) * dh)
+            A = ops.mm(Q[rows, cols], K[rows, cols].T) * scale + key_bias[b][None, :]
+            Pbh = softmax_rows(A)
+            Pr[b, h] = Pbh
+            C[rows, cols] = ops.mm(Pbh, V[rows, cols])
+    O = ops.mm(C, P[p + "wo"].T) + P[p + "bo"]
+    X1, ln1 = layer_norm(X + O, P[p + "ln1_g"], P[p + "ln1_b"], cfg.ln_eps)
+    U = ops.mm(X1, P[p + "w1"].T) + P[p + "b1"]
+    G = gelu(U)
+    D = ops.mm(G, P[p + "w2"].T) + P[p + "b2"]
+    X2, ln2 = layer_norm(X1 + D, P[p + "ln2_g"], P[p + "ln2_b"], cfg.ln_eps)
+    cache = {"X": X, "Q": Q, "K": K, "V": V, "P": Pr, "C": C, "ln1": ln1, "X1": X1, "U": U, "G": G, "ln2": ln2}
+    return X2, cache
+
+
+def masked_rows(batch):
+    """Ascending flat positions with a label, and the labels there (integer, unique)."""
+    lab = np.asarray(batch["labels"]).reshape(-1)
+    pos = np.flatnonzero(lab != IGNORE_LABEL)
+    return pos.astype(np.int64), lab[pos].astype(np.int64)
+
+
+def head_forward(cfg, P, XL, pos, Y, ops):
+    Xm = XL[pos]
+    Ut = ops.mm(Xm, P["head.wt"].T) + P["head.bt"]
+    Gt = gelu(Ut)
+    Hm, ln = layer_norm(Gt, P["head.ln_g"], P["head.ln_b"], cfg.ln_eps)
+    Z = ops.mm(Hm, P["emb.word"].T) + P["head.b_out"]
+    zmax = Z.max(axis=-1, keepdims=True)
+    lse = (zmax + np.log(np.exp(Z - zmax).sum(axis=-1, keepdims=True)))[:, 0]
+    M = len(pos)
+    losses = lse - Z[np.arange(M), Y]
+    loss = losses.sum() / M
+    return loss, {"Xm": Xm, "Ut": Ut, "Gt": Gt, "Hm": Hm, "ln": ln, "Z": Z, "lse": lse, "pos": pos, "Y": Y}
+
+
+def forward(cfg, params, batch, n_layers=None, ops=None, keep_from=0, prefix_at=None):
+    """Forward through the embedding block, layers 0..n_layers-1 and the masked-LM head.
+
+    Layer caches below `keep_from` are dropped (those layers run forward only).
+    `prefix_out` in the returned cache is the input of layer `prefix_at` (default keep_from),
+    i.e. the output of the frozen prefix.
+    """
+    ops = ops or Ops()
+    P = to_f64(params)
+    n_layers = cfg.n_layers if n_layers is None else n_layers
+    prefix_at = keep_from if prefix_at is None else prefix_at
+    ids = np.asarray(batch["input_ids"])
+    B, S = ids.shape
+    key_bias = (1.0 - np.asarray(batch["attn_mask"], dtype=np.float64)) * cfg.mask_bias
+    X, emb_cache = embed_forward(cfg, P, batch)
+    layer_caches = [None] * n_layers
+    prefix_out = None
+    for i in range(n_layers):
+        if i == prefix_at:
+            prefix_out = X
+        X, c = layer_forward(cfg, P, i, X, key_bias, B, S, ops)
+        if i >= keep_from:
+            layer_caches[i] = c
+    pos, Y = masked_rows(batch)
+    if len(pos) == 0:
+        raise ValueError("batch has no predicted position")
+    loss, head_cache = head_forward(cfg, P, X, pos, Y, ops)
+    cache = {"P64": P, "B": B, "S": S, "T": B * S, "n_layers": n_layers, "emb": emb_cache, "layers": layer_caches,
+             "head": head_cache, "XL": X, "prefix_out": prefix_out, "keep_from": keep_from}
+    return loss, cache
+
+
+# ----------------------------------------------------------------------------------------------
+# backward
+# ----------------------------------------------------------------------------------------------
+def head_backward(cfg, P, hc, T, ops):
+    M = len(hc["pos"])
+    Z = hc["Z"]
+    dZ = np.exp(Z - hc["lse"][:, None])
+    dZ[np.arange(M), hc["Y"]] -= 1.0
+    dZ /= M
+    g = {}
+    g["head.b_out"] = dZ.sum(axis=0)
+    g_word_head = ops.mm(dZ.T, hc["Hm"])          # contribution to the tied word matrix
+    dHm = ops.mm(dZ, P["emb.word"])
+    dGt, g["head.ln_g"], g["head.ln_b"] = layer_norm_backward(dHm, P["head.ln_g"], hc["ln"])
+    dUt = dGt * gelu_grad(hc["Ut"])
+    g["head.wt"] = ops.mm(dUt.T, hc["Xm"])
+    g["head.bt"] = dUt.sum(axis=0)
+    dXm = ops.mm(dUt, P["head.wt"])
+    dXL = np.zeros((T, cfg.hidden), dtype=np.float64)
+    dXL[hc["pos"]] = dXm
+    return dXL, g, g_word_head, dZ
+
+
+def layer_backward(cfg, P, i, c, dX2, B, S, ops):
+    p = f"layer{i}."
+    H, nh = cfg.hidden, cfg.n_heads
+    dh = H // nh
+    scale = 1.0 / math.sqrt(dh)
+    g = {}
+    dZ2, g[p + "ln2_g"], g[p + "ln2_b"] = layer_norm_backward(dX2, P[p + "ln2_g"], c["ln2"])
+    dD = dZ2
+    g[p + "w2"] = ops.mm(dD.T, c["G"])
+    g[p + "b2"] = dD.sum(axis=0)
+    dG = ops.mm(dD, P[p + "w2"])
+    dU = dG * gelu_grad(c["U"])
+    g[p + "w1"] = ops.mm(dU.T, c["X1"])
+    g[p + "b1"] = dU.sum(axis=0)
+    dX1 = ops.mm(dU, P[p + "w1"]) + dZ2
+    dZ1, g[p + "ln1_g"], g[p + "ln1_b"] = layer_norm_backward(dX1, P[p + "ln1_g"], c["ln1"])
+    dO = dZ1
+    g[p + "wo"] = ops.mm(dO.T, c["C"])
+    g[p + "bo"] = dO.sum(axis=0)
+    dC = ops.mm(dO, P[p + "wo"])
+    dQ = np.empty_like(dC)
+    dK = np.empty_like(dC)
+    dV = np.empty_like(dC)
+    for b in range(B):
+        rows = slice(b * S, (b + 1) * S)
+        for h in range(nh):
+            cols = slice(h * dh, (h + 1) * dh)
+            Pbh = c["P"][b, h]
+            dCbh = dC[rows, cols]
+            dV[rows, cols] = ops.mm(Pbh.T, dCbh)
+            dP = ops.mm(dCbh, c["V"][rows, cols].T)
+            dA = Pbh * (dP - (dP * Pbh).sum(axis=-1, keepdims=True))
+            dQ[rows, cols] = ops.mm(dA, c["K"][rows, cols]) * scale
+            dK[rows, cols] = ops.mm(dA.T, c["Q"][rows, cols]) * scale
+    X = c["X"]
+    for nm, dY in (("q", dQ), ("k", dK), ("v", dV)):
+        g[p + "w" + nm] = ops.mm(dY.T, X)
+        g[p + "b" + nm] = dY.sum(axis=0)
+    dX = ops.mm(dQ, P[p + "wq"]) + ops.mm(dK, P[p + "wk"]) + ops.mm(dV, P[p + "wv"]) + dZ1
+    return dX, g
+
+
+def embed_backward(cfg, P, ec, dX0):
+    g = {}
+    dz, g["emb.ln_g"], g["emb.ln_b"] = layer_norm_backward(dX0, P["emb.ln_g"], ec["ln"])
+    gw = np.zeros_like(P["emb.word"])
+    gp = np.zeros_like(P["emb.pos"])
+    gt = np.zeros_like(P["emb.type"])
+    np.add.at(gw, ec["ids"], dz)
+    np.add.at(gp, ec["pos"], dz)
+    np.add.at(gt, ec["tt"], dz)
+    g["emb.pos"], g["emb.type"] = gp, gt
+    return g, gw
+
+
+def backward(cfg, cache, ops=None, stop_layer=0, with_embeddings=True):
+    """Reverse-mode gradients of the loss for layers >= stop_layer, the head and (optionally) the embeddings."""
+    ops = ops or Ops()
+    P = cache["P64"]
+    B, S, T = cache["B"], cache["S"], cache["T"]
+    dX, grads, g_word_head, _ = head_backward(cfg, P, cache["head"], T, ops)
+    for i in range(cache["n_layers"] - 1, stop_layer - 1, -1):
+        dX, g = layer_backward(cfg, P, i, cache["layers"][i], dX, B, S, ops)
+        grads.update(g)
+    if with_embeddings:
+        assert stop_layer == 0
+        ge, gw_in = embed_backward(cfg, P, cache["emb"], dX)
+        grads.update(ge)
+        grads["emb.word"] = gw_in + g_word_head   # tied matrix: input gather + output projection
+    return grads
+
+
+def stage_tensor_names(frozen_layers, trainable_layers, train_embeddings):
+    names = list(EMB_TENSORS) if train_embeddings else []
+    for i in range(frozen_layers, frozen_layers + trainable_layers):
+        names += [f"layer{i}.{t}" for t in LAYER_TENSORS]
+    names += list(HEAD_TENSORS)
+    return names
+
+
+def stage_step(cfg, params, batch, frozen_layers, trainable_layers, train_embeddings=False, ops=None,
+               full_backprop=False):
+    """Loss and gradients of one MSLT stage step (Section 3.2).
+
+    Layers [0, frozen) run forward only; layers [frozen, frozen+trainable) and the
+    output layer get gradients; the embedding block (with the tied word matrix) gets
+    gradients only when `train_embeddings` (first stage, retraining).  With
+    full_backprop the backward runs through every layer and the trainable slice is
+    taken afterwards, which is the plain definition; without it the backward stops at
+    the lowest trainable layer, which by the chain rule yields the same slice.
+    """
+    if trainable_layers < 1 or frozen_layers < 0 or frozen_layers + trainable_layers > cfg.n_layers:
+        raise ValueError("bad layer split")
+    if train_embeddings and frozen_layers != 0:
+        raise ValueError("embeddings train only when nothing is frozen")
+    n = frozen_layers + trainable_layers
+    keep_from = 0 if full_backprop else frozen_layers
+    loss, cache = forward(cfg, params, batch, n_layers=n, ops=ops, keep_from=keep_from, prefix_at=frozen_layers)
+    if full_backprop:
+        g_all = backward(cfg, cache, ops=ops, stop_layer=0, with_embeddings=True)
+    else:
+        g_all = backward(cfg, cache, ops=ops, stop_layer=frozen_layers, with_embeddings=train_embeddings)
+    names = stage_tensor_names(frozen_layers, trainable_layers, train_embeddings)
+    grads = {k: g_all[k] for k in names}
+    info = {"pos": cache["head"]["pos"], "labels": cache["head"]["Y"], "prefix_out": cache["prefix_out"],
+            "XL": cache["XL"], "cache": cache}
+    return loss, grads, info
+
+
+# ----------------------------------------------------------------------------------------------
+# optimizers (textbook Adam with decoupled weight decay; LAMB = same direction scaled per tensor)
+# ----------------------------------------------------------------------------------------------
+def decays(name: str) -> bool:
+    """Weight decay applies to matrices and embedding tables, not to biases or LayerNorm parameters."""
+    leaf = name.split(".")[-1]
+    return leaf in ("word", "pos", "type", "wq", "wk", "wv", "wo", "w1", "w2", "wt")
+
+
+def new_opt_state(params):
+    return {k: {"m": np.zeros_like(np.asarray(v, dtype=np.float64)),
+                "v": np.zeros_like(np.asarray(v, dtype=np.float64)), "t": 0} for k, v in params.items()}
+
+
+def optimizer_update(params, grads, state, kind="adam", lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-6,
+                     weight_decay=0.01, bias_correction=True):
+    """Update exactly the tensors in `grads`; every other tensor and its state stay untouched.
+
+    m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;  mhat, vhat bias-corrected with the
+    tensor's own step count;  u = mhat / (sqrt(vhat) + eps) + wd * w.
+    Adam: w -= lr u.   LAMB: w -= lr * (|w| / |u|) u, ratio 1 if either norm is 0.
+    Returns new float64 params dict (inputs are not modified) and per-tensor trust ratios.
+    """
+    out = {k: np.array(v, dtype=np.float64, copy=True) for k, v in params.items()}
+    ratios = {}
+    for name, g in grads.items():
+        st = state[name]
+        g = np.asarray(g, dtype=np.float64)
+        w = out[name]
+        st["t"] += 1
+        t = st["t"]
+        st["m"] = beta1 * st["m"] + (1.0 - beta1) * g
+        st["v"] = beta2 * st["v"] + (1.0 - beta2) * g * g
+        if bias_correction:
+            mhat = st["m"] / (1.0 - beta1 ** t)
+            vhat = st["v"] / (1.0 - beta2 ** t)
+        else:
+            mhat, vhat = st["m"], st["v"]
+        u = mhat / (np.sqrt(vhat) + eps)
+        if decays(name) and weight_decay != 0.0:
+            u = u + weight_decay * w
+        r = 1.0
+        if kind == "lamb":
+            wn = math.sqrt(float((w * w).sum()))
+            un = math.sqrt(float((u * u).sum()))
+            r = wn / un if (wn > 0.0 and un > 0.0) else 1.0
+        elif kind != "adam":
+            raise ValueError(kind)
+        ratios[name] = r
+        out[name] = w - lr * r * u
+    return out, ratios
+
+
+def grow(params, n_present, n_new):
+    """Stack growth (Section 3.2): new layer n_present+i is a copy of layer n_present-n_new+i."""
+    out = dict(params)
+    for i in range(n_new):
+        for t in LAYER_TENSORS:
+            out[f"layer{n_present + i}.{t}"] = np.array(params[f"layer{n_present - n_new + i}.{t}"], copy=True)
+    return out
