@@ -1,0 +1,170 @@
+/*
+ * mslt.h -- C ABI of the MSLT stage-step library for AMD MI355X (gfx950).
+ *
+ * One training step of a stage of Multi-Stage Layerwise Training (paper Section 3.2):
+ * the bottom `frozen_layers` encoder layers of a BERT stack, trained in earlier stages, run
+ * forward only and keep no intermediates; the `trainable_layers` layers above them and the
+ * output layer (masked-LM head) run forward and backward and are the only tensors that get
+ * gradients and an optimizer update (Section 3.1, last paragraph; Figure 1).  The embedding
+ * block with the word matrix shared between input and output is trained only when nothing is
+ * frozen -- the first stage and the final joint retraining (Section 3.2).
+ *
+ * Conventions
+ *   - Every function returns 0 on success and a negative mslt_status on error; the message of
+ *     the last error of the calling thread is available from mslt_last_error().  A call that
+ *     fails validation enqueues no GPU work and leaves every arena untouched.
+ *   - The library never allocates or frees device memory.  The caller (normally PyTorch) owns
+ *     four device arenas whose sizes mslt_query_sizes() reports, and a HIP stream; all GPU work
+ *     is enqueued on that stream.  Host memory passed in is read or written before the call
+ *     returns.  "DEVICE" / "HOST" below say where a pointer must live.
+ *   - Weight matrices are [out, in] row-major fp32 in the canonical tensor order reported by
+ *     mslt_tensor_table(): embedding block, encoder layers bottom to top, head.
+ *   - precision 0: fp32 storage and arithmetic everywhere.  precision 1: bf16 activations and
+ *     bf16 shadow copies of the weight matrices feeding MFMA, fp32 accumulation, fp32 softmax /
+ *     LayerNorm / GELU / cross-entropy internals, fp32 gradients, master weights and optimizer
+ *     state.
+ *   - Calls on one model must not overlap; they are not thread-safe.
+ */
+#ifndef MSLT_H
+#define MSLT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mslt_model mslt_model; /* opaque host object; owns no device memory */
+
+enum mslt_status {
+  MSLT_OK = 0,
+  MSLT_ERR_ARG = -1,      /* null pointer, bad shape, bad layer split, size mismatch */
+  MSLT_ERR_STATE = -2,    /* call order: update / get_grads without a successful step */
+  MSLT_ERR_DATA = -3,     /* batch content: id out of range, no predicted position, too many */
+  MSLT_ERR_HIP = -4,      /* a HIP runtime call failed */
+  MSLT_ERR_NONFINITE = -5 /* the step ran but the loss is not finite */
+};
+
+typedef struct {
+  int n_layers_max;    /* encoder layers the arenas hold (12 Base, 24 Large: Section 4.1) */
+  int hidden;          /* H; multiple of 4, at most 2048 */
+  int n_heads;         /* H / n_heads = head width, at most 128 */
+  int ffn;             /* F */
+  int vocab;           /* V */
+  int max_pos;         /* rows of the position table; seq <= max_pos */
+  int type_vocab;      /* rows of the token-type table */
+  int max_batch;       /* largest batch a step may bring */
+  int max_seq;         /* largest sequence length a step may bring */
+  int max_predictions; /* largest number of predicted positions per step; 0 = max_batch*max_seq */
+  int precision;       /* 0 fp32, 1 bf16 compute with fp32 master */
+  float ln_eps;        /* LayerNorm epsilon (1e-12) */
+  float mask_bias;     /* added to the scores of padded keys (-10000) */
+} mslt_config;
+
+/* One masked-LM batch.  DEVICE pointers to int32 arrays of batch*seq entries, row-major
+ * [batch][seq], owned by the caller and valid until the step's stream work has finished.
+ * attn_mask: 1 token, 0 padding.  labels: original id at predicted positions, -100 elsewhere. */
+typedef struct {
+  const int32_t* input_ids;
+  const int32_t* token_type_ids;
+  const int32_t* attn_mask;
+  const int32_t* labels;
+  int batch;
+  int seq;
+} mslt_batch;
+
+/* Optimizer of the update (Section 4.1: LAMB, lr 0.00088; Section 5 also names Adam).
+ * u = mhat/(sqrt(vhat)+eps) + weight_decay*w (decay on matrices and embedding tables only).
+ * kind 0 Adam: w -= lr*u.  kind 1 LAMB: w -= lr*(|w|/|u|)*u per logical tensor (ratio 1 if a
+ * norm is 0).  bias_correction != 0 divides m, v by (1-beta^t), t counted per tensor. */
+typedef struct {
+  int kind;
+  float lr, beta1, beta2, eps, weight_decay;
+  int bias_correction;
+} mslt_opt;
+
+typedef struct {
+  char name[32];  /* "emb.word", "layer3.wq", "head.b_out", ... */
+  int layer;      /* encoder layer index, -1 embedding block, -2 head */
+  int rows, cols; /* logical shape; cols = 1 for vectors */
+  int decays;     /* 1 if weight decay applies */
+  size_t offset;  /* element offset inside the parameter / gradient / moment arenas */
+  size_t count;   /* rows*cols */
+} mslt_tensor_desc;
+
+/* Arena sizes in bytes for a configuration.  param_bytes: fp32 master weights.  grad_bytes:
+ * fp32 gradients (same offsets).  opt_state_bytes: first and second moments.  workspace_bytes:
+ * bf16 shadows, activations, the stash of the trainable layers, head buffers, reduction scratch.
+ * HOST pointers; any may be null. */
+int mslt_query_sizes(const mslt_config* cfg, size_t* param_bytes, size_t* grad_bytes, size_t* opt_state_bytes,
+                     size_t* workspace_bytes);
+
+/* Creates a model over caller-owned DEVICE arenas (each at least the queried size, 256-byte
+ * aligned) and a HIP stream (hipStream_t passed as void*, null = default stream).  Zero-fills all
+ * four arenas on the stream: parameters and optimizer state start at zero, step counts at 0.
+ * *out is a HOST object to be released with mslt_destroy(). */
+int mslt_init_model(const mslt_config* cfg, void* param_arena, void* grad_arena, void* opt_arena, void* workspace,
+                    void* hip_stream, mslt_model** out);
+
+/* Canonical tensor list.  *out points to an array of *n descriptors owned by the model. */
+int mslt_tensor_table(const mslt_model* m, int* n, const mslt_tensor_desc** out);
+
+/* Loads all parameters from a packed HOST fp32 array in canonical order (n_floats = sum of
+ * counts) and rebuilds the bf16 shadows.  Blocks until the copy is done. */
+int mslt_load_params(mslt_model* m, const float* host_fp32, size_t n_floats);
+
+/* Reads all parameters back into a packed HOST fp32 array in canonical order.  Blocks. */
+int mslt_get_params(const mslt_model* m, float* host_fp32_out, size_t n_floats);
+
+/* One stage step (Section 3.2): forward through layers [0, frozen+trainable), masked-LM loss,
+ * backward through the head and the top `trainable_layers` layers only.  Layers above
+ * frozen+trainable are not executed (the stack of an earlier stage is shallower).
+ * Requirements: trainable_layers >= 1, frozen_layers >= 0, frozen+trainable <= n_layers_max,
+ * train_embeddings may be 1 only if frozen_layers == 0, batch <= max_batch, seq <= max_seq,
+ * at least one and at most max_predictions predicted positions, ids inside their tables
+ * (checked on the device before any other work; violations return MSLT_ERR_DATA).
+ * Gradients of exactly the trainable tensors are left in the gradient arena.  *loss_out (HOST)
+ * receives the mean loss over predicted positions; the call waits for the stream for this. */
+int mslt_stage_step(mslt_model* m, int frozen_layers, int trainable_layers, int train_embeddings,
+                    const mslt_batch* batch, float* loss_out);
+
+/* Number of floats mslt_get_grads() will write for the last successful step. */
+int mslt_grad_count(const mslt_model* m, size_t* n_floats);
+
+/* Gradients of the last step's trainable tensors, packed in canonical order, to HOST. Blocks. */
+int mslt_get_grads(const mslt_model* m, float* host_fp32_out, size_t n_floats);
+
+/* Applies the optimizer to exactly the tensors that received gradients in the last step
+ * (Section 3.2: only the new top layers and the output layer are updated; everything is updated
+ * in the first stage and in retraining) and refreshes their bf16 shadows.  Frozen tensors, their
+ * moments and step counts are not touched.  Enqueues work only; does not block.  A second call
+ * without a new step is an error. */
+int mslt_apply_update(mslt_model* m, const mslt_opt* opt);
+
+/* Predicted positions (ascending flat index b*seq+s) and their labels as found by the last
+ * step, to HOST arrays of at least max_predictions entries; *m_out = their number.  Blocks. */
+int mslt_debug_masked(const mslt_model* m, int32_t* pos_out, int32_t* label_out, int* m_out);
+
+/* Output of the frozen prefix of the last step (the input of the lowest trainable layer;
+ * the embedding output if nothing was frozen), batch*seq*hidden values widened to fp32, to
+ * HOST.  Blocks.  Valid until the next step. */
+int mslt_debug_prefix_output(const mslt_model* m, float* host_fp32_out, size_t n_floats);
+
+/* Stack growth between stages (Section 3.2): layer n_present+i becomes a copy of layer
+ * n_present-n_new+i, i = 0..n_new-1 (parameters and shadows); the new layers' moments are
+ * zeroed and their step counts reset.  Enqueues work only. */
+int mslt_grow(mslt_model* m, int n_present, int n_new);
+
+/* Waits until all work enqueued on the model's stream has finished. */
+int mslt_sync(const mslt_model* m);
+
+int mslt_destroy(mslt_model* m);
+
+/* Message of the calling thread's last error ("" if none). */
+const char* mslt_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSLT_H */

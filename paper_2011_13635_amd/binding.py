@@ -1,0 +1,214 @@
+"""ctypes binding of libmslt.so: same names as include/mslt.h, argument marshalling only.
+
+PyTorch is used for device memory (the four arenas, the batch tensors) and the stream.
+Every step of the path runs inside the library's HIP kernels; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmslt.so")
+
+EXPORTS = [
+    "mslt_query_sizes", "mslt_init_model", "mslt_tensor_table", "mslt_load_params", "mslt_get_params",
+    "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_debug_masked",
+    "mslt_debug_prefix_output", "mslt_grow", "mslt_sync", "mslt_destroy", "mslt_last_error",
+]
+
+MSLT_OK, MSLT_ERR_ARG, MSLT_ERR_STATE, MSLT_ERR_DATA, MSLT_ERR_HIP, MSLT_ERR_NONFINITE = 0, -1, -2, -3, -4, -5
+
+
+class MsltError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"mslt error {code}: {msg}")
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers_max", C.c_int), ("hidden", C.c_int), ("n_heads", C.c_int), ("ffn", C.c_int),
+                ("vocab", C.c_int), ("max_pos", C.c_int), ("type_vocab", C.c_int), ("max_batch", C.c_int),
+                ("max_seq", C.c_int), ("max_predictions", C.c_int), ("precision", C.c_int),
+                ("ln_eps", C.c_float), ("mask_bias", C.c_float)]
+
+
+class Batch(C.Structure):
+    _fields_ = [("input_ids", C.c_void_p), ("token_type_ids", C.c_void_p), ("attn_mask", C.c_void_p),
+                ("labels", C.c_void_p), ("batch", C.c_int), ("seq", C.c_int)]
+
+
+class Opt(C.Structure):
+    _fields_ = [("kind", C.c_int), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("bias_correction", C.c_int)]
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("layer", C.c_int), ("rows", C.c_int), ("cols", C.c_int),
+                ("decays", C.c_int), ("offset", C.c_size_t), ("count", C.c_size_t)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2011_13635_amd.build)")
+    lib = C.CDLL(LIB_PATH)
+    vp, sz = C.c_void_p, C.c_size_t
+    P = C.POINTER
+    lib.mslt_query_sizes.argtypes = [P(Config), P(sz), P(sz), P(sz), P(sz)]
+    lib.mslt_init_model.argtypes = [P(Config), vp, vp, vp, vp, vp, P(vp)]
+    lib.mslt_tensor_table.argtypes = [vp, P(C.c_int), P(P(TensorDesc))]
+    lib.mslt_load_params.argtypes = [vp, vp, sz]
+    lib.mslt_get_params.argtypes = [vp, vp, sz]
+    lib.mslt_stage_step.argtypes = [vp, C.c_int, C.c_int, C.c_int, P(Batch), P(C.c_float)]
+    lib.mslt_grad_count.argtypes = [vp, P(sz)]
+    lib.mslt_get_grads.argtypes = [vp, vp, sz]
+    lib.mslt_apply_update.argtypes = [vp, P(Opt)]
+    lib.mslt_debug_masked.argtypes = [vp, vp, vp, P(C.c_int)]
+    lib.mslt_debug_prefix_output.argtypes = [vp, vp, sz]
+    lib.mslt_grow.argtypes = [vp, C.c_int, C.c_int]
+    lib.mslt_sync.argtypes = [vp]
+    lib.mslt_destroy.argtypes = [vp]
+    lib.mslt_last_error.argtypes = []
+    lib.mslt_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        if name != "mslt_last_error":
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc, allow=()):
+    if rc != 0 and rc not in allow:
+        raise MsltError(rc, load_library().mslt_last_error().decode())
+    return rc
+
+
+def make_config(shape, max_batch, max_seq, precision, max_predictions=0) -> Config:
+    """Config from a synth.ModelShape-like object (n_layers, hidden, n_heads, ffn, vocab, ...)."""
+    return Config(shape.n_layers, shape.hidden, shape.n_heads, shape.ffn, shape.vocab, shape.max_pos,
+                  shape.type_vocab, max_batch, max_seq, max_predictions, precision, shape.ln_eps, shape.mask_bias)
+
+
+def mslt_query_sizes(cfg: Config):
+    a, b, c, d = C.c_size_t(), C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(load_library().mslt_query_sizes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
+    return a.value, b.value, c.value, d.value
+
+
+def adam(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-6, weight_decay=0.01, bias_correction=True) -> Opt:
+    return Opt(0, lr, beta1, beta2, eps, weight_decay, int(bias_correction))
+
+
+def lamb(lr=0.00088, beta1=0.9, beta2=0.999, eps=1e-6, weight_decay=0.01, bias_correction=True) -> Opt:
+    return Opt(1, lr, beta1, beta2, eps, weight_decay, int(bias_correction))
+
+
+class Model:
+    """Owns the torch device arenas and the opaque model handle.  Methods mirror the C calls."""
+
+    def __init__(self, cfg: Config, device="cuda:0", stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the MSLT library has no CPU path")
+        self.lib = load_library()
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        sizes = mslt_query_sizes(cfg)
+        self.sizes = sizes
+        with torch.cuda.device(self.device):
+            self.arenas = [torch.empty(max(s, 256), dtype=torch.uint8, device=self.device) for s in sizes]
+            self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        h = C.c_void_p()
+        _check(self.lib.mslt_init_model(C.byref(cfg), *[C.c_void_p(a.data_ptr()) for a in self.arenas],
+                                        C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+        self.handle = h
+        self._batch_keep = None
+        n = C.c_int()
+        tab = C.POINTER(TensorDesc)()
+        _check(self.lib.mslt_tensor_table(self.handle, C.byref(n), C.byref(tab)))
+        self.table = [(tab[i].name.decode(), tab[i].layer, tab[i].rows, tab[i].cols, tab[i].decays, tab[i].offset,
+                       tab[i].count) for i in range(n.value)]
+        self.packed_count = sum(t[6] for t in self.table)
+
+    # -- parameters
+    def mslt_load_params(self, flat: np.ndarray):
+        flat = np.ascontiguousarray(flat, dtype=np.float32)
+        _check(self.lib.mslt_load_params(self.handle, flat.ctypes.data_as(C.c_void_p), flat.size))
+
+    def mslt_get_params(self) -> np.ndarray:
+        out = np.empty(self.packed_count, dtype=np.float32)
+        _check(self.lib.mslt_get_params(self.handle, out.ctypes.data_as(C.c_void_p), out.size))
+        return out
+
+    # -- batches
+    def device_batch(self, batch) -> Batch:
+        """Copies a host batch (dict of int arrays [B,S]) to the device; returns the C struct."""
+        torch = self.torch
+        B, S = batch["input_ids"].shape
+        keep = [torch.as_tensor(np.ascontiguousarray(batch[k], dtype=np.int32)).to(self.device)
+                for k in ("input_ids", "token_type_ids", "attn_mask", "labels")]
+        torch.cuda.synchronize(self.device)
+        cb = Batch(*[C.c_void_p(t.data_ptr()) for t in keep], B, S)
+        cb._keep = keep   # keep the tensors alive as long as the struct
+        return cb
+
+    # -- the step
+    def mslt_stage_step(self, frozen_layers, trainable_layers, train_embeddings, cbatch: Batch, allow=()):
+        loss = C.c_float()
+        rc = _check(self.lib.mslt_stage_step(self.handle, frozen_layers, trainable_layers, int(train_embeddings),
+                                             C.byref(cbatch), C.byref(loss)), allow)
+        return loss.value if rc == 0 else rc
+
+    def mslt_grad_count(self) -> int:
+        n = C.c_size_t()
+        _check(self.lib.mslt_grad_count(self.handle, C.byref(n)))
+        return n.value
+
+    def mslt_get_grads(self) -> np.ndarray:
+        out = np.empty(self.mslt_grad_count(), dtype=np.float32)
+        _check(self.lib.mslt_get_grads(self.handle, out.ctypes.data_as(C.c_void_p), out.size))
+        return out
+
+    def mslt_apply_update(self, opt: Opt):
+        _check(self.lib.mslt_apply_update(self.handle, C.byref(opt)))
+
+    def mslt_debug_masked(self):
+        cap = self.cfg.max_predictions or self.cfg.max_batch * self.cfg.max_seq
+        pos = np.empty(cap, dtype=np.int32)
+        lab = np.empty(cap, dtype=np.int32)
+        m = C.c_int()
+        _check(self.lib.mslt_debug_masked(self.handle, pos.ctypes.data_as(C.c_void_p), lab.ctypes.data_as(C.c_void_p),
+                                          C.byref(m)))
+        return pos[:m.value].copy(), lab[:m.value].copy()
+
+    def mslt_debug_prefix_output(self, batch, seq) -> np.ndarray:
+        out = np.empty(batch * seq * self.cfg.hidden, dtype=np.float32)
+        _check(self.lib.mslt_debug_prefix_output(self.handle, out.ctypes.data_as(C.c_void_p), out.size))
+        return out.reshape(batch * seq, self.cfg.hidden)
+
+    def mslt_grow(self, n_present, n_new):
+        _check(self.lib.mslt_grow(self.handle, n_present, n_new))
+
+    def mslt_sync(self):
+        _check(self.lib.mslt_sync(self.handle))
+
+    def close(self):
+        if self.handle:
+            self.lib.mslt_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,190 @@
+// Shared device helpers and the launcher interface between the kernel files and the host logic.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace mslt {
+
+// ---- bf16 storage type with round-to-nearest-even conversion -------------------------------
+struct bf16 {
+  uint16_t x;
+};
+
+__host__ __device__ inline float bf2f(bf16 v) {
+  union { uint32_t u; float f; } c;
+  c.u = ((uint32_t)v.x) << 16;
+  return c.f;
+}
+__host__ __device__ inline bf16 f2bf(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  bf16 r;
+  if ((u & 0x7fffffffu) > 0x7f800000u) {  // NaN stays NaN
+    r.x = (uint16_t)((u >> 16) | 0x40);
+    return r;
+  }
+  u += 0x7fffu + ((u >> 16) & 1u);
+  r.x = (uint16_t)(u >> 16);
+  return r;
+}
+
+__device__ inline float ldf(const float* p) { return *p; }
+__device__ inline float ldf(const bf16* p) { return bf2f(*p); }
+__device__ inline void stf(float* p, float v) { *p = v; }
+__device__ inline void stf(bf16* p, float v) { *p = f2bf(v); }
+
+// ---- wavefront (64 lanes) reductions --------------------------------------------------------
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// erf-form GELU and its derivative, fp32
+__device__ inline float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
+__device__ inline float gelu_grad_f(float u) {
+  float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752440f));
+  float pdf = 0.39894228040143267794f * __expf(-0.5f * u * u);
+  return cdf + u * pdf;
+}
+
+// ---- GEMM interface -------------------------------------------------------------------------
+// C(m,n) = sum_k A(m,k) * B(n,k), fp32 accumulation, followed by an epilogue.
+// Each operand has unit stride along exactly one of its two indices:
+//   a_kcontig: A(m,k) = A[m*lda + k]   else A(m,k) = A[k*lda + m]   (same for B with n)
+enum EpiAct { EPI_NONE = 0, EPI_GELU = 1, EPI_MUL_GELU_GRAD = 2, EPI_ADD = 3 };
+
+struct Epilogue {
+  void* out = nullptr;      // [M, ldo]; element type: float if out_f32 else the activation type
+  int ldo = 0;
+  int out_f32 = 0;
+  const float* bias = nullptr;  // per column n, or null
+  int act = EPI_NONE;
+  void* out2 = nullptr;     // EPI_GELU: pre-activation values (activation type), may be null
+  const void* aux = nullptr;  // EPI_MUL_GELU_GRAD: pre-activation U[m,n]; EPI_ADD: addend R[m,n]
+  int ldaux = 0;
+};
+
+struct GemmDesc {
+  const void* A = nullptr;
+  const void* B = nullptr;
+  int M = 0, N = 0, K = 0;
+  int lda = 0, ldb = 0;
+  int a_kcontig = 1, b_kcontig = 1;
+  Epilogue epi;
+};
+
+// dtype: 0 = float operands, 1 = bf16 operands.
+// Guarded SIMT kernel: any shape, any leading dimension.
+hipError_t gemm_simt(int dtype, const GemmDesc& d, hipStream_t s);
+// MFMA kernel (bf16 only): M, N multiples of 128, K multiple of 64 (per split), all loads in
+// bounds by construction (padded buffers).  splitk > 1 writes fp32 partials to `partials`
+// ([splitk][M][N]) and reduces them in fixed order into the epilogue.
+bool gemm_mfma_supported(const GemmDesc& d);
+hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s);
+
+// ---- attention ------------------------------------------------------------------------------
+struct AttnDesc {
+  const void* qkv;    // [T, 3H] rows = tokens: Q | K | V, head h at columns h*dh
+  void* ctx;          // [T, H]
+  float* lse;         // [B, nh, S] natural log-sum-exp of the masked scaled scores, or null
+  const int32_t* attn_mask;  // [B, S]
+  int B, S, nh, dh;
+  float mask_bias;
+};
+struct AttnBwdDesc {
+  const void* qkv;
+  const void* ctx;
+  const void* dctx;   // [T, H]
+  const float* lse;
+  float* delta;       // scratch [B, nh, S]
+  void* dqkv;         // [T, 3H]
+  const int32_t* attn_mask;
+  int B, S, nh, dh;
+  float mask_bias;
+};
+hipError_t attention_fwd_simple(int dtype, const AttnDesc& d, hipStream_t s);
+hipError_t attention_bwd_simple(int dtype, const AttnBwdDesc& d, hipStream_t s);
+bool attention_mfma_supported(int S, int dh);
+hipError_t attention_fwd_mfma(const AttnDesc& d, hipStream_t s);
+hipError_t attention_bwd_mfma(const AttnBwdDesc& d, hipStream_t s);
+
+// ---- row-wise and element-wise kernels ------------------------------------------------------
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t cast_f32_to_bf16(const float* src, bf16* dst, size_t n, hipStream_t s);
+hipError_t widen_to_f32(int dtype, const void* src, float* dst, size_t n, hipStream_t s);
+
+// checks the batch and compacts predicted positions.  counters[0] = M, counters[1] = error bits
+// (1 id range, 2 type range, 4 label range, 8 mask value).  inv[t] = j if t is the j-th predicted
+// position else -1.
+// pos/lab hold at most `cap` entries; counters[0] still reports the true count.
+hipError_t batch_scan(const int32_t* ids, const int32_t* tt, const int32_t* am, const int32_t* labels, int T, int vocab,
+                      int type_vocab, int cap, int32_t* pos, int32_t* lab, int32_t* inv, int32_t* counters,
+                      hipStream_t s);
+
+struct LnStash {
+  void* xhat = nullptr;   // [rows, H] activation type, or null
+  float* rstd = nullptr;  // [rows] or null
+};
+hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S, const float* word, const float* pos,
+                        const float* type, const float* g, const float* b, float eps, void* out, LnStash st, int T,
+                        int H, hipStream_t s);
+// out = LN(a + r) (r may be null)
+hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, const float* b, float eps, void* out,
+                      LnStash st, int rows, int H, hipStream_t s);
+// dz from dy, xhat, rstd, gamma; dgamma/dbeta via partials (scratch holds 2*ceil(rows/32)*H floats)
+hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
+                  float* db, float* scratch, int rows, int H, hipStream_t s);
+// column sums of Y[rows, N] (leading dimension ld) into out[N]; scratch holds ceil(rows/64)*N floats
+hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s);
+size_t colsum_scratch_floats(int rows, int N);
+size_t ln_bwd_scratch_floats(int rows, int H);
+
+hipError_t mul_gelu_grad(int dtype, const void* dg, const void* u, void* du, size_t n, hipStream_t s);
+hipError_t gather_rows(int dtype, const void* x, const int32_t* pos, int M, int Mpad, int H, void* out, hipStream_t s);
+hipError_t scatter_rows(int dtype, const void* dxm, const int32_t* inv, int rows_total, int T, int H, void* out,
+                        hipStream_t s);
+// cross-entropy over fp32 logits [Mpad, ldz]: writes dZ (activation type, zero in padded rows and
+// columns), per-row loss and lse; loss_out = mean over M rows in fixed order.
+hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mpad, int V, void* dz,
+                      float* row_loss, float* lse, float* loss_out, hipStream_t s);
+
+// embedding backward (first stage / retraining only): adds the gather contribution into gword,
+// writes gpos (all gpos_rows rows) and gtype.  rank/order hold T ints, cnt/start round_up(vocab,4)
+// ints, scratch ceil(T/64)*type_vocab*H floats.
+hipError_t embed_bwd(int dtype, const void* dz, const int32_t* ids, const int32_t* tt, int B, int S, int H, int vocab,
+                     int type_vocab, float* gword, float* gpos, float* gtype, int32_t* rank, int32_t* cnt,
+                     int32_t* start, int32_t* order, int gpos_rows, float* scratch, hipStream_t s);
+
+// ---- optimizer ------------------------------------------------------------------------------
+struct OptTensor {   // one logical tensor, device-side descriptor
+  unsigned long long offset;
+  unsigned long long count;
+  int decays;
+  int first_chunk;  // index of its first chunk in the global chunk list
+  int n_chunks;
+  int pad_;
+};
+struct OptHyper {
+  int kind;
+  float lr, beta1, beta2, eps, wd;
+  int bias_correction;
+};
+constexpr int OPT_CHUNK = 16384;  // elements per workgroup
+// Updates tensors [tensor0, tensor0+n_tensors), whose chunks are [chunk0, chunk0+n_chunks).
+// tsteps[i] is tensor i's step count (already incremented for this update).
+// chunk_norms: 2 floats per chunk; ratio: 1 float per tensor (LAMB only).
+hipError_t bump_steps(int32_t* tsteps, int tensor0, int n_tensors, hipStream_t s);
+hipError_t optimizer_step(const OptHyper& h, const OptTensor* tensors, const int32_t* tsteps, int tensor0,
+                          int n_tensors, const int32_t* chunk_tensor, int chunk0, int n_chunks, float* w,
+                          const float* g, float* m, float* v, bf16* shadow, float* chunk_norms, float* ratio,
+                          hipStream_t s);
+
+}  // namespace mslt

@@ -1,0 +1,706 @@
+// Host logic of the MSLT stage-step library: tensor table, arena layout, the launch sequence of
+// one stage step (frozen prefix forward-only, trainable top layers and head forward + backward),
+// gradient read-back and the optimizer update over the trainable tensors only (paper Section
+// 3.2).  Every arithmetic step runs in the HIP kernels of the sibling files; this file only
+// validates, lays out memory and enqueues.
+#include "../../include/mslt.h"
+#include "common.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace mslt;
+
+static thread_local std::string g_err;
+static int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+#define HIP_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e__ = (expr);                                                                \
+    if (e__ != hipSuccess) return fail(MSLT_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+static inline size_t rup(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+enum { T_WORD = 0, T_POS, T_TYPE, T_ELN_G, T_ELN_B, N_EMB };
+enum { L_WQ = 0, L_WK, L_WV, L_BQ, L_BK, L_BV, L_WO, L_BO, L_LN1G, L_LN1B, L_W1, L_B1, L_W2, L_B2, L_LN2G, L_LN2B, N_LAYER_T };
+enum { H_WT = 0, H_BT, H_LNG, H_LNB, H_BOUT, N_HEAD };
+
+struct LayerStash {
+  void *xout, *qkv, *ctx, *xhat1, *x1, *u, *g, *xhat2;
+  float *lse, *rstd1, *rstd2;
+};
+
+struct mslt_model {
+  mslt_config cfg;
+  int dtype;        // 0 fp32, 1 bf16
+  size_t esz;       // bytes per activation element
+  bool mfma;        // bf16 MFMA GEMMs with padded row counts
+  hipStream_t stream;
+  int H, F, V, Vp, nh, dh, L, Tp, Mp, cap;
+  std::vector<mslt_tensor_desc> table;
+  std::vector<size_t> alloc_count;  // elements reserved per tensor (>= count)
+  size_t arena_elems, packed_count;
+  float *param, *grad, *mom1, *mom2;
+  char* ws;
+  size_t ws_bytes;
+  // workspace carve-up
+  bf16* shadow;
+  void *x0, *xhat0; float* rstd0;
+  void *xa, *xb;                       // frozen-prefix ping-pong
+  void *s_qkv, *s_ctx, *s_x1, *s_g, *s_y;  // scratch of the forward-only path (+ s_y: pre-LN GEMM output)
+  std::vector<LayerStash> stash;
+  void *dxa, *dxb, *d_d, *d_u, *d_x1, *d_z1, *d_c, *d_qkv, *d_z0;
+  float *delta;
+  int32_t *pos, *lab, *inv, *counters;
+  void *xm, *ut, *gt, *xhat_t, *hm, *dz, *d_hm, *d_gt, *d_ut, *d_xm;
+  float *rstd_t, *logits, *row_loss, *lse_t, *loss;
+  float *red_scratch; size_t red_floats;
+  float *splitk; size_t splitk_floats;
+  int32_t *e_rank, *e_cnt, *e_start, *e_order;
+  OptTensor* o_tensors; int32_t* o_chunk_tensor; int32_t* o_tsteps; float* o_chunk_norms; float* o_ratio;
+  std::vector<int> first_chunk;  // per tensor, plus total at the end
+  // pinned host scalars
+  int32_t* h_counters; float* h_loss;
+  // last step
+  bool have_grads;
+  int last_f, last_k, last_emb, last_B, last_S, last_M;
+  const void* last_prefix;
+};
+
+// ---- tensor table ---------------------------------------------------------------------------
+static void add_tensor(mslt_model* m, const char* name, int layer, int rows, int cols, int decays, size_t reserve,
+                       bool align, size_t& off) {
+  mslt_tensor_desc d;
+  memset(&d, 0, sizeof d);
+  snprintf(d.name, sizeof d.name, "%s", name);
+  d.layer = layer;
+  d.rows = rows;
+  d.cols = cols;
+  d.decays = decays;
+  d.count = (size_t)rows * cols;
+  if (align) off = rup(off, 64);
+  d.offset = off;
+  off += reserve ? reserve : d.count;
+  m->table.push_back(d);
+  m->alloc_count.push_back(reserve ? reserve : d.count);
+}
+
+static void build_table(mslt_model* m) {
+  const int H = m->H, F = m->F, V = m->V, Vp = m->Vp;
+  size_t off = 0;
+  add_tensor(m, "emb.word", -1, V, H, 1, (size_t)Vp * H, true, off);
+  add_tensor(m, "emb.pos", -1, m->cfg.max_pos, H, 1, 0, true, off);
+  add_tensor(m, "emb.type", -1, m->cfg.type_vocab, H, 1, 0, true, off);
+  add_tensor(m, "emb.ln_g", -1, H, 1, 0, 0, true, off);
+  add_tensor(m, "emb.ln_b", -1, H, 1, 0, 0, true, off);
+  static const char* ln[N_LAYER_T] = {"wq", "wk", "wv", "bq", "bk", "bv", "wo", "bo", "ln1_g", "ln1_b",
+                                      "w1", "b1", "w2", "b2", "ln2_g", "ln2_b"};
+  for (int l = 0; l < m->L; ++l) {
+    char nm[32];
+    for (int j = 0; j < N_LAYER_T; ++j) {
+      snprintf(nm, sizeof nm, "layer%d.%s", l, ln[j]);
+      int rows = H, cols = 1, dec = 0;
+      switch (j) {
+        case L_WQ: case L_WK: case L_WV: case L_WO: rows = H; cols = H; dec = 1; break;
+        case L_W1: rows = F; cols = H; dec = 1; break;
+        case L_W2: rows = H; cols = F; dec = 1; break;
+        case L_B1: rows = F; break;
+        default: break;
+      }
+      // wq|wk|wv and bq|bk|bv stay contiguous: they are read as one [3H,H] matrix and one [3H] bias
+      bool align = !(j == L_WK || j == L_WV || j == L_BK || j == L_BV);
+      add_tensor(m, nm, l, rows, cols, dec, 0, align, off);
+    }
+  }
+  add_tensor(m, "head.wt", -2, H, H, 1, 0, true, off);
+  add_tensor(m, "head.bt", -2, H, 1, 0, 0, true, off);
+  add_tensor(m, "head.ln_g", -2, H, 1, 0, 0, true, off);
+  add_tensor(m, "head.ln_b", -2, H, 1, 0, 0, true, off);
+  add_tensor(m, "head.b_out", -2, V, 1, 0, (size_t)Vp, true, off);
+  m->arena_elems = rup(off, 64);
+  m->packed_count = 0;
+  for (auto& d : m->table) m->packed_count += d.count;
+  // optimizer chunks
+  m->first_chunk.clear();
+  int c = 0;
+  for (auto& d : m->table) {
+    m->first_chunk.push_back(c);
+    c += (int)((d.count + OPT_CHUNK - 1) / OPT_CHUNK);
+  }
+  m->first_chunk.push_back(c);
+}
+static inline int t_emb(int j) { return j; }
+static inline int t_layer(int l, int j) { return N_EMB + l * N_LAYER_T + j; }
+static inline int t_head(const mslt_model* m, int j) { return N_EMB + m->L * N_LAYER_T + j; }
+static inline float* Wf(const mslt_model* m, int t) { return m->param + m->table[t].offset; }
+static inline float* Gf(const mslt_model* m, int t) { return m->grad + m->table[t].offset; }
+// GEMM operand view of a weight matrix: bf16 shadow in bf16 mode, the master itself in fp32 mode
+static inline const void* Wg(const mslt_model* m, int t) {
+  return m->dtype ? (const void*)(m->shadow + m->table[t].offset) : (const void*)(m->param + m->table[t].offset);
+}
+
+// ---- workspace ------------------------------------------------------------------------------
+struct Bump {
+  char* base;
+  size_t off;
+  template <typename T>
+  T* take(size_t bytes) {
+    off = rup(off, 256);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+static size_t carve(mslt_model* m, char* base) {
+  Bump b{base, 0};
+  const size_t e = m->esz, H = m->H, F = m->F, Tp = m->Tp, Mp = m->Mp, Vp = m->Vp;
+  const size_t TH = Tp * H * e, TF = Tp * F * e, MH = Mp * H * e;
+  m->shadow = m->dtype ? b.take<bf16>(m->arena_elems * 2) : nullptr;
+  m->x0 = b.take<void>(TH); m->xhat0 = b.take<void>(TH); m->rstd0 = b.take<float>(Tp * 4);
+  m->xa = b.take<void>(TH); m->xb = b.take<void>(TH);
+  m->s_qkv = b.take<void>(3 * TH); m->s_ctx = b.take<void>(TH); m->s_x1 = b.take<void>(TH);
+  m->s_g = b.take<void>(TF); m->s_y = b.take<void>(TH);
+  m->stash.resize(m->L);
+  size_t lse_bytes = (size_t)m->cfg.max_batch * m->nh * m->cfg.max_seq * 4;
+  for (int l = 0; l < m->L; ++l) {
+    LayerStash& s = m->stash[l];
+    s.xout = b.take<void>(TH); s.qkv = b.take<void>(3 * TH); s.ctx = b.take<void>(TH);
+    s.xhat1 = b.take<void>(TH); s.x1 = b.take<void>(TH); s.u = b.take<void>(TF); s.g = b.take<void>(TF);
+    s.xhat2 = b.take<void>(TH);
+    s.lse = b.take<float>(lse_bytes); s.rstd1 = b.take<float>(Tp * 4); s.rstd2 = b.take<float>(Tp * 4);
+  }
+  m->dxa = b.take<void>(TH); m->dxb = b.take<void>(TH); m->d_d = b.take<void>(TH); m->d_u = b.take<void>(TF);
+  m->d_x1 = b.take<void>(TH); m->d_z1 = b.take<void>(TH); m->d_c = b.take<void>(TH); m->d_qkv = b.take<void>(3 * TH);
+  m->d_z0 = b.take<void>(TH);
+  m->delta = b.take<float>(lse_bytes);
+  m->pos = b.take<int32_t>((size_t)m->cap * 4); m->lab = b.take<int32_t>((size_t)m->cap * 4);
+  m->inv = b.take<int32_t>(Tp * 4); m->counters = b.take<int32_t>(64);
+  m->xm = b.take<void>(MH); m->ut = b.take<void>(MH); m->gt = b.take<void>(MH); m->xhat_t = b.take<void>(MH);
+  m->hm = b.take<void>(MH); m->dz = b.take<void>(Mp * Vp * e); m->d_hm = b.take<void>(MH); m->d_gt = b.take<void>(MH);
+  m->d_ut = b.take<void>(MH); m->d_xm = b.take<void>(MH);
+  m->rstd_t = b.take<float>(Mp * 4); m->logits = b.take<float>(Mp * Vp * 4); m->row_loss = b.take<float>(Mp * 4);
+  m->lse_t = b.take<float>(Mp * 4); m->loss = b.take<float>(64);
+  // reduction scratch: the largest of LayerNorm-backward partials, column-sum partials, token-type partials
+  size_t rows = Tp > Mp ? Tp : Mp;
+  size_t maxN = 3 * H > F ? 3 * H : F;
+  if (Vp > maxN) maxN = Vp;
+  size_t red = ln_bwd_scratch_floats((int)rows, (int)H);
+  size_t cs = colsum_scratch_floats((int)Tp, (int)(3 * H > F ? 3 * H : F));
+  size_t cv = colsum_scratch_floats((int)Mp, (int)Vp);
+  size_t ct = colsum_scratch_floats((int)Tp, (int)(m->cfg.type_vocab * H));
+  if (cs > red) red = cs;
+  if (cv > red) red = cv;
+  if (ct > red) red = ct;
+  m->red_floats = red;
+  m->red_scratch = b.take<float>(red * 4);
+  m->splitk_floats = m->mfma ? (size_t)1024 * 128 * 128 : 0;
+  m->splitk = b.take<float>(m->splitk_floats * 4);
+  m->e_rank = b.take<int32_t>(Tp * 4); m->e_order = b.take<int32_t>(Tp * 4);
+  m->e_cnt = b.take<int32_t>(rup(m->V, 4) * 4); m->e_start = b.take<int32_t>(rup(m->V, 4) * 4);
+  size_t nt = m->table.size();
+  size_t nchunks = (size_t)m->first_chunk.back();
+  m->o_tensors = b.take<OptTensor>(nt * sizeof(OptTensor));
+  m->o_chunk_tensor = b.take<int32_t>(nchunks * 4);
+  m->o_tsteps = b.take<int32_t>(nt * 4);
+  m->o_chunk_norms = b.take<float>(nchunks * 8);
+  m->o_ratio = b.take<float>(nt * 4);
+  return rup(b.off, 256);
+}
+
+static int check_config(const mslt_config* c) {
+  if (!c) return fail(MSLT_ERR_ARG, "config is null");
+  if (c->n_layers_max < 1 || c->hidden < 4 || c->n_heads < 1 || c->ffn < 4 || c->vocab < 2 || c->max_pos < 1 ||
+      c->type_vocab < 1 || c->max_batch < 1 || c->max_seq < 1 || c->max_predictions < 0)
+    return fail(MSLT_ERR_ARG, "config: non-positive dimension");
+  if (c->hidden % 4 || c->ffn % 4) return fail(MSLT_ERR_ARG, "config: hidden and ffn must be multiples of 4");
+  if (c->hidden > 2048) return fail(MSLT_ERR_ARG, "config: hidden above 2048 is not supported");
+  if (c->hidden % c->n_heads) return fail(MSLT_ERR_ARG, "config: hidden is not a multiple of n_heads");
+  if (c->hidden / c->n_heads > 128) return fail(MSLT_ERR_ARG, "config: head width above 128 is not supported");
+  if (c->type_vocab > 4) return fail(MSLT_ERR_ARG, "config: type_vocab above 4 is not supported");
+  if (c->max_seq > c->max_pos) return fail(MSLT_ERR_ARG, "config: max_seq exceeds max_pos");
+  if ((long long)c->max_batch * c->max_seq > (1 << 22)) return fail(MSLT_ERR_ARG, "config: max_batch*max_seq too large");
+  if (c->precision != 0 && c->precision != 1) return fail(MSLT_ERR_ARG, "config: precision must be 0 or 1");
+  if (!(c->ln_eps >= 0.f)) return fail(MSLT_ERR_ARG, "config: ln_eps must be >= 0");
+  return MSLT_OK;
+}
+
+static void setup_dims(mslt_model* m, const mslt_config* cfg) {
+  m->cfg = *cfg;
+  m->dtype = cfg->precision;
+  m->esz = cfg->precision ? 2 : 4;
+  m->H = cfg->hidden; m->F = cfg->ffn; m->V = cfg->vocab; m->nh = cfg->n_heads; m->dh = cfg->hidden / cfg->n_heads;
+  m->L = cfg->n_layers_max;
+  m->Vp = (int)rup(cfg->vocab, 128);
+  int T = cfg->max_batch * cfg->max_seq;
+  m->cap = cfg->max_predictions > 0 && cfg->max_predictions < T ? cfg->max_predictions : T;
+  m->Tp = (int)rup(T, 128);
+  m->Mp = (int)rup(m->cap, 128);
+  m->mfma = cfg->precision == 1 && cfg->hidden % 128 == 0 && cfg->ffn % 128 == 0;
+  build_table(m);
+}
+
+extern "C" int mslt_query_sizes(const mslt_config* cfg, size_t* param_bytes, size_t* grad_bytes, size_t* opt_state_bytes,
+                                size_t* workspace_bytes) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  mslt_model m{};
+  setup_dims(&m, cfg);
+  size_t ws = carve(&m, nullptr);
+  if (param_bytes) *param_bytes = m.arena_elems * 4;
+  if (grad_bytes) *grad_bytes = m.arena_elems * 4;
+  if (opt_state_bytes) *opt_state_bytes = m.arena_elems * 8;
+  if (workspace_bytes) *workspace_bytes = ws;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_init_model(const mslt_config* cfg, void* param_arena, void* grad_arena, void* opt_arena,
+                               void* workspace, void* hip_stream, mslt_model** out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!param_arena || !grad_arena || !opt_arena || !workspace || !out) return fail(MSLT_ERR_ARG, "null arena or out");
+  for (void* p : {param_arena, grad_arena, opt_arena, workspace})
+    if (reinterpret_cast<uintptr_t>(p) % 256) return fail(MSLT_ERR_ARG, "arena not 256-byte aligned");
+  mslt_model* m = new mslt_model{};
+  setup_dims(m, cfg);
+  m->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  m->param = (float*)param_arena;
+  m->grad = (float*)grad_arena;
+  m->mom1 = (float*)opt_arena;
+  m->mom2 = m->mom1 + m->arena_elems;
+  m->ws = (char*)workspace;
+  m->ws_bytes = carve(m, m->ws);
+  m->have_grads = false;
+  m->last_prefix = nullptr;
+  hipError_t e;
+#define INIT_TRY(expr)                                                                  \
+  if ((e = (expr)) != hipSuccess) {                                                     \
+    delete m;                                                                           \
+    return fail(MSLT_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e));                   \
+  }
+  INIT_TRY(hipHostMalloc((void**)&m->h_counters, 64, hipHostMallocDefault));
+  m->h_loss = reinterpret_cast<float*>(m->h_counters + 8);
+  INIT_TRY(fill_zero(m->param, m->arena_elems * 4, m->stream));
+  INIT_TRY(fill_zero(m->grad, m->arena_elems * 4, m->stream));
+  INIT_TRY(fill_zero(m->mom1, m->arena_elems * 8, m->stream));
+  INIT_TRY(fill_zero(m->ws, m->ws_bytes, m->stream));
+  // optimizer tables
+  std::vector<OptTensor> ot(m->table.size());
+  std::vector<int32_t> ct((size_t)m->first_chunk.back());
+  for (size_t i = 0; i < m->table.size(); ++i) {
+    ot[i].offset = m->table[i].offset;
+    ot[i].count = m->table[i].count;
+    ot[i].decays = m->table[i].decays;
+    ot[i].first_chunk = m->first_chunk[i];
+    ot[i].n_chunks = m->first_chunk[i + 1] - m->first_chunk[i];
+    ot[i].pad_ = 0;
+    for (int c = m->first_chunk[i]; c < m->first_chunk[i + 1]; ++c) ct[c] = (int32_t)i;
+  }
+  INIT_TRY(hipMemcpyAsync(m->o_tensors, ot.data(), ot.size() * sizeof(OptTensor), hipMemcpyHostToDevice, m->stream));
+  INIT_TRY(hipMemcpyAsync(m->o_chunk_tensor, ct.data(), ct.size() * 4, hipMemcpyHostToDevice, m->stream));
+  INIT_TRY(hipStreamSynchronize(m->stream));
+#undef INIT_TRY
+  *out = m;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_destroy(mslt_model* m) {
+  if (!m) return MSLT_OK;
+  hipStreamSynchronize(m->stream);
+  if (m->h_counters) hipHostFree(m->h_counters);
+  delete m;
+  return MSLT_OK;
+}
+
+extern "C" const char* mslt_last_error(void) { return g_err.c_str(); }
+
+extern "C" int mslt_sync(const mslt_model* m) {
+  if (!m) return fail(MSLT_ERR_ARG, "model is null");
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  return MSLT_OK;
+}
+
+extern "C" int mslt_tensor_table(const mslt_model* m, int* n, const mslt_tensor_desc** out) {
+  if (!m || !n || !out) return fail(MSLT_ERR_ARG, "null argument");
+  *n = (int)m->table.size();
+  *out = m->table.data();
+  return MSLT_OK;
+}
+
+static int refresh_shadow(mslt_model* m, size_t off, size_t count) {
+  if (!m->dtype) return MSLT_OK;
+  HIP_TRY(cast_f32_to_bf16(m->param + off, m->shadow + off, count, m->stream));
+  return MSLT_OK;
+}
+
+extern "C" int mslt_load_params(mslt_model* m, const float* host, size_t n_floats) {
+  if (!m || !host) return fail(MSLT_ERR_ARG, "null argument");
+  if (n_floats != m->packed_count)
+    return fail(MSLT_ERR_ARG, "load_params: expected %zu floats, got %zu", m->packed_count, n_floats);
+  size_t o = 0;
+  for (auto& d : m->table) {
+    HIP_TRY(hipMemcpyAsync(m->param + d.offset, host + o, d.count * 4, hipMemcpyHostToDevice, m->stream));
+    o += d.count;
+  }
+  int rc = refresh_shadow(m, 0, m->arena_elems);
+  if (rc) return rc;
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  return MSLT_OK;
+}
+
+extern "C" int mslt_get_params(const mslt_model* m, float* host, size_t n_floats) {
+  if (!m || !host) return fail(MSLT_ERR_ARG, "null argument");
+  if (n_floats != m->packed_count)
+    return fail(MSLT_ERR_ARG, "get_params: expected %zu floats, got %zu", m->packed_count, n_floats);
+  size_t o = 0;
+  for (auto& d : m->table) {
+    HIP_TRY(hipMemcpyAsync(host + o, m->param + d.offset, d.count * 4, hipMemcpyDeviceToHost, m->stream));
+    o += d.count;
+  }
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  return MSLT_OK;
+}
+
+// ---- GEMM dispatch --------------------------------------------------------------------------
+static int pick_splitk(int M, int N, int K) {
+  int tiles = (M / 128) * (N / 128);
+  if (tiles >= 256 || K < 1024) return 1;
+  int s = (512 + tiles - 1) / tiles;
+  if (s > 16) s = 16;
+  while (s > 1 && (K % (s * 64) != 0 || K / s < 256)) --s;
+  return s;
+}
+static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false) {
+  if (m->mfma && gemm_mfma_supported(d)) {
+    int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
+    while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
+    HIP_TRY(gemm_mfma(d, sk, m->splitk, m->stream));
+  } else {
+    HIP_TRY(gemm_simt(m->dtype, d, m->stream));
+  }
+  return MSLT_OK;
+}
+#define RC(expr)          \
+  do {                    \
+    int rc__ = (expr);    \
+    if (rc__) return rc__; \
+  } while (0)
+
+// Y[rows,N] = X[rows,K] W[N,K]^T + bias, optional GELU
+static int linear_fwd(mslt_model* m, const void* X, int rows, int K, const void* W, int N, const float* bias, void* Y,
+                      int out_f32, int ldo, int act, void* pre_act) {
+  GemmDesc d;
+  d.A = X; d.lda = K; d.a_kcontig = 1; d.M = rows;
+  d.B = W; d.ldb = K; d.b_kcontig = 1; d.N = N; d.K = K;
+  d.epi.out = Y; d.epi.ldo = ldo; d.epi.out_f32 = out_f32; d.epi.bias = bias; d.epi.act = act; d.epi.out2 = pre_act;
+  return run_gemm(m, d);
+}
+// dX[rows,K] = dY[rows,N] W[N,K]  (+ addend | * gelu'(U))
+static int linear_bwd_input(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* W, int K, void* dX,
+                            int act, const void* aux) {
+  GemmDesc d;
+  d.A = dY; d.lda = ldy; d.a_kcontig = 1; d.M = rows;
+  d.B = W; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = N;
+  d.epi.out = dX; d.epi.ldo = K; d.epi.act = act; d.epi.aux = aux; d.epi.ldaux = K;
+  return run_gemm(m, d);
+}
+// dW[N,K] = dY[rows,N]^T X[rows,K]   (fp32 out, contraction over rows)
+static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* X, int K, float* dW) {
+  GemmDesc d;
+  d.A = dY; d.lda = ldy; d.a_kcontig = 0; d.M = N;
+  d.B = X; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = rows;
+  d.epi.out = dW; d.epi.ldo = K; d.epi.out_f32 = 1;
+  return run_gemm(m, d, true);
+}
+
+// ---- one encoder layer ----------------------------------------------------------------------
+static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, const void* Xin, void* Xout,
+                         const LayerStash* st) {
+  const int H = m->H, F = m->F;
+  void* qkv = st ? st->qkv : m->s_qkv;
+  void* ctx = st ? st->ctx : m->s_ctx;
+  void* x1 = st ? st->x1 : m->s_x1;
+  void* g = st ? st->g : m->s_g;
+  RC(linear_fwd(m, Xin, Tr, H, Wg(m, t_layer(l, L_WQ)), 3 * H, Wf(m, t_layer(l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr));
+  AttnDesc a{qkv, ctx, st ? st->lse : nullptr, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh, m->cfg.mask_bias};
+  if (m->dtype == 1 && attention_mfma_supported(bt->seq, m->dh))
+    HIP_TRY(attention_fwd_mfma(a, m->stream));
+  else
+    HIP_TRY(attention_fwd_simple(m->dtype, a, m->stream));
+  RC(linear_fwd(m, ctx, Tr, H, Wg(m, t_layer(l, L_WO)), H, Wf(m, t_layer(l, L_BO)), m->s_y, 0, H, EPI_NONE, nullptr));
+  LnStash s1, s2;
+  if (st) { s1.xhat = st->xhat1; s1.rstd = st->rstd1; s2.xhat = st->xhat2; s2.rstd = st->rstd2; }
+  HIP_TRY(add_ln_fwd(m->dtype, m->s_y, Xin, Wf(m, t_layer(l, L_LN1G)), Wf(m, t_layer(l, L_LN1B)), m->cfg.ln_eps, x1, s1,
+                     Tr, H, m->stream));
+  RC(linear_fwd(m, x1, Tr, H, Wg(m, t_layer(l, L_W1)), F, Wf(m, t_layer(l, L_B1)), g, 0, F, EPI_GELU, st ? st->u : nullptr));
+  RC(linear_fwd(m, g, Tr, F, Wg(m, t_layer(l, L_W2)), H, Wf(m, t_layer(l, L_B2)), m->s_y, 0, H, EPI_NONE, nullptr));
+  HIP_TRY(add_ln_fwd(m->dtype, m->s_y, x1, Wf(m, t_layer(l, L_LN2G)), Wf(m, t_layer(l, L_LN2B)), m->cfg.ln_eps, Xout, s2,
+                     Tr, H, m->stream));
+  return MSLT_OK;
+}
+
+static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, float* out) {
+  HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, m->red_scratch, m->stream));
+  return MSLT_OK;
+}
+
+// dXout: gradient w.r.t. the layer output; dXin: where to put the gradient w.r.t. the layer input,
+// or null when nothing below needs it (the block below is frozen: Section 3.1).
+static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, const void* dXout,
+                          void* dXin) {
+  const int H = m->H, F = m->F;
+  const LayerStash& st = m->stash[l];
+  hipStream_t s = m->stream;
+  HIP_TRY(ln_bwd(m->dtype, dXout, st.xhat2, st.rstd2, Wf(m, t_layer(l, L_LN2G)), m->d_d, Gf(m, t_layer(l, L_LN2G)),
+                 Gf(m, t_layer(l, L_LN2B)), m->red_scratch, Tr, H, s));
+  RC(linear_bwd_weight(m, m->d_d, Tr, H, H, st.g, F, Gf(m, t_layer(l, L_W2))));
+  RC(bias_grad(m, m->d_d, H, Tr, H, Gf(m, t_layer(l, L_B2))));
+  RC(linear_bwd_input(m, m->d_d, Tr, H, H, Wg(m, t_layer(l, L_W2)), F, m->d_u, EPI_MUL_GELU_GRAD, st.u));
+  RC(linear_bwd_weight(m, m->d_u, Tr, F, F, st.x1, H, Gf(m, t_layer(l, L_W1))));
+  RC(bias_grad(m, m->d_u, F, Tr, F, Gf(m, t_layer(l, L_B1))));
+  RC(linear_bwd_input(m, m->d_u, Tr, F, F, Wg(m, t_layer(l, L_W1)), H, m->d_x1, EPI_ADD, m->d_d));
+  HIP_TRY(ln_bwd(m->dtype, m->d_x1, st.xhat1, st.rstd1, Wf(m, t_layer(l, L_LN1G)), m->d_z1, Gf(m, t_layer(l, L_LN1G)),
+                 Gf(m, t_layer(l, L_LN1B)), m->red_scratch, Tr, H, s));
+  RC(linear_bwd_weight(m, m->d_z1, Tr, H, H, st.ctx, H, Gf(m, t_layer(l, L_WO))));
+  RC(bias_grad(m, m->d_z1, H, Tr, H, Gf(m, t_layer(l, L_BO))));
+  RC(linear_bwd_input(m, m->d_z1, Tr, H, H, Wg(m, t_layer(l, L_WO)), H, m->d_c, EPI_NONE, nullptr));
+  AttnBwdDesc a{st.qkv, st.ctx, m->d_c, st.lse, m->delta, m->d_qkv, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh,
+                m->cfg.mask_bias};
+  if (m->dtype == 1 && attention_mfma_supported(bt->seq, m->dh))
+    HIP_TRY(attention_bwd_mfma(a, s));
+  else
+    HIP_TRY(attention_bwd_simple(m->dtype, a, s));
+  if (Tr > T)  // padded token rows must contribute nothing to the weight gradients
+    HIP_TRY(fill_zero((char*)m->d_qkv + (size_t)T * 3 * H * m->esz, (size_t)(Tr - T) * 3 * H * m->esz, s));
+  RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_layer(l, L_WQ))));
+  RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_layer(l, L_BQ))));
+  if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_layer(l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
+  return MSLT_OK;
+}
+
+// ---- the stage step -------------------------------------------------------------------------
+extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const mslt_batch* bt, float* loss_out) {
+  if (!m || !bt || !loss_out) return fail(MSLT_ERR_ARG, "null argument");
+  if (k < 1 || f < 0 || f + k > m->L)
+    return fail(MSLT_ERR_ARG, "stage_step: bad layer split frozen=%d trainable=%d (layers %d)", f, k, m->L);
+  if (train_emb != 0 && train_emb != 1) return fail(MSLT_ERR_ARG, "stage_step: train_embeddings must be 0 or 1");
+  if (train_emb && f != 0) return fail(MSLT_ERR_ARG, "stage_step: embeddings train only when nothing is frozen");
+  if (!bt->input_ids || !bt->token_type_ids || !bt->attn_mask || !bt->labels)
+    return fail(MSLT_ERR_ARG, "stage_step: null batch pointer");
+  if (bt->batch < 1 || bt->batch > m->cfg.max_batch || bt->seq < 1 || bt->seq > m->cfg.max_seq)
+    return fail(MSLT_ERR_ARG, "stage_step: batch %dx%d outside 1..%dx1..%d", bt->batch, bt->seq, m->cfg.max_batch,
+                m->cfg.max_seq);
+  hipStream_t s = m->stream;
+  const int H = m->H, B = bt->batch, S = bt->seq, T = B * S;
+  m->have_grads = false;
+
+  // S0: batch check and compaction of the predicted positions (only index scratch is written)
+  HIP_TRY(batch_scan(bt->input_ids, bt->token_type_ids, bt->attn_mask, bt->labels, T, m->V, m->cfg.type_vocab, m->cap,
+                     m->pos, m->lab, m->inv, m->counters, s));
+  HIP_TRY(hipMemcpyAsync(m->h_counters, m->counters, 8, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  const int M = m->h_counters[0], bad = m->h_counters[1];
+  if (bad) return fail(MSLT_ERR_DATA, "stage_step: batch content out of range (bits %d: 1 id, 2 type, 4 label, 8 mask)", bad);
+  if (M < 1) return fail(MSLT_ERR_DATA, "stage_step: no predicted position in the batch");
+  if (M > m->cap) return fail(MSLT_ERR_DATA, "stage_step: %d predicted positions exceed max_predictions %d", M, m->cap);
+  const int Tr = m->mfma ? (int)rup(T, 128) : T;
+  const int Mr = m->mfma ? (int)rup(M, 128) : M;
+  const int Vr = m->mfma ? m->Vp : m->V;
+
+  // S1: embeddings + LayerNorm
+  LnStash e0;
+  if (train_emb) { e0.xhat = m->xhat0; e0.rstd = m->rstd0; }
+  HIP_TRY(embed_ln_fwd(m->dtype, bt->input_ids, bt->token_type_ids, S, Wf(m, T_WORD), Wf(m, T_POS), Wf(m, T_TYPE),
+                       Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, s));
+  // S2: frozen prefix, forward only, two ping-pong buffers, nothing kept
+  const void* x = m->x0;
+  for (int l = 0; l < f; ++l) {
+    void* xo = (l & 1) ? m->xb : m->xa;
+    RC(layer_forward(m, l, bt, Tr, x, xo, nullptr));
+    x = xo;
+  }
+  m->last_prefix = x;
+  // S3: trainable layers, with stash
+  for (int l = f; l < f + k; ++l) {
+    RC(layer_forward(m, l, bt, Tr, x, m->stash[l].xout, &m->stash[l]));
+    x = m->stash[l].xout;
+  }
+  // S4-S6: head forward and loss
+  const int th = t_head(m, 0);
+  HIP_TRY(gather_rows(m->dtype, x, m->pos, M, Mr, H, m->xm, s));
+  RC(linear_fwd(m, m->xm, Mr, H, Wg(m, th + H_WT), H, Wf(m, th + H_BT), m->gt, 0, H, EPI_GELU, m->ut));
+  LnStash sh{m->xhat_t, m->rstd_t};
+  HIP_TRY(add_ln_fwd(m->dtype, m->gt, nullptr, Wf(m, th + H_LNG), Wf(m, th + H_LNB), m->cfg.ln_eps, m->hm, sh, Mr, H, s));
+  RC(linear_fwd(m, m->hm, Mr, H, Wg(m, T_WORD), Vr, Wf(m, th + H_BOUT), m->logits, 1, m->Vp, EPI_NONE, nullptr));
+  HIP_TRY(ce_fwd_bwd(m->dtype, m->logits, m->Vp, m->lab, M, Mr, m->V, m->dz, m->row_loss, m->lse_t, m->loss, s));
+  HIP_TRY(hipMemcpyAsync(m->h_loss, m->loss, 4, hipMemcpyDeviceToHost, s));
+  // S7: head backward
+  RC(bias_grad(m, m->dz, m->Vp, Mr, m->V, Gf(m, th + H_BOUT)));
+  if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD)));
+  RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr));
+  HIP_TRY(ln_bwd(m->dtype, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG),
+                 Gf(m, th + H_LNB), m->red_scratch, Mr, H, s));
+  HIP_TRY(mul_gelu_grad(m->dtype, m->d_gt, m->ut, m->d_ut, (size_t)Mr * H, s));
+  RC(linear_bwd_weight(m, m->d_ut, Mr, H, H, m->xm, H, Gf(m, th + H_WT)));
+  RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT)));
+  RC(linear_bwd_input(m, m->d_ut, Mr, H, H, Wg(m, th + H_WT), H, m->d_xm, EPI_NONE, nullptr));
+  // S8: scatter into the gradient of the top layer's output
+  void* dx = m->dxa;
+  HIP_TRY(scatter_rows(m->dtype, m->d_xm, m->inv, Tr, T, H, dx, s));
+  // S9: trainable layers backward, top down
+  for (int l = f + k - 1; l >= f; --l) {
+    const void* xin = (l == f) ? m->last_prefix : m->stash[l - 1].xout;
+    bool need_dx = (l > f) || train_emb;
+    void* dxin = need_dx ? (dx == m->dxa ? m->dxb : m->dxa) : nullptr;
+    RC(layer_backward(m, l, bt, T, Tr, xin, dx, dxin));
+    if (dxin) dx = dxin;
+  }
+  // S10: embedding backward (first stage / retraining)
+  if (train_emb) {
+    HIP_TRY(ln_bwd(m->dtype, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B),
+                   m->red_scratch, T, H, s));
+    HIP_TRY(embed_bwd(m->dtype, m->d_z0, bt->input_ids, bt->token_type_ids, B, S, H, m->V, m->cfg.type_vocab,
+                      Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order,
+                      m->cfg.max_pos, m->red_scratch, s));
+  }
+  HIP_TRY(hipStreamSynchronize(s));
+  *loss_out = *m->h_loss;
+  m->have_grads = true;
+  m->last_f = f; m->last_k = k; m->last_emb = train_emb; m->last_B = B; m->last_S = S; m->last_M = M;
+  if (!std::isfinite(*loss_out)) return fail(MSLT_ERR_NONFINITE, "stage_step: loss is not finite");
+  return MSLT_OK;
+}
+
+// trainable tensor ranges of the last step, as [first, last) index pairs in table order
+static int trainable_ranges(const mslt_model* m, int (*r)[2]) {
+  int n = 0;
+  if (m->last_emb) { r[n][0] = 0; r[n][1] = N_EMB; ++n; }
+  r[n][0] = t_layer(m->last_f, 0); r[n][1] = t_layer(m->last_f + m->last_k, 0); ++n;
+  r[n][0] = t_head(m, 0); r[n][1] = t_head(m, 0) + N_HEAD; ++n;
+  // merge adjacent ranges
+  int out = 0;
+  for (int i = 0; i < n; ++i) {
+    if (out && r[out - 1][1] == r[i][0]) r[out - 1][1] = r[i][1];
+    else { r[out][0] = r[i][0]; r[out][1] = r[i][1]; ++out; }
+  }
+  return out;
+}
+
+extern "C" int mslt_grad_count(const mslt_model* m, size_t* n_floats) {
+  if (!m || !n_floats) return fail(MSLT_ERR_ARG, "null argument");
+  if (!m->have_grads) return fail(MSLT_ERR_STATE, "no gradients: run a successful stage_step first");
+  int r[3][2];
+  int n = trainable_ranges(m, r);
+  size_t c = 0;
+  for (int i = 0; i < n; ++i)
+    for (int t = r[i][0]; t < r[i][1]; ++t) c += m->table[t].count;
+  *n_floats = c;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_get_grads(const mslt_model* m, float* host, size_t n_floats) {
+  if (!m || !host) return fail(MSLT_ERR_ARG, "null argument");
+  size_t need;
+  int rc = mslt_grad_count(m, &need);
+  if (rc) return rc;
+  if (need != n_floats) return fail(MSLT_ERR_ARG, "get_grads: expected %zu floats, got %zu", need, n_floats);
+  int r[3][2];
+  int n = trainable_ranges(m, r);
+  size_t o = 0;
+  for (int i = 0; i < n; ++i)
+    for (int t = r[i][0]; t < r[i][1]; ++t) {
+      HIP_TRY(hipMemcpyAsync(host + o, m->grad + m->table[t].offset, m->table[t].count * 4, hipMemcpyDeviceToHost,
+                             m->stream));
+      o += m->table[t].count;
+    }
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  return MSLT_OK;
+}
+
+extern "C" int mslt_apply_update(mslt_model* m, const mslt_opt* opt) {
+  if (!m || !opt) return fail(MSLT_ERR_ARG, "null argument");
+  if (!m->have_grads) return fail(MSLT_ERR_STATE, "apply_update: no gradients from a preceding stage_step");
+  if (opt->kind != 0 && opt->kind != 1) return fail(MSLT_ERR_ARG, "apply_update: kind must be 0 (Adam) or 1 (LAMB)");
+  if (!(opt->beta1 >= 0.f && opt->beta1 < 1.f && opt->beta2 >= 0.f && opt->beta2 < 1.f && opt->eps >= 0.f))
+    return fail(MSLT_ERR_ARG, "apply_update: bad beta or eps");
+  OptHyper h{opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay, opt->bias_correction};
+  int r[3][2];
+  int n = trainable_ranges(m, r);
+  for (int i = 0; i < n; ++i) {
+    int t0 = r[i][0], nt = r[i][1] - r[i][0];
+    int c0 = m->first_chunk[t0], nc = m->first_chunk[r[i][1]] - c0;
+    HIP_TRY(bump_steps(m->o_tsteps, t0, nt, m->stream));
+    HIP_TRY(optimizer_step(h, m->o_tensors, m->o_tsteps, t0, nt, m->o_chunk_tensor, c0, nc, m->param, m->grad, m->mom1,
+                           m->mom2, m->shadow, m->o_chunk_norms, m->o_ratio, m->stream));
+  }
+  m->have_grads = false;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_debug_masked(const mslt_model* m, int32_t* pos_out, int32_t* label_out, int* m_out) {
+  if (!m || !pos_out || !label_out || !m_out) return fail(MSLT_ERR_ARG, "null argument");
+  if (!m->last_prefix) return fail(MSLT_ERR_STATE, "debug_masked: no step has run");
+  HIP_TRY(hipMemcpyAsync(pos_out, m->pos, (size_t)m->last_M * 4, hipMemcpyDeviceToHost, m->stream));
+  HIP_TRY(hipMemcpyAsync(label_out, m->lab, (size_t)m->last_M * 4, hipMemcpyDeviceToHost, m->stream));
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  *m_out = m->last_M;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_debug_prefix_output(const mslt_model* m, float* host, size_t n_floats) {
+  if (!m || !host) return fail(MSLT_ERR_ARG, "null argument");
+  if (!m->last_prefix) return fail(MSLT_ERR_STATE, "debug_prefix_output: no step has run");
+  size_t need = (size_t)m->last_B * m->last_S * m->H;
+  if (n_floats != need) return fail(MSLT_ERR_ARG, "debug_prefix_output: expected %zu floats, got %zu", need, n_floats);
+  if (m->dtype == 0) {
+    HIP_TRY(hipMemcpyAsync(host, m->last_prefix, need * 4, hipMemcpyDeviceToHost, m->stream));
+  } else {
+    // widen on the device into the logits buffer (free between steps), then copy
+    if (need > (size_t)m->Mp * m->Vp) return fail(MSLT_ERR_ARG, "debug_prefix_output: scratch too small");
+    HIP_TRY(widen_to_f32(1, m->last_prefix, m->logits, need, m->stream));
+    HIP_TRY(hipMemcpyAsync(host, m->logits, need * 4, hipMemcpyDeviceToHost, m->stream));
+  }
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  return MSLT_OK;
+}
+
+extern "C" int mslt_grow(mslt_model* m, int n_present, int n_new) {
+  if (!m) return fail(MSLT_ERR_ARG, "model is null");
+  if (n_new < 1 || n_present < n_new || n_present + n_new > m->L)
+    return fail(MSLT_ERR_ARG, "grow: bad layer counts present=%d new=%d (layers %d)", n_present, n_new, m->L);
+  for (int i = 0; i < n_new; ++i) {
+    int src = n_present - n_new + i, dst = n_present + i;
+    for (int j = 0; j < N_LAYER_T; ++j) {
+      const mslt_tensor_desc& a = m->table[t_layer(src, j)];
+      const mslt_tensor_desc& b = m->table[t_layer(dst, j)];
+      HIP_TRY(hipMemcpyAsync(m->param + b.offset, m->param + a.offset, a.count * 4, hipMemcpyDeviceToDevice, m->stream));
+      if (m->dtype)
+        HIP_TRY(hipMemcpyAsync(m->shadow + b.offset, m->shadow + a.offset, a.count * 2, hipMemcpyDeviceToDevice,
+                               m->stream));
+    }
+    // moments of the new layer restart from zero (its tensors are one contiguous block)
+    size_t lo = m->table[t_layer(dst, 0)].offset;
+    size_t hi = m->table[t_layer(dst, N_LAYER_T - 1)].offset + m->table[t_layer(dst, N_LAYER_T - 1)].count;
+    hi = rup(hi, 4);
+    HIP_TRY(fill_zero(m->mom1 + lo, (hi - lo) * 4, m->stream));
+    HIP_TRY(fill_zero(m->mom2 + lo, (hi - lo) * 4, m->stream));
+  }
+  // step counts of the new layers back to 0: 16 ints per layer are contiguous in the table
+  std::vector<int32_t> z((size_t)n_new * N_LAYER_T, 0);
+  HIP_TRY(hipMemcpyAsync(m->o_tsteps + t_layer(n_present, 0), z.data(), z.size() * 4, hipMemcpyHostToDevice, m->stream));
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  m->have_grads = false;
+  return MSLT_OK;
+}

@@ -1,0 +1,756 @@
+// Row-wise, element-wise and indexing kernels of the MSLT stage step: embedding + LayerNorm,
+// residual + LayerNorm and its backward, column sums for bias gradients, masked-row
+// compaction / gather / scatter, cross-entropy over the vocabulary logits, embedding backward.
+// All are bound by HBM traffic; rows are handled one wavefront (64 lanes) per row with the row
+// held in registers, reductions by cross-lane shuffles.  No atomics on floating point: every
+// reduction has a fixed order, so results are bitwise reproducible.
+#include "common.h"
+
+namespace mslt {
+
+// ---- small vector helpers -------------------------------------------------------------------
+__device__ inline float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ inline float4 load4(const bf16* p) {
+  uint2 r = *reinterpret_cast<const uint2*>(p);
+  float4 o;
+  o.x = __uint_as_float(r.x << 16);
+  o.y = __uint_as_float(r.x & 0xffff0000u);
+  o.z = __uint_as_float(r.y << 16);
+  o.w = __uint_as_float(r.y & 0xffff0000u);
+  return o;
+}
+__device__ inline void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ inline void store4(bf16* p, float4 v) {
+  uint2 r;
+  r.x = (uint32_t)f2bf(v.x).x | ((uint32_t)f2bf(v.y).x << 16);
+  r.y = (uint32_t)f2bf(v.z).x | ((uint32_t)f2bf(v.w).x << 16);
+  *reinterpret_cast<uint2*>(p) = r;
+}
+
+constexpr int LN_MAXV = 8;  // float4 per lane: H <= 64*4*8 = 2048
+
+// ---- fill / cast ----------------------------------------------------------------------------
+__global__ void k_fill_zero(uint32_t* p, size_t n_words) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t n4 = n_words / 4;
+  uint4 z = make_uint4(0, 0, 0, 0);
+  for (size_t j = i; j < n4; j += stride) reinterpret_cast<uint4*>(p)[j] = z;
+  for (size_t j = n4 * 4 + i; j < n_words; j += stride) p[j] = 0;
+}
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 4 != 0 || (reinterpret_cast<uintptr_t>(p) % 16) != 0) return hipErrorInvalidValue;
+  size_t words = bytes / 4;
+  size_t blocks = (words / 4 + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 8192) blocks = 8192;
+  k_fill_zero<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(reinterpret_cast<uint32_t*>(p), words);
+  return hipGetLastError();
+}
+
+__global__ void k_cast_bf16(const float* __restrict__ src, bf16* __restrict__ dst, size_t n) {
+  size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+  for (; i + 3 < n; i += stride) store4(dst + i, load4(src + i));
+  // tail (n not a multiple of 4): handled by the first threads
+  size_t t = (n / 4) * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) dst[t] = f2bf(src[t]);
+}
+hipError_t cast_f32_to_bf16(const float* src, bf16* dst, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n / 4 + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 8192) blocks = 8192;
+  k_cast_bf16<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+
+template <typename AT>
+__global__ void k_widen(const AT* __restrict__ src, float* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = ldf(src + i);
+}
+hipError_t widen_to_f32(int dtype, const void* src, float* dst, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (dtype == 0)
+    k_widen<float><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const float*)src, dst, n);
+  else
+    k_widen<bf16><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const bf16*)src, dst, n);
+  return hipGetLastError();
+}
+
+// ---- batch check + compaction of predicted positions (integer, exact) -----------------------
+__global__ void __launch_bounds__(1024) k_batch_scan(const int32_t* __restrict__ ids, const int32_t* __restrict__ tt,
+                                                     const int32_t* __restrict__ am, const int32_t* __restrict__ labels,
+                                                     int T, int vocab, int type_vocab, int cap, int32_t* pos,
+                                                     int32_t* lab, int32_t* inv, int32_t* counters) {
+  __shared__ int sc[1024];
+  __shared__ int bad_all;
+  int tid = threadIdx.x;
+  if (tid == 0) bad_all = 0;
+  int per = (T + 1023) / 1024;
+  int b = tid * per, e = min(T, b + per);
+  int c = 0, bad = 0;
+  for (int t = b; t < e; ++t) {
+    int id = ids[t];
+    if (id < 0 || id >= vocab) bad |= 1;
+    int ty = tt[t];
+    if (ty < 0 || ty >= type_vocab) bad |= 2;
+    int l = labels[t];
+    if (l != -100) {
+      if (l < 0 || l >= vocab) bad |= 4;
+      ++c;
+    }
+    int a = am[t];
+    if (a != 0 && a != 1) bad |= 8;
+  }
+  sc[tid] = c;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int v = tid >= o ? sc[tid - o] : 0;
+    __syncthreads();
+    sc[tid] += v;
+    __syncthreads();
+  }
+  if (bad) atomicOr(&bad_all, bad);
+  int off = sc[tid] - c;
+  for (int t = b; t < e; ++t) {
+    int l = labels[t];
+    if (l != -100) {
+      if (off < cap) {
+        pos[off] = t;
+        lab[off] = l;
+        inv[t] = off;
+      } else {
+        inv[t] = -1;
+      }
+      ++off;
+    } else {
+      inv[t] = -1;
+    }
+  }
+  __syncthreads();
+  if (tid == 1023) {
+    counters[0] = sc[1023];
+    counters[1] = bad_all;
+  }
+}
+hipError_t batch_scan(const int32_t* ids, const int32_t* tt, const int32_t* am, const int32_t* labels, int T, int vocab,
+                      int type_vocab, int cap, int32_t* pos, int32_t* lab, int32_t* inv, int32_t* counters,
+                      hipStream_t s) {
+  k_batch_scan<<<dim3(1), dim3(1024), 0, s>>>(ids, tt, am, labels, T, vocab, type_vocab, cap, pos, lab, inv, counters);
+  return hipGetLastError();
+}
+
+// ---- LayerNorm forward on a row held in registers -------------------------------------------
+template <typename AT>
+__device__ inline void ln_row_finish(float4 (&z)[LN_MAXV], int H, int lane, const float* __restrict__ g,
+                                     const float* __restrict__ b, float eps, AT* __restrict__ out,
+                                     AT* __restrict__ xhat, float* __restrict__ rstd_out) {
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    int c = (i * 64 + lane) * 4;
+    if (c < H) sum += (z[i].x + z[i].y) + (z[i].z + z[i].w);
+  }
+  float mu = wave_sum(sum) / (float)H;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    int c = (i * 64 + lane) * 4;
+    if (c < H) {
+      z[i].x -= mu; z[i].y -= mu; z[i].z -= mu; z[i].w -= mu;
+      sq += (z[i].x * z[i].x + z[i].y * z[i].y) + (z[i].z * z[i].z + z[i].w * z[i].w);
+    }
+  }
+  float var = wave_sum(sq) / (float)H;
+  float rstd = 1.0f / sqrtf(var + eps);
+  if (rstd_out != nullptr && lane == 0) *rstd_out = rstd;
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    int c = (i * 64 + lane) * 4;
+    if (c < H) {
+      float4 xh = make_float4(z[i].x * rstd, z[i].y * rstd, z[i].z * rstd, z[i].w * rstd);
+      if (xhat != nullptr) store4(xhat + c, xh);
+      float4 gg = load4(g + c), bb = load4(b + c);
+      store4(out + c, make_float4(xh.x * gg.x + bb.x, xh.y * gg.y + bb.y, xh.z * gg.z + bb.z, xh.w * gg.w + bb.w));
+    }
+  }
+}
+
+template <typename AT>
+__global__ void __launch_bounds__(256) k_embed_ln(const int32_t* __restrict__ ids, const int32_t* __restrict__ tt, int S,
+                                                  const float* __restrict__ word, const float* __restrict__ pos,
+                                                  const float* __restrict__ type, const float* __restrict__ g,
+                                                  const float* __restrict__ b, float eps, AT* __restrict__ out,
+                                                  AT* __restrict__ xhat, float* __restrict__ rstd, int T, int H) {
+  int lane = threadIdx.x & 63;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const float* w = word + (size_t)ids[row] * H;
+  const float* p = pos + (size_t)(row % S) * H;
+  const float* ty = type + (size_t)tt[row] * H;
+  float4 z[LN_MAXV];
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    int c = (i * 64 + lane) * 4;
+    if (c < H) {
+      float4 a = load4(w + c), b2 = load4(p + c), c2 = load4(ty + c);
+      z[i] = make_float4(a.x + b2.x + c2.x, a.y + b2.y + c2.y, a.z + b2.z + c2.z, a.w + b2.w + c2.w);
+    }
+  }
+  ln_row_finish<AT>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
+                    rstd ? rstd + row : nullptr);
+}
+hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S, const float* word, const float* pos,
+                        const float* type, const float* g, const float* b, float eps, void* out, LnStash st, int T,
+                        int H, hipStream_t s) {
+  dim3 grid((T + 3) / 4), block(256);
+  if (dtype == 0)
+    k_embed_ln<float><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (float*)out, (float*)st.xhat,
+                                             st.rstd, T, H);
+  else
+    k_embed_ln<bf16><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (bf16*)out, (bf16*)st.xhat, st.rstd,
+                                            T, H);
+  return hipGetLastError();
+}
+
+template <typename AT>
+__global__ void __launch_bounds__(256) k_add_ln(const AT* __restrict__ a, const AT* __restrict__ r,
+                                                const float* __restrict__ g, const float* __restrict__ b, float eps,
+                                                AT* __restrict__ out, AT* __restrict__ xhat, float* __restrict__ rstd,
+                                                int rows, int H) {
+  int lane = threadIdx.x & 63;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const AT* pa = a + (size_t)row * H;
+  const AT* pr = r ? r + (size_t)row * H : nullptr;
+  float4 z[LN_MAXV];
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    int c = (i * 64 + lane) * 4;
+    if (c < H) {
+      float4 x = load4(pa + c);
+      if (pr) {
+        float4 y = load4(pr + c);
+        x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w;
+      }
+      z[i] = x;
+    }
+  }
+  ln_row_finish<AT>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
+                    rstd ? rstd + row : nullptr);
+}
+hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, const float* b, float eps, void* out,
+                      LnStash st, int rows, int H, hipStream_t s) {
+  dim3 grid((rows + 3) / 4), block(256);
+  if (dtype == 0)
+    k_add_ln<float><<<grid, block, 0, s>>>((const float*)a, (const float*)r, g, b, eps, (float*)out, (float*)st.xhat,
+                                           st.rstd, rows, H);
+  else
+    k_add_ln<bf16><<<grid, block, 0, s>>>((const bf16*)a, (const bf16*)r, g, b, eps, (bf16*)out, (bf16*)st.xhat,
+                                          st.rstd, rows, H);
+  return hipGetLastError();
+}
+
+// ---- column-sum finalisation: out[c] = sum over p of partial[p][c], fixed order -------------
+__global__ void k_colsum_final(const float* __restrict__ partial, int n_partials, int N, float* __restrict__ out) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= N) return;
+  float acc = 0.f;
+  for (int p = 0; p < n_partials; ++p) acc += partial[(size_t)p * N + c];
+  out[c] = acc;
+}
+
+// ---- LayerNorm backward ---------------------------------------------------------------------
+constexpr int LNB_ROWS_PER_WAVE = 8;
+constexpr int LNB_ROWS_PER_BLOCK = 4 * LNB_ROWS_PER_WAVE;
+size_t ln_bwd_scratch_floats(int rows, int H) {
+  return (size_t)2 * ((rows + LNB_ROWS_PER_BLOCK - 1) / LNB_ROWS_PER_BLOCK) * H;
+}
+
+template <typename AT>
+__global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const AT* __restrict__ xhat,
+                                                const float* __restrict__ rstd, const float* __restrict__ g,
+                                                AT* __restrict__ dz, float* __restrict__ part_g,
+                                                float* __restrict__ part_b, int rows, int H) {
+  __shared__ float red[3][64 * 4 * LN_MAXV];
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float4 gg[LN_MAXV], ag[LN_MAXV], ab[LN_MAXV];
+#pragma unroll
+  for (int i = 0; i < LN_MAXV; ++i) {
+    int c = (i * 64 + lane) * 4;
+    ag[i] = make_float4(0, 0, 0, 0);
+    ab[i] = make_float4(0, 0, 0, 0);
+    gg[i] = (c < H) ? load4(g + c) : make_float4(0, 0, 0, 0);
+  }
+  int row0 = blockIdx.x * LNB_ROWS_PER_BLOCK + wave * LNB_ROWS_PER_WAVE;
+  float invH = 1.0f / (float)H;
+  for (int rr = 0; rr < LNB_ROWS_PER_WAVE; ++rr) {
+    int row = row0 + rr;
+    if (row >= rows) break;
+    const AT* pdy = dy + (size_t)row * H;
+    const AT* pxh = xhat + (size_t)row * H;
+    float4 d[LN_MAXV], x[LN_MAXV];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+      int c = (i * 64 + lane) * 4;
+      if (c < H) {
+        float4 y = load4(pdy + c);
+        x[i] = load4(pxh + c);
+        ag[i].x += y.x * x[i].x; ag[i].y += y.y * x[i].y; ag[i].z += y.z * x[i].z; ag[i].w += y.w * x[i].w;
+        ab[i].x += y.x; ab[i].y += y.y; ab[i].z += y.z; ab[i].w += y.w;
+        d[i] = make_float4(y.x * gg[i].x, y.y * gg[i].y, y.z * gg[i].z, y.w * gg[i].w);
+        s1 += (d[i].x + d[i].y) + (d[i].z + d[i].w);
+        s2 += (d[i].x * x[i].x + d[i].y * x[i].y) + (d[i].z * x[i].z + d[i].w * x[i].w);
+      }
+    }
+    float m1 = wave_sum(s1) * invH, m2 = wave_sum(s2) * invH;
+    float rs = rstd[row];
+    AT* pdz = dz + (size_t)row * H;
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+      int c = (i * 64 + lane) * 4;
+      if (c < H)
+        store4(pdz + c, make_float4((d[i].x - m1 - x[i].x * m2) * rs, (d[i].y - m1 - x[i].y * m2) * rs,
+                                    (d[i].z - m1 - x[i].z * m2) * rs, (d[i].w - m1 - x[i].w * m2) * rs));
+    }
+  }
+  // cross-wave reduction of the per-column partial sums, waves added in order 0,1,2,3
+  for (int pass = 0; pass < 2; ++pass) {
+    float4* acc = pass == 0 ? ag : ab;
+    if (wave > 0) {
+#pragma unroll
+      for (int i = 0; i < LN_MAXV; ++i) {
+        int c = (i * 64 + lane) * 4;
+        if (c < H) *reinterpret_cast<float4*>(&red[wave - 1][c]) = acc[i];
+      }
+    }
+    __syncthreads();
+    if (wave == 0) {
+      float* dst = (pass == 0 ? part_g : part_b) + (size_t)blockIdx.x * H;
+#pragma unroll
+      for (int i = 0; i < LN_MAXV; ++i) {
+        int c = (i * 64 + lane) * 4;
+        if (c < H) {
+          float4 v = acc[i];
+          for (int w = 0; w < 3; ++w) {
+            float4 o = *reinterpret_cast<float4*>(&red[w][c]);
+            v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+          }
+          *reinterpret_cast<float4*>(dst + c) = v;
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
+                  float* db, float* scratch, int rows, int H, hipStream_t s) {
+  int nb = (rows + LNB_ROWS_PER_BLOCK - 1) / LNB_ROWS_PER_BLOCK;
+  float* pg = scratch;
+  float* pb = scratch + (size_t)nb * H;
+  if (dtype == 0)
+    k_ln_bwd<float><<<dim3(nb), dim3(256), 0, s>>>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, pg, pb,
+                                                   rows, H);
+  else
+    k_ln_bwd<bf16><<<dim3(nb), dim3(256), 0, s>>>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, pg, pb, rows,
+                                                  H);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_colsum_final<<<dim3((H + 255) / 256), dim3(256), 0, s>>>(pg, nb, H, dg);
+  k_colsum_final<<<dim3((H + 255) / 256), dim3(256), 0, s>>>(pb, nb, H, db);
+  return hipGetLastError();
+}
+
+// ---- column sums (bias gradients) -----------------------------------------------------------
+constexpr int CS_ROWS = 64;
+size_t colsum_scratch_floats(int rows, int N) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * N; }
+
+template <typename AT>
+__global__ void __launch_bounds__(256) k_colsum_partial(const AT* __restrict__ y, int ld, int rows, int N,
+                                                        float* __restrict__ partial) {
+  int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= N) return;
+  int r0 = blockIdx.y * CS_ROWS, r1 = min(rows, r0 + CS_ROWS);
+  float acc = 0.f;
+  for (int r = r0; r < r1; ++r) acc += ldf(y + (size_t)r * ld + c);
+  partial[(size_t)blockIdx.y * N + c] = acc;
+}
+hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s) {
+  int nchunks = (rows + CS_ROWS - 1) / CS_ROWS;
+  dim3 grid((N + 255) / 256, nchunks), block(256);
+  if (dtype == 0)
+    k_colsum_partial<float><<<grid, block, 0, s>>>((const float*)y, ld, rows, N, scratch);
+  else
+    k_colsum_partial<bf16><<<grid, block, 0, s>>>((const bf16*)y, ld, rows, N, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_colsum_final<<<dim3((N + 255) / 256), dim3(256), 0, s>>>(scratch, nchunks, N, out);
+  return hipGetLastError();
+}
+
+// ---- GELU backward (head only; the layers fuse it into the GEMM epilogue) -------------------
+template <typename AT>
+__global__ void k_mul_gelu_grad(const AT* __restrict__ dg, const AT* __restrict__ u, AT* __restrict__ du, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) stf(du + i, ldf(dg + i) * gelu_grad_f(ldf(u + i)));
+}
+hipError_t mul_gelu_grad(int dtype, const void* dg, const void* u, void* du, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (dtype == 0)
+    k_mul_gelu_grad<float><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const float*)dg, (const float*)u, (float*)du, n);
+  else
+    k_mul_gelu_grad<bf16><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const bf16*)dg, (const bf16*)u, (bf16*)du, n);
+  return hipGetLastError();
+}
+
+// ---- gather of predicted rows / scatter of their gradients ----------------------------------
+template <typename AT>
+__global__ void k_gather_rows(const AT* __restrict__ x, const int32_t* __restrict__ pos, int M, int H,
+                              AT* __restrict__ out) {
+  int j = blockIdx.x;
+  AT* o = out + (size_t)j * H;
+  if (j < M) {
+    const AT* src = x + (size_t)pos[j] * H;
+    for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) store4(o + c, load4(src + c));
+  } else {
+    for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) store4(o + c, make_float4(0, 0, 0, 0));
+  }
+}
+hipError_t gather_rows(int dtype, const void* x, const int32_t* pos, int M, int Mpad, int H, void* out, hipStream_t s) {
+  if (dtype == 0)
+    k_gather_rows<float><<<dim3(Mpad), dim3(64), 0, s>>>((const float*)x, pos, M, H, (float*)out);
+  else
+    k_gather_rows<bf16><<<dim3(Mpad), dim3(64), 0, s>>>((const bf16*)x, pos, M, H, (bf16*)out);
+  return hipGetLastError();
+}
+
+template <typename AT>
+__global__ void k_scatter_rows(const AT* __restrict__ dxm, const int32_t* __restrict__ inv, int T, int H,
+                               AT* __restrict__ out) {
+  int t = blockIdx.x;
+  int j = t < T ? inv[t] : -1;
+  AT* o = out + (size_t)t * H;
+  if (j >= 0) {
+    const AT* src = dxm + (size_t)j * H;
+    for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) store4(o + c, load4(src + c));
+  } else {
+    for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) store4(o + c, make_float4(0, 0, 0, 0));
+  }
+}
+hipError_t scatter_rows(int dtype, const void* dxm, const int32_t* inv, int rows_total, int T, int H, void* out,
+                        hipStream_t s) {
+  if (dtype == 0)
+    k_scatter_rows<float><<<dim3(rows_total), dim3(64), 0, s>>>((const float*)dxm, inv, T, H, (float*)out);
+  else
+    k_scatter_rows<bf16><<<dim3(rows_total), dim3(64), 0, s>>>((const bf16*)dxm, inv, T, H, (bf16*)out);
+  return hipGetLastError();
+}
+
+// ---- cross-entropy over the vocabulary ------------------------------------------------------
+__device__ inline float block_reduce_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+__device__ inline float block_reduce_max_256(float v, float* sh) {
+  v = wave_max(v);
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+
+template <typename AT>
+__global__ void __launch_bounds__(256) k_ce(const float* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
+                                            int M, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
+                                            float* __restrict__ lse_out) {
+  __shared__ float sh[4];
+  int j = blockIdx.x;
+  AT* d = dz + (size_t)j * ldz;
+  if (j >= M) {
+    for (int c = threadIdx.x; c < ldz; c += 256) stf(d + c, 0.f);
+    return;
+  }
+  const float* z = logits + (size_t)j * ldz;
+  float mx = -INFINITY;
+  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, z[c]);
+  mx = block_reduce_max_256(mx, sh);
+  float se = 0.f;
+  for (int c = threadIdx.x; c < V; c += 256) se += __expf(z[c] - mx);
+  se = block_reduce_sum_256(se, sh);
+  float lse = mx + __logf(se);
+  int y = lab[j];
+  float invM = 1.0f / (float)M;
+  for (int c = threadIdx.x; c < ldz; c += 256) {
+    float v = 0.f;
+    if (c < V) v = (__expf(z[c] - lse) - (c == y ? 1.0f : 0.0f)) * invM;
+    stf(d + c, v);
+  }
+  if (threadIdx.x == 0) {
+    row_loss[j] = lse - z[y];
+    lse_out[j] = lse;
+  }
+}
+__global__ void __launch_bounds__(256) k_mean_rows(const float* __restrict__ v, int M, float* __restrict__ out) {
+  __shared__ float sh[256];
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < M; i += 256) acc += v[i];
+  sh[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = sh[0] / (float)M;
+}
+hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mpad, int V, void* dz,
+                      float* row_loss, float* lse, float* loss_out, hipStream_t s) {
+  if (dtype == 0)
+    k_ce<float><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, V, (float*)dz, row_loss, lse);
+  else
+    k_ce<bf16><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, V, (bf16*)dz, row_loss, lse);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_mean_rows<<<dim3(1), dim3(256), 0, s>>>(row_loss, M, loss_out);
+  return hipGetLastError();
+}
+
+// ---- embedding backward (first stage and retraining only) -----------------------------------
+// Word rows: tokens are grouped by id with their original order kept inside a group (stable
+// rank by counting earlier equal ids), so each vocabulary row is summed by one workgroup in
+// ascending token order: deterministic, no floating-point atomics.
+__global__ void k_token_rank(const int32_t* __restrict__ ids, int T, int32_t* __restrict__ rank, int32_t* __restrict__ cnt) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  int id = ids[t];
+  int r = 0;
+  for (int u = 0; u < t; ++u) r += (ids[u] == id) ? 1 : 0;
+  rank[t] = r;
+  atomicAdd(&cnt[id], 1);
+}
+__global__ void __launch_bounds__(1024) k_exclusive_scan(const int32_t* __restrict__ cnt, int n, int32_t* __restrict__ start) {
+  __shared__ int sc[1024];
+  int tid = threadIdx.x;
+  int per = (n + 1023) / 1024;
+  int b = tid * per, e = min(n, b + per);
+  int c = 0;
+  for (int i = b; i < e; ++i) c += cnt[i];
+  sc[tid] = c;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int v = tid >= o ? sc[tid - o] : 0;
+    __syncthreads();
+    sc[tid] += v;
+    __syncthreads();
+  }
+  int off = sc[tid] - c;
+  for (int i = b; i < e; ++i) {
+    start[i] = off;
+    off += cnt[i];
+  }
+}
+__global__ void k_token_order(const int32_t* __restrict__ ids, const int32_t* __restrict__ rank,
+                              const int32_t* __restrict__ start, int T, int32_t* __restrict__ order) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  order[start[ids[t]] + rank[t]] = t;
+}
+template <typename AT>
+__global__ void __launch_bounds__(256) k_word_grad(const AT* __restrict__ dz, const int32_t* __restrict__ cnt,
+                                                   const int32_t* __restrict__ start, const int32_t* __restrict__ order,
+                                                   int H, float* __restrict__ gword) {
+  int v = blockIdx.x;
+  int n = cnt[v];
+  if (n == 0) return;
+  int s0 = start[v];
+  for (int c = threadIdx.x; c < H; c += 256) {
+    float acc = 0.f;
+    for (int i = 0; i < n; ++i) acc += ldf(dz + (size_t)order[s0 + i] * H + c);
+    gword[(size_t)v * H + c] += acc;
+  }
+}
+template <typename AT>
+__global__ void k_pos_grad(const AT* __restrict__ dz, int B, int S, int H, int rows_total, float* __restrict__ gpos) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows_total * H) return;
+  int s = (int)(i / H), c = (int)(i % H);
+  float acc = 0.f;
+  if (s < S)
+    for (int b = 0; b < B; ++b) acc += ldf(dz + ((size_t)b * S + s) * H + c);
+  gpos[i] = acc;
+}
+template <typename AT>
+__global__ void __launch_bounds__(256) k_type_partial(const AT* __restrict__ dz, const int32_t* __restrict__ tt, int T,
+                                                      int H, int type_vocab, float* __restrict__ partial) {
+  int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= H) return;
+  int r0 = blockIdx.y * CS_ROWS, r1 = min(T, r0 + CS_ROWS);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int r = r0; r < r1; ++r) {
+    float v = ldf(dz + (size_t)r * H + c);
+    int ty = tt[r];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] += (ty == k) ? v : 0.f;
+  }
+  for (int k = 0; k < type_vocab; ++k) partial[((size_t)blockIdx.y * type_vocab + k) * H + c] = acc[k];
+}
+template <typename AT>
+static hipError_t embed_bwd_t(const AT* dz, const int32_t* ids, const int32_t* tt, int B, int S, int H, int vocab,
+                              int type_vocab, float* gword, float* gpos, float* gtype, int32_t* rank, int32_t* cnt,
+                              int32_t* start, int32_t* order, int gpos_rows, float* scratch, hipStream_t s) {
+  int T = B * S;
+  hipError_t e = fill_zero(cnt, (size_t)((vocab + 3) / 4) * 16, s);
+  if (e != hipSuccess) return e;
+  k_token_rank<<<dim3((T + 255) / 256), dim3(256), 0, s>>>(ids, T, rank, cnt);
+  k_exclusive_scan<<<dim3(1), dim3(1024), 0, s>>>(cnt, vocab, start);
+  k_token_order<<<dim3((T + 255) / 256), dim3(256), 0, s>>>(ids, rank, start, T, order);
+  k_word_grad<AT><<<dim3(vocab), dim3(256), 0, s>>>(dz, cnt, start, order, H, gword);
+  size_t np = (size_t)gpos_rows * H;
+  k_pos_grad<AT><<<dim3((unsigned)((np + 255) / 256)), dim3(256), 0, s>>>(dz, B, S, H, gpos_rows, gpos);
+  int nchunks = (T + CS_ROWS - 1) / CS_ROWS;
+  k_type_partial<AT><<<dim3((H + 255) / 256, nchunks), dim3(256), 0, s>>>(dz, tt, T, H, type_vocab, scratch);
+  int N = type_vocab * H;
+  k_colsum_final<<<dim3((N + 255) / 256), dim3(256), 0, s>>>(scratch, nchunks, N, gtype);
+  return hipGetLastError();
+}
+hipError_t embed_bwd(int dtype, const void* dz, const int32_t* ids, const int32_t* tt, int B, int S, int H, int vocab,
+                     int type_vocab, float* gword, float* gpos, float* gtype, int32_t* rank, int32_t* cnt,
+                     int32_t* start, int32_t* order, int gpos_rows, float* scratch, hipStream_t s) {
+  if (dtype == 0)
+    return embed_bwd_t<float>((const float*)dz, ids, tt, B, S, H, vocab, type_vocab, gword, gpos, gtype, rank, cnt,
+                              start, order, gpos_rows, scratch, s);
+  return embed_bwd_t<bf16>((const bf16*)dz, ids, tt, B, S, H, vocab, type_vocab, gword, gpos, gtype, rank, cnt, start,
+                           order, gpos_rows, scratch, s);
+}
+
+// ---- fused multi-tensor Adam / LAMB ---------------------------------------------------------
+// One workgroup per chunk of OPT_CHUNK elements of one logical tensor.
+// Pass 1 updates the moments; Adam also applies the step.  LAMB leaves per-chunk sums of w^2 and
+// u^2, a second kernel adds them per tensor in chunk order, and pass 2 recomputes u from the new
+// moments and applies the step with the tensor's trust ratio.
+__global__ void k_bump_steps(int32_t* tsteps, int tensor0, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) tsteps[tensor0 + i] += 1;
+}
+hipError_t bump_steps(int32_t* tsteps, int tensor0, int n_tensors, hipStream_t s) {
+  if (n_tensors <= 0) return hipSuccess;
+  k_bump_steps<<<dim3((n_tensors + 63) / 64), dim3(64), 0, s>>>(tsteps, tensor0, n_tensors);
+  return hipGetLastError();
+}
+__device__ inline void opt_corrections(const OptHyper& h, int t, float& c1, float& c2) {
+  if (h.bias_correction) {
+    c1 = (float)(1.0 / (1.0 - pow((double)h.beta1, (double)t)));
+    c2 = (float)(1.0 / (1.0 - pow((double)h.beta2, (double)t)));
+  } else {
+    c1 = 1.f;
+    c2 = 1.f;
+  }
+}
+__global__ void __launch_bounds__(256) k_opt_pass1(OptHyper h, const OptTensor* __restrict__ tensors,
+                                                   const int32_t* __restrict__ tsteps,
+                                                   const int32_t* __restrict__ chunk_tensor, int chunk0,
+                                                   float* __restrict__ w, const float* __restrict__ g,
+                                                   float* __restrict__ m, float* __restrict__ v,
+                                                   bf16* __restrict__ shadow, float* __restrict__ chunk_norms) {
+  __shared__ float sh[4];
+  int chunk = chunk0 + blockIdx.x;
+  int ti = chunk_tensor[chunk];
+  OptTensor tn = tensors[ti];
+  size_t lo = (size_t)(chunk - tn.first_chunk) * OPT_CHUNK;
+  size_t hi = lo + OPT_CHUNK < tn.count ? lo + OPT_CHUNK : (size_t)tn.count;
+  float c1, c2;
+  opt_corrections(h, tsteps[ti], c1, c2);
+  float wd = tn.decays ? h.wd : 0.f;
+  float sw = 0.f, su = 0.f;
+  for (size_t i = lo + threadIdx.x; i < hi; i += 256) {
+    size_t a = tn.offset + i;
+    float gi = g[a], wi = w[a];
+    float mi = h.beta1 * m[a] + (1.f - h.beta1) * gi;
+    float vi = h.beta2 * v[a] + (1.f - h.beta2) * gi * gi;
+    m[a] = mi;
+    v[a] = vi;
+    float u = (mi * c1) / (sqrtf(vi * c2) + h.eps) + wd * wi;
+    if (h.kind == 0) {
+      wi -= h.lr * u;
+      w[a] = wi;
+      if (shadow) shadow[a] = f2bf(wi);
+    } else {
+      sw += wi * wi;
+      su += u * u;
+    }
+  }
+  if (h.kind != 0) {
+    sw = block_reduce_sum_256(sw, sh);
+    su = block_reduce_sum_256(su, sh);
+    if (threadIdx.x == 0) {
+      chunk_norms[2 * (size_t)chunk] = sw;
+      chunk_norms[2 * (size_t)chunk + 1] = su;
+    }
+  }
+}
+__global__ void k_lamb_ratio(const OptTensor* __restrict__ tensors, int tensor0, int n_tensors,
+                             const float* __restrict__ chunk_norms, float* __restrict__ ratio) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_tensors) return;
+  OptTensor tn = tensors[tensor0 + i];
+  float sw = 0.f, su = 0.f;
+  for (int c = 0; c < tn.n_chunks; ++c) {
+    sw += chunk_norms[2 * (size_t)(tn.first_chunk + c)];
+    su += chunk_norms[2 * (size_t)(tn.first_chunk + c) + 1];
+  }
+  float wn = sqrtf(sw), un = sqrtf(su);
+  ratio[tensor0 + i] = (wn > 0.f && un > 0.f) ? wn / un : 1.0f;
+}
+__global__ void __launch_bounds__(256) k_lamb_pass2(OptHyper h, const OptTensor* __restrict__ tensors,
+                                                    const int32_t* __restrict__ tsteps,
+                                                    const int32_t* __restrict__ chunk_tensor, int chunk0,
+                                                    float* __restrict__ w, const float* __restrict__ m,
+                                                    const float* __restrict__ v, bf16* __restrict__ shadow,
+                                                    const float* __restrict__ ratio) {
+  int chunk = chunk0 + blockIdx.x;
+  int ti = chunk_tensor[chunk];
+  OptTensor tn = tensors[ti];
+  size_t lo = (size_t)(chunk - tn.first_chunk) * OPT_CHUNK;
+  size_t hi = lo + OPT_CHUNK < tn.count ? lo + OPT_CHUNK : (size_t)tn.count;
+  float c1, c2;
+  opt_corrections(h, tsteps[ti], c1, c2);
+  float wd = tn.decays ? h.wd : 0.f;
+  float step = h.lr * ratio[ti];
+  for (size_t i = lo + threadIdx.x; i < hi; i += 256) {
+    size_t a = tn.offset + i;
+    float wi = w[a];
+    float u = (m[a] * c1) / (sqrtf(v[a] * c2) + h.eps) + wd * wi;
+    wi -= step * u;
+    w[a] = wi;
+    if (shadow) shadow[a] = f2bf(wi);
+  }
+}
+hipError_t optimizer_step(const OptHyper& h, const OptTensor* tensors, const int32_t* tsteps, int tensor0,
+                          int n_tensors, const int32_t* chunk_tensor, int chunk0, int n_chunks, float* w,
+                          const float* g, float* m, float* v, bf16* shadow, float* chunk_norms, float* ratio,
+                          hipStream_t s) {
+  if (n_chunks <= 0) return hipSuccess;
+  k_opt_pass1<<<dim3(n_chunks), dim3(256), 0, s>>>(h, tensors, tsteps, chunk_tensor, chunk0, w, g, m, v, shadow,
+                                                   chunk_norms);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || h.kind == 0) return e;
+  k_lamb_ratio<<<dim3((n_tensors + 63) / 64), dim3(64), 0, s>>>(tensors, tensor0, n_tensors, chunk_norms, ratio);
+  k_lamb_pass2<<<dim3(n_chunks), dim3(256), 0, s>>>(h, tensors, tsteps, chunk_tensor, chunk0, w, m, v, shadow, ratio);
+  return hipGetLastError();
+}
+
+}  // namespace mslt

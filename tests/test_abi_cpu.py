@@ -1,0 +1,69 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes and validates configurations."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2011_13635_amd import binding, synth
+
+
+def declared_symbols(repo_root):
+    text = open(os.path.join(repo_root, "include", "mslt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mslt_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    lib = binding.load_library()
+    names = declared_symbols(repo_root)
+    assert len(names) >= 15
+    assert sorted(binding.EXPORTS) == names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_query_sizes_scale_with_config():
+    tiny = binding.mslt_query_sizes(binding.make_config(synth.tiny_shape(), 4, 64, 0))
+    base = binding.mslt_query_sizes(binding.make_config(synth.bert_base_shape(), 64, 128, 1))
+    assert all(b > t > 0 for b, t in zip(base, tiny))
+    p, g, o, w = base
+    assert p == g and o == 2 * p
+    # 12-layer Base with head: about 110 M parameters in fp32 (+ padding of the vocabulary to 128 rows)
+    assert 109e6 * 4 < p < 111e6 * 4
+    assert p % 256 == 0 and w % 256 == 0
+
+
+@pytest.mark.parametrize("field,value", [("hidden", 130), ("hidden", 4096), ("n_heads", 5), ("precision", 2),
+                                         ("type_vocab", 9), ("max_seq", 1024), ("n_layers_max", 0), ("vocab", 1)])
+def test_bad_config_is_rejected(field, value):
+    cfg = binding.make_config(synth.tiny_shape(), 4, 64, 0)
+    setattr(cfg, field, value)
+    with pytest.raises(binding.MsltError) as ei:
+        binding.mslt_query_sizes(cfg)
+    assert ei.value.code == binding.MSLT_ERR_ARG
+    assert "config" in str(ei.value)
+
+
+def test_null_arguments_return_error_codes():
+    lib = binding.load_library()
+    assert lib.mslt_query_sizes(None, None, None, None, None) == binding.MSLT_ERR_ARG
+    assert lib.mslt_stage_step(None, 0, 1, 0, None, None) == binding.MSLT_ERR_ARG
+    assert lib.mslt_apply_update(None, None) == binding.MSLT_ERR_ARG
+    assert lib.mslt_get_grads(None, None, 0) == binding.MSLT_ERR_ARG
+    assert lib.mslt_load_params(None, None, 0) == binding.MSLT_ERR_ARG
+    assert lib.mslt_destroy(None) == 0
+    cfg = binding.make_config(synth.tiny_shape(), 4, 64, 0)
+    h = ctypes.c_void_p()
+    # null arenas are refused before any GPU call
+    assert lib.mslt_init_model(ctypes.byref(cfg), None, None, None, None, None, ctypes.byref(h)) == binding.MSLT_ERR_ARG
+    assert b"null" in lib.mslt_last_error()
+
+
+def test_model_needs_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        binding.Model(binding.make_config(synth.tiny_shape(), 4, 64, 0))
