@@ -1,6 +1,332 @@
-// placeholder, replaced below
+// bf16 MFMA GEMM for gfx950: C(m,n) = sum_k A(m,k) B(n,k), fp32 accumulation, shared epilogue.
+//
+// One 256-thread workgroup (4 wavefronts, 2x2) computes a 128x128 tile of C; each wavefront owns
+// a 64x64 quarter as 2x2 blocks of v_mfma_f32_32x32x16_bf16.  The k loop advances 64 at a time
+// through two LDS stages: while the matrix cores work on stage s, the next operand slabs travel
+// global -> registers -> LDS stage s^1.  Both operands sit in LDS as [128 rows][64 k] bf16 with
+// the 16-byte chunks of a row XOR-swizzled by the row index, so the 16-byte fragment reads of
+// the MFMA layout (lane = row, 8 consecutive k) are free of bank conflicts without padding.
+// An operand whose k index is the strided one in memory (the weight in dX = dY.W, both operands
+// in dW = dY^T.X) is transposed in registers on its way into LDS, so every product of the
+// training step runs through this one kernel.  The epilogue stages each wavefront's quarter in
+// LDS and writes 16-byte rows: bias, GELU (+ pre-activation store), GELU-derivative multiply or
+// residual add are fused there.  With split-k the tile's partial sums go to an fp32 workspace
+// and a second kernel adds the splits in a fixed order (deterministic, no atomics).
 #include "common.h"
+
 namespace mslt {
-bool gemm_mfma_supported(const GemmDesc&) { return false; }
-hipError_t gemm_mfma(const GemmDesc&, int, float*, hipStream_t) { return hipErrorNotSupported; }
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // first-class 16-byte register value
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int STAGE_ELEMS = (BM + BN) * BK;            // bf16 elements per pipeline stage
+constexpr int EPI_LD = 68;                             // floats per staged row of a wavefront quarter
+constexpr int LDS_BYTES_MAIN = 2 * STAGE_ELEMS * 2;    // 65536
+constexpr int LDS_BYTES_EPI = 4 * 64 * EPI_LD * 4;     // 69632
+constexpr int LDS_BYTES = LDS_BYTES_EPI > LDS_BYTES_MAIN ? LDS_BYTES_EPI : LDS_BYTES_MAIN;
+
+// 16-byte chunk swizzle of a 128-byte LDS row
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row >> 4) & 7); }
+
+struct MfmaParams {
+  const bf16* A;
+  const bf16* B;
+  int M, N, K;       // K = contraction length of this launch (all splits together)
+  int lda, ldb;
+  int splitk;
+  int tiles_m, tiles_n;
+  float* partials;   // [splitk][M][N] when splitk > 1
+  Epilogue epi;
+};
+
+// ---- global -> register slab loads ----------------------------------------------------------
+// Four 16-byte registers per thread and operand.  Named members (not an array) so that the
+// compiler keeps them in VGPRs across the MFMA block.
+struct Slab {
+  u32x4_t v0, v1, v2, v3;
+};
+
+// k-contiguous operand [rows][ld]: thread t takes 16-byte chunk t%8 of rows t/8 + 32p.
+// k-strided operand [k][ld]: thread takes 8 rows (16 bytes) of 4 consecutive k.
+template <bool KC>
+__device__ __forceinline__ void load_slab(const bf16* __restrict__ base, int ld, int row0, int k0, int tid, Slab& s) {
+  if constexpr (KC) {
+    const bf16* q = base + (size_t)(row0 + (tid >> 3)) * ld + k0 + 8 * (tid & 7);
+    size_t step = (size_t)32 * ld;
+    s.v0 = *reinterpret_cast<const u32x4_t*>(q);
+    s.v1 = *reinterpret_cast<const u32x4_t*>(q + step);
+    s.v2 = *reinterpret_cast<const u32x4_t*>(q + 2 * step);
+    s.v3 = *reinterpret_cast<const u32x4_t*>(q + 3 * step);
+  } else {
+    const bf16* q = base + (size_t)(k0 + 4 * (tid >> 4)) * ld + row0 + 8 * (tid & 15);
+    s.v0 = *reinterpret_cast<const u32x4_t*>(q);
+    s.v1 = *reinterpret_cast<const u32x4_t*>(q + ld);
+    s.v2 = *reinterpret_cast<const u32x4_t*>(q + 2 * (size_t)ld);
+    s.v3 = *reinterpret_cast<const u32x4_t*>(q + 3 * (size_t)ld);
+  }
 }
+
+__device__ __forceinline__ void put_row4(bf16* __restrict__ lds, int row, int kg, uint32_t a, uint32_t b, uint32_t c,
+                                         uint32_t d, uint32_t sel) {
+  u32x2_t o;
+  o.x = __builtin_amdgcn_perm(b, a, sel);
+  o.y = __builtin_amdgcn_perm(d, c, sel);
+  *reinterpret_cast<u32x2_t*>(lds + row * BK + 8 * ((kg >> 1) ^ swz(row)) + 4 * (kg & 1)) = o;
+}
+
+template <bool KC>
+__device__ __forceinline__ void store_slab(bf16* __restrict__ lds, int tid, const Slab& s) {
+  if constexpr (KC) {
+    int c = tid & 7, r = tid >> 3;
+    *reinterpret_cast<u32x4_t*>(lds + r * BK + 8 * (c ^ swz(r))) = s.v0;
+    *reinterpret_cast<u32x4_t*>(lds + (r + 32) * BK + 8 * (c ^ swz(r + 32))) = s.v1;
+    *reinterpret_cast<u32x4_t*>(lds + (r + 64) * BK + 8 * (c ^ swz(r + 64))) = s.v2;
+    *reinterpret_cast<u32x4_t*>(lds + (r + 96) * BK + 8 * (c ^ swz(r + 96))) = s.v3;
+  } else {
+    // row 8cg+j gets its four k values: the low (even j) or high (odd j) halves of word j/2
+    int cg = tid & 15, kg = tid >> 4, r = 8 * cg;
+    const uint32_t LO = 0x05040100u, HI = 0x07060302u;
+    put_row4(lds, r + 0, kg, s.v0.x, s.v1.x, s.v2.x, s.v3.x, LO);
+    put_row4(lds, r + 1, kg, s.v0.x, s.v1.x, s.v2.x, s.v3.x, HI);
+    put_row4(lds, r + 2, kg, s.v0.y, s.v1.y, s.v2.y, s.v3.y, LO);
+    put_row4(lds, r + 3, kg, s.v0.y, s.v1.y, s.v2.y, s.v3.y, HI);
+    put_row4(lds, r + 4, kg, s.v0.z, s.v1.z, s.v2.z, s.v3.z, LO);
+    put_row4(lds, r + 5, kg, s.v0.z, s.v1.z, s.v2.z, s.v3.z, HI);
+    put_row4(lds, r + 6, kg, s.v0.w, s.v1.w, s.v2.w, s.v3.w, LO);
+    put_row4(lds, r + 7, kg, s.v0.w, s.v1.w, s.v2.w, s.v3.w, HI);
+  }
+}
+
+__device__ __forceinline__ bf16x8_t lds_frag(const bf16* __restrict__ lds, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8_t*>(lds + row * BK + 8 * (chunk ^ swz(row)));
+}
+
+// ---- epilogue on 8 consecutive columns ------------------------------------------------------
+__device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(&u);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = __uint_as_float(w[i] << 16);
+    f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  uint4 u;
+  uint32_t* w = reinterpret_cast<uint32_t*>(&u);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(f[2 * i]).x | ((uint32_t)f2bf(f[2 * i + 1]).x << 16);
+  return u;
+}
+__device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float (&v)[8], const float (&bias)[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] += bias[i];
+  size_t o = (size_t)m * e.ldo + n;
+  if (e.act == EPI_GELU) {
+    if (e.out2) *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(e.out2) + o) = pack8(v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = gelu_f(v[i]);
+  } else if (e.act == EPI_MUL_GELU_GRAD) {
+    float u[8];
+    unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n), u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_f(u[i]);
+  } else if (e.act == EPI_ADD) {
+    float u[8];
+    unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n), u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += u[i];
+  }
+  if (e.out_f32) {
+    float* p = reinterpret_cast<float*>(e.out) + o;
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(e.out) + o) = pack8(v);
+  }
+}
+
+// ---- the kernel -----------------------------------------------------------------------------
+template <bool A_KC, bool B_KC>
+__global__ void __launch_bounds__(256, 2) k_gemm_mfma(MfmaParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* lds = reinterpret_cast<bf16*>(smem);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // workgroup -> (split, tile): consecutive ids go round-robin to the 8 XCDs, so give each XCD a
+  // contiguous range of tiles (row-major over the tile grid) to keep its L2 working set small
+  const int total = p.tiles_m * p.tiles_n * p.splitk;
+  int pid = blockIdx.x;
+  {
+    int per = (total + 7) >> 3, tall = total & 7;
+    if (tall == 0) tall = 8;
+    int xcd = pid & 7, local = pid >> 3;
+    pid = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+  }
+  const int tiles = p.tiles_m * p.tiles_n;
+  const int split = pid / tiles;
+  const int tile = pid - split * tiles;
+  const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int kper = p.K / p.splitk;
+  const int kbeg = split * kper;
+  const int nk = kper / BK;
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  Slab ra, rb;
+  load_slab<A_KC>(p.A, p.lda, m0, kbeg, tid, ra);
+  load_slab<B_KC>(p.B, p.ldb, n0, kbeg, tid, rb);
+  store_slab<A_KC>(lds, tid, ra);
+  store_slab<B_KC>(lds + BM * BK, tid, rb);
+  __syncthreads();
+
+  const int arow = 64 * wm + (lane & 31), brow = 64 * wn + (lane & 31), half = lane >> 5;
+  for (int kt = 0; kt < nk; ++kt) {
+    const bf16* sa = lds + (kt & 1) * STAGE_ELEMS;
+    const bf16* sb = sa + BM * BK;
+    if (kt + 1 < nk) {
+      load_slab<A_KC>(p.A, p.lda, m0, kbeg + (kt + 1) * BK, tid, ra);
+      load_slab<B_KC>(p.B, p.ldb, n0, kbeg + (kt + 1) * BK, tid, rb);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8_t fa0 = lds_frag(sa, arow, 2 * ks + half);
+      bf16x8_t fa1 = lds_frag(sa, arow + 32, 2 * ks + half);
+      bf16x8_t fb0 = lds_frag(sb, brow, 2 * ks + half);
+      bf16x8_t fb1 = lds_frag(sb, brow + 32, 2 * ks + half);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb1, acc[1][1], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      bf16* da = lds + ((kt + 1) & 1) * STAGE_ELEMS;
+      store_slab<A_KC>(da, tid, ra);
+      store_slab<B_KC>(da + BM * BK, tid, rb);
+    }
+    __syncthreads();
+  }
+
+  // stage this wavefront's 64x64 quarter in LDS (all operand reads are behind the last barrier)
+  float* stage = reinterpret_cast<float*>(smem) + wave * 64 * EPI_LD;
+#pragma unroll
+  for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int row = 32 * bi + 8 * (r >> 2) + 4 * half + (r & 3);
+        stage[row * EPI_LD + 32 * bj + (lane & 31)] = acc[bi][bj][r];
+      }
+  __syncthreads();
+
+  const int cc = 8 * (lane & 7);
+  const int n = n0 + 64 * wn + cc;
+  Epilogue e = p.epi;
+  float bias[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) bias[i] = 0.f;
+  if (p.splitk > 1) {
+    e = Epilogue();
+    e.out = p.partials + (size_t)split * p.M * p.N;
+    e.ldo = p.N;
+    e.out_f32 = 1;
+  } else if (e.bias) {
+    float4 b0 = *reinterpret_cast<const float4*>(e.bias + n), b1 = *reinterpret_cast<const float4*>(e.bias + n + 4);
+    bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
+    bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    int row = 8 * i + (lane >> 3);
+    float4 x0 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc);
+    float4 x1 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc + 4);
+    float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+    epilogue8(e, m0 + 64 * wm + row, n, v, bias);
+  }
+}
+
+// sums the split-k partials in split order and applies the epilogue; 8 columns per thread
+__global__ void __launch_bounds__(256) k_splitk_reduce(const float* __restrict__ partials, int splitk, int M, int N,
+                                                       Epilogue e) {
+  size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (idx >= (size_t)M * N) return;
+  int m = (int)(idx / N), n = (int)(idx % N);
+  float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int s = 0; s < splitk; ++s) {
+    const float* q = partials + (size_t)s * M * N + idx;
+    float4 a = *reinterpret_cast<const float4*>(q), b = *reinterpret_cast<const float4*>(q + 4);
+    v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+    v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+  }
+  float bias[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (e.bias) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bias[i] = e.bias[n + i];
+  }
+  epilogue8(e, m, n, v, bias);
+}
+
+bool gemm_mfma_supported(const GemmDesc& d) {
+  if (d.M <= 0 || d.N <= 0 || d.K <= 0) return false;
+  if (d.M % BM || d.N % BN || d.K % BK) return false;
+  if (d.lda % 8 || d.ldb % 8 || d.epi.ldo % 8) return false;
+  if ((d.epi.act == EPI_MUL_GELU_GRAD || d.epi.act == EPI_ADD) && d.epi.ldaux % 8) return false;
+  auto al = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+  if (!al(d.A) || !al(d.B) || !al(d.epi.out) || !al(d.epi.out2) || !al(d.epi.aux) || !al(d.epi.bias)) return false;
+  return true;
+}
+
+hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s) {
+  if (!gemm_mfma_supported(d)) return hipErrorInvalidValue;
+  if (splitk < 1 || d.K % (splitk * BK) != 0) return hipErrorInvalidValue;
+  if (splitk > 1 && partials == nullptr) return hipErrorInvalidValue;
+  MfmaParams p;
+  p.A = reinterpret_cast<const bf16*>(d.A);
+  p.B = reinterpret_cast<const bf16*>(d.B);
+  p.M = d.M; p.N = d.N; p.K = d.K;
+  p.lda = d.lda; p.ldb = d.ldb;
+  p.splitk = splitk;
+  p.tiles_m = d.M / BM; p.tiles_n = d.N / BN;
+  p.partials = partials;
+  p.epi = d.epi;
+  dim3 grid((unsigned)(p.tiles_m * p.tiles_n * splitk)), block(256);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_mfma<true, true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_mfma<true, false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_mfma<false, true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_mfma<false, false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES)) != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (d.a_kcontig && d.b_kcontig)
+    k_gemm_mfma<true, true><<<grid, block, LDS_BYTES, s>>>(p);
+  else if (d.a_kcontig && !d.b_kcontig)
+    k_gemm_mfma<true, false><<<grid, block, LDS_BYTES, s>>>(p);
+  else if (!d.a_kcontig && d.b_kcontig)
+    k_gemm_mfma<false, true><<<grid, block, LDS_BYTES, s>>>(p);
+  else
+    k_gemm_mfma<false, false><<<grid, block, LDS_BYTES, s>>>(p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splitk == 1) return e;
+  size_t n8 = (size_t)d.M * d.N / 8;
+  k_splitk_reduce<<<dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s>>>(partials, splitk, d.M, d.N, d.epi);
+  return hipGetLastError();
+}
+
+}  // namespace mslt
