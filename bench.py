@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of one MSLT stage step (stage_step + apply_update) on one MI355X.
+
+Workload (default): BERT-Base, stage 2 of the schedule: 6 encoder layers present, the bottom 3
+frozen (forward only), the top 3 and the masked-LM head trainable, batch 64 x sequence 128,
+bf16 compute with fp32 master weights, Adam.  Inputs are seeded and synthetic (Zipf token ids,
+15 % masking, N(0, 0.02) weights); they are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is tokens/s of the whole step.  `roofline` covers the dominant
+kernel, the bf16 MFMA GEMM: algorithmic FLOPs of all its launches in a step divided by their
+summed duration, measured with HIP events on the library's stream in a second pass over the same
+steps directly after the timed region (event recording would disturb the step timing itself).
+`cpu_baseline` times the float64 numpy oracle on the host cores on one step of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU, dense
+PEAK_HBM_GBS = 8000.0
+
+
+def run_steps(model, cbatches, f, k, emb, opt, n):
+    loss = None
+    for i in range(n):
+        loss = model.mslt_stage_step(f, k, emb, cbatches[i % len(cbatches)])
+        model.mslt_apply_update(opt)
+    return loss
+
+
+def time_steps(torch, model, cbatches, f, k, emb, opt, steps, warmup):
+    run_steps(model, cbatches, f, k, emb, opt, warmup)
+    model.mslt_sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    loss = run_steps(model, cbatches, f, k, emb, opt, steps)
+    model.mslt_sync()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt / steps, loss
+
+
+def profile_steps(model, cbatches, f, k, emb, opt, steps):
+    model.mslt_profile_enable(True)
+    run_steps(model, cbatches, f, k, emb, opt, steps)
+    prof = model.mslt_profile_read()
+    model.mslt_profile_enable(False)
+    for v in prof.values():
+        for key in ("launches", "ms", "flops", "bytes"):
+            v[key] = v[key] / steps
+    return prof
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-compare", action="store_true", help="skip the final-stage vs full-step comparison")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2011_13635_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        return 2
+
+    B, S = 64, 128
+    f, k = 3, 3
+    shape = synth.bert_base_shape(6)
+    W = synth.make_weights(shape, seed=0)
+    batches = [synth.make_batch(shape, B, S, seed=1 + i) for i in range(4)]
+    n_pred = max(len(b["masked_positions"]) for b in batches)
+    model = binding.Model(binding.make_config(shape, B, S, 1, max_predictions=n_pred + 64))
+    model.mslt_load_params(synth.pack_weights(shape, W))
+    cb = [model.device_batch(b) for b in batches]
+    opt = binding.adam(lr=1e-4)
+
+    sec, loss = time_steps(torch, model, cb, f, k, False, opt, args.steps, args.warmup)
+    tokens = B * S
+    prof = profile_steps(model, cb, f, k, False, opt, min(args.steps, 20))
+
+    gemm = [v for n, v in prof.items() if n.startswith("gemm_mfma")]
+    g_flops = sum(v["flops"] for v in gemm)
+    g_ms = sum(v["ms"] for v in gemm)
+    g_launch = sum(v["launches"] for v in gemm)
+    achieved = g_flops / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    classes = {}
+    for n, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
+        e = {"ms": round(v["ms"], 4), "launches": round(v["launches"], 1)}
+        if v["flops"] > 0 and n.startswith(("gemm", "attention")):
+            e["TFLOP/s"] = round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1)
+        if v["bytes"] > 0:
+            e["GB/s"] = round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1)
+        classes[n] = e
+
+    out = {
+        "metric": "MSLT stage-step tokens/sec at BERT-Base/Large; MFMA util % vs bf16 peak",
+        "value": round(tokens / sec, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "BERT-Base MSLT stage 2: 6 layers, bottom 3 frozen, top 3 + MLM head trainable, "
+                               "batch 64 x seq 128, Adam, bf16 with fp32 master", "frozen_layers": f,
+                   "trainable_layers": k, "batch": B, "seq_len": S, "tokens_per_step": tokens,
+                   "predicted_per_step": int(len(batches[0]["masked_positions"])), "loss": round(float(loss), 5)},
+        "roofline": {"bound": "mfma", "kernel": "k_gemm_mfma (all layouts)", "achieved": round(achieved, 1),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "launches_per_step": round(g_launch, 1),
+                     "avg_launch_us": round(g_ms * 1e3 / max(g_launch, 1), 2),
+                     "gemm_ms_per_step": round(g_ms, 4), "gemm_gflop_per_step": round(g_flops / 1e9, 1)},
+        "kernel_classes": classes,
+        "profiled_ms_per_step": round(sum(v["ms"] for v in prof.values()), 4),
+    }
+    model.close()
+    del model
+    torch.cuda.empty_cache()
+
+    if not args.no_compare:
+        # final stage of the Base schedule (9 frozen + 3 trainable) against the same kernels with all 12
+        # layers and the embeddings trainable (the retraining step)
+        shape12 = synth.bert_base_shape(12)
+        W12 = synth.make_weights(shape12, seed=0)
+        m12 = binding.Model(binding.make_config(shape12, B, S, 1, max_predictions=n_pred + 64))
+        m12.mslt_load_params(synth.pack_weights(shape12, W12))
+        cb12 = [m12.device_batch(b) for b in batches]
+        n_cmp = max(5, min(args.steps, 20))
+        sec_stage, _ = time_steps(torch, m12, cb12, 9, 3, False, opt, n_cmp, 3)
+        sec_full, _ = time_steps(torch, m12, cb12, 0, 12, True, opt, n_cmp, 3)
+        out["final_stage_vs_full"] = {"workload": "BERT-Base 12 layers, batch 64 x seq 128",
+                                      "mslt_9_frozen_3_trainable_ms": round(sec_stage * 1e3, 4),
+                                      "full_12_trainable_ms": round(sec_full * 1e3, 4),
+                                      "mslt_tokens_per_s": round(tokens / sec_stage, 1),
+                                      "full_tokens_per_s": round(tokens / sec_full, 1),
+                                      "speedup": round(sec_full / sec_stage, 3)}
+        m12.close()
+
+    if not args.no_cpu_baseline:
+        from oracle import mslt_oracle as O
+        threads = len(os.sched_getaffinity(0))
+        try:
+            from threadpoolctl import threadpool_info
+            blas = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+            if blas:
+                threads = max(blas)
+        except Exception:
+            pass
+        t0 = time.perf_counter()
+        ref_loss, ref_g, _ = O.stage_step(shape, W, batches[0], f, k, False)
+        st = O.new_opt_state(O.to_f64({n: W[n] for n in ref_g}))
+        O.optimizer_update({n: W[n] for n in ref_g}, ref_g, st, kind="adam", lr=1e-4)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(tokens / dt, 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                               "sample": "one full stage step + Adam update of the same workload "
+                                         f"(batch 64 x seq 128, {tokens} tokens), float64 numpy",
+                               "seconds": round(dt, 2), "oracle_loss": round(float(ref_loss), 5)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

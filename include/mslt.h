@@ -156,6 +156,20 @@ int mslt_debug_prefix_output(const mslt_model* m, float* host_fp32_out, size_t n
  * zeroed and their step counts reset.  Enqueues work only. */
 int mslt_grow(mslt_model* m, int n_present, int n_new);
 
+/* Measurement aid (Section 4 reports wall-clock time only; this gives the per-kernel view).
+ * While enabled, every group of launches of one kernel class is bracketed by two HIP events on
+ * the model's stream.  mslt_profile_read() waits for the stream, adds up per class the elapsed
+ * time, launch groups, algorithmic FLOPs and algorithmic HBM bytes since the last read into
+ * `out` (HOST array of at least 16 entries; *n = entries written) and clears the record.
+ * Event recording costs a few microseconds per launch: keep it off when timing whole steps. */
+typedef struct {
+  char name[24];
+  int launches;
+  double ms, flops, bytes;
+} mslt_profile_entry;
+int mslt_profile_enable(mslt_model* m, int on);
+int mslt_profile_read(mslt_model* m, mslt_profile_entry* out, int cap, int* n);
+
 /* Waits until all work enqueued on the model's stream has finished. */
 int mslt_sync(const mslt_model* m);
 

@@ -17,6 +17,7 @@ EXPORTS = [
     "mslt_query_sizes", "mslt_init_model", "mslt_tensor_table", "mslt_load_params", "mslt_get_params",
     "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_debug_masked",
     "mslt_debug_prefix_output", "mslt_grow", "mslt_sync", "mslt_destroy", "mslt_last_error",
+    "mslt_profile_enable", "mslt_profile_read",
 ]
 
 MSLT_OK, MSLT_ERR_ARG, MSLT_ERR_STATE, MSLT_ERR_DATA, MSLT_ERR_HIP, MSLT_ERR_NONFINITE = 0, -1, -2, -3, -4, -5
@@ -50,6 +51,11 @@ class TensorDesc(C.Structure):
                 ("decays", C.c_int), ("offset", C.c_size_t), ("count", C.c_size_t)]
 
 
+class ProfileEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 24), ("launches", C.c_int), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
 _lib = None
 
 
@@ -75,6 +81,8 @@ def load_library():
     lib.mslt_debug_masked.argtypes = [vp, vp, vp, P(C.c_int)]
     lib.mslt_debug_prefix_output.argtypes = [vp, vp, sz]
     lib.mslt_grow.argtypes = [vp, C.c_int, C.c_int]
+    lib.mslt_profile_enable.argtypes = [vp, C.c_int]
+    lib.mslt_profile_read.argtypes = [vp, P(ProfileEntry), C.c_int, P(C.c_int)]
     lib.mslt_sync.argtypes = [vp]
     lib.mslt_destroy.argtypes = [vp]
     lib.mslt_last_error.argtypes = []
@@ -198,6 +206,17 @@ class Model:
 
     def mslt_grow(self, n_present, n_new):
         _check(self.lib.mslt_grow(self.handle, n_present, n_new))
+
+    def mslt_profile_enable(self, on: bool):
+        _check(self.lib.mslt_profile_enable(self.handle, int(on)))
+
+    def mslt_profile_read(self):
+        """Per kernel class since the last read: {name: dict(launches, ms, flops, bytes)} (classes that ran)."""
+        buf = (ProfileEntry * 16)()
+        n = C.c_int()
+        _check(self.lib.mslt_profile_read(self.handle, buf, 16, C.byref(n)))
+        return {buf[i].name.decode(): {"launches": buf[i].launches, "ms": buf[i].ms, "flops": buf[i].flops,
+                                       "bytes": buf[i].bytes} for i in range(n.value) if buf[i].launches}
 
     def mslt_sync(self):
         _check(self.lib.mslt_sync(self.handle))

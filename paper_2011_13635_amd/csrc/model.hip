@@ -37,6 +37,29 @@ enum { T_WORD = 0, T_POS, T_TYPE, T_ELN_G, T_ELN_B, N_EMB };
 enum { L_WQ = 0, L_WK, L_WV, L_BQ, L_BK, L_BV, L_WO, L_BO, L_LN1G, L_LN1B, L_W1, L_B1, L_W2, L_B2, L_LN2G, L_LN2B, N_LAYER_T };
 enum { H_WT = 0, H_BT, H_LNG, H_LNB, H_BOUT, N_HEAD };
 
+// Optional per-kernel-class timing with HIP events on the model's stream (off by default).
+enum ProfClass { PC_GEMM_NT = 0, PC_GEMM_NN, PC_GEMM_TN, PC_GEMM_SIMT, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD, PC_LN_BWD,
+                 PC_COLSUM, PC_EMBED, PC_HEAD_MISC, PC_CE, PC_EMBED_BWD, PC_OPT, PC_COUNT };
+static const char* kProfNames[PC_COUNT] = {"gemm_mfma_nt", "gemm_mfma_nn", "gemm_mfma_tn", "gemm_simt", "attention_fwd",
+                                           "attention_bwd", "layernorm_fwd", "layernorm_bwd", "bias_colsum", "embed_fwd",
+                                           "head_gather_scatter", "cross_entropy", "embed_bwd", "optimizer"};
+struct ProfSpan {
+  hipEvent_t a, b;
+  int cls;
+  double flops, bytes;
+};
+struct Profiler {
+  bool on = false;
+  std::vector<ProfSpan> spans;    // spans of the steps since the last read
+  std::vector<hipEvent_t> pool;   // recycled events
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    hipEventCreate(&e);
+    return e;
+  }
+};
+
 struct LayerStash {
   void *xout, *qkv, *ctx, *xhat1, *x1, *u, *g, *xhat2;
   float *lse, *rstd1, *rstd2;
@@ -77,6 +100,7 @@ struct mslt_model {
   bool have_grads;
   int last_f, last_k, last_emb, last_B, last_S, last_M;
   const void* last_prefix;
+  Profiler prof;
 };
 
 // ---- tensor table ---------------------------------------------------------------------------
@@ -150,6 +174,22 @@ static inline float* Gf(const mslt_model* m, int t) { return m->grad + m->table[
 static inline const void* Wg(const mslt_model* m, int t) {
   return m->dtype ? (const void*)(m->shadow + m->table[t].offset) : (const void*)(m->param + m->table[t].offset);
 }
+
+struct ProfScope {   // brackets the launches of one kernel class with two events
+  mslt_model* m;
+  ProfSpan sp;
+  bool active;
+  ProfScope(mslt_model* m_, int cls, double flops, double bytes) : m(m_), active(m_->prof.on) {
+    if (!active) return;
+    sp.a = m->prof.get(); sp.b = m->prof.get(); sp.cls = cls; sp.flops = flops; sp.bytes = bytes;
+    hipEventRecord(sp.a, m->stream);
+  }
+  ~ProfScope() {
+    if (!active) return;
+    hipEventRecord(sp.b, m->stream);
+    m->prof.spans.push_back(sp);
+  }
+};
 
 // ---- workspace ------------------------------------------------------------------------------
 struct Bump {
@@ -320,6 +360,8 @@ extern "C" int mslt_destroy(mslt_model* m) {
   if (!m) return MSLT_OK;
   hipStreamSynchronize(m->stream);
   if (m->h_counters) hipHostFree(m->h_counters);
+  for (auto& sp : m->prof.spans) { hipEventDestroy(sp.a); hipEventDestroy(sp.b); }
+  for (auto e : m->prof.pool) hipEventDestroy(e);
   delete m;
   return MSLT_OK;
 }
@@ -383,7 +425,11 @@ static int pick_splitk(int M, int N, int K) {
   return s;
 }
 static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false) {
-  if (m->mfma && gemm_mfma_supported(d)) {
+  const bool use_mfma = m->mfma && gemm_mfma_supported(d);
+  const double out_esz = d.epi.out_f32 ? 4.0 : (double)m->esz;
+  ProfScope ps(m, !use_mfma ? PC_GEMM_SIMT : (d.a_kcontig ? (d.b_kcontig ? PC_GEMM_NT : PC_GEMM_NN) : PC_GEMM_TN),
+               2.0 * d.M * d.N * d.K, ((double)d.M * d.K + (double)d.N * d.K) * m->esz + (double)d.M * d.N * out_esz);
+  if (use_mfma) {
     int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
     while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
     HIP_TRY(gemm_mfma(d, sk, m->splitk, m->stream));
@@ -425,6 +471,13 @@ static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int
   return run_gemm(m, d, true);
 }
 
+static int ln_forward(mslt_model* m, const void* a, const void* r, const float* g, const float* b, void* out, LnStash st,
+                      int rows) {
+  ProfScope ps(m, PC_LN_FWD, 0.0, (double)rows * m->H * m->esz * (2.0 + (r ? 1.0 : 0.0) + (st.xhat ? 1.0 : 0.0)));
+  HIP_TRY(add_ln_fwd(m->dtype, a, r, g, b, m->cfg.ln_eps, out, st, rows, m->H, m->stream));
+  return MSLT_OK;
+}
+
 // ---- one encoder layer ----------------------------------------------------------------------
 static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, const void* Xin, void* Xout,
                          const LayerStash* st) {
@@ -435,24 +488,33 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
   void* g = st ? st->g : m->s_g;
   RC(linear_fwd(m, Xin, Tr, H, Wg(m, t_layer(l, L_WQ)), 3 * H, Wf(m, t_layer(l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr));
   AttnDesc a{qkv, ctx, st ? st->lse : nullptr, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh, m->cfg.mask_bias};
-  if (m->dtype == 1 && attention_mfma_supported(bt->seq, m->dh))
-    HIP_TRY(attention_fwd_mfma(a, m->stream));
-  else
-    HIP_TRY(attention_fwd_simple(m->dtype, a, m->stream));
+  {
+    const double TS = (double)bt->batch * bt->seq;
+    ProfScope ps(m, PC_ATTN_FWD, 4.0 * TS * bt->seq * H, 4.0 * TS * H * m->esz);
+    if (m->dtype == 1 && attention_mfma_supported(bt->seq, m->dh))
+      HIP_TRY(attention_fwd_mfma(a, m->stream));
+    else
+      HIP_TRY(attention_fwd_simple(m->dtype, a, m->stream));
+  }
   RC(linear_fwd(m, ctx, Tr, H, Wg(m, t_layer(l, L_WO)), H, Wf(m, t_layer(l, L_BO)), m->s_y, 0, H, EPI_NONE, nullptr));
   LnStash s1, s2;
   if (st) { s1.xhat = st->xhat1; s1.rstd = st->rstd1; s2.xhat = st->xhat2; s2.rstd = st->rstd2; }
-  HIP_TRY(add_ln_fwd(m->dtype, m->s_y, Xin, Wf(m, t_layer(l, L_LN1G)), Wf(m, t_layer(l, L_LN1B)), m->cfg.ln_eps, x1, s1,
-                     Tr, H, m->stream));
+  RC(ln_forward(m, m->s_y, Xin, Wf(m, t_layer(l, L_LN1G)), Wf(m, t_layer(l, L_LN1B)), x1, s1, Tr));
   RC(linear_fwd(m, x1, Tr, H, Wg(m, t_layer(l, L_W1)), F, Wf(m, t_layer(l, L_B1)), g, 0, F, EPI_GELU, st ? st->u : nullptr));
   RC(linear_fwd(m, g, Tr, F, Wg(m, t_layer(l, L_W2)), H, Wf(m, t_layer(l, L_B2)), m->s_y, 0, H, EPI_NONE, nullptr));
-  HIP_TRY(add_ln_fwd(m->dtype, m->s_y, x1, Wf(m, t_layer(l, L_LN2G)), Wf(m, t_layer(l, L_LN2B)), m->cfg.ln_eps, Xout, s2,
-                     Tr, H, m->stream));
+  RC(ln_forward(m, m->s_y, x1, Wf(m, t_layer(l, L_LN2G)), Wf(m, t_layer(l, L_LN2B)), Xout, s2, Tr));
   return MSLT_OK;
 }
 
 static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, float* out) {
+  ProfScope ps(m, PC_COLSUM, (double)rows * N, (double)rows * N * m->esz);
   HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, m->red_scratch, m->stream));
+  return MSLT_OK;
+}
+static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz,
+                       float* dg, float* db, int rows) {
+  ProfScope ps(m, PC_LN_BWD, 0.0, 3.0 * rows * m->H * m->esz);
+  HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, m->red_scratch, rows, m->H, m->stream));
   return MSLT_OK;
 }
 
@@ -463,27 +525,31 @@ static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int
   const int H = m->H, F = m->F;
   const LayerStash& st = m->stash[l];
   hipStream_t s = m->stream;
-  HIP_TRY(ln_bwd(m->dtype, dXout, st.xhat2, st.rstd2, Wf(m, t_layer(l, L_LN2G)), m->d_d, Gf(m, t_layer(l, L_LN2G)),
-                 Gf(m, t_layer(l, L_LN2B)), m->red_scratch, Tr, H, s));
+  RC(ln_backward(m, dXout, st.xhat2, st.rstd2, Wf(m, t_layer(l, L_LN2G)), m->d_d, Gf(m, t_layer(l, L_LN2G)),
+                 Gf(m, t_layer(l, L_LN2B)), Tr));
   RC(linear_bwd_weight(m, m->d_d, Tr, H, H, st.g, F, Gf(m, t_layer(l, L_W2))));
   RC(bias_grad(m, m->d_d, H, Tr, H, Gf(m, t_layer(l, L_B2))));
   RC(linear_bwd_input(m, m->d_d, Tr, H, H, Wg(m, t_layer(l, L_W2)), F, m->d_u, EPI_MUL_GELU_GRAD, st.u));
   RC(linear_bwd_weight(m, m->d_u, Tr, F, F, st.x1, H, Gf(m, t_layer(l, L_W1))));
   RC(bias_grad(m, m->d_u, F, Tr, F, Gf(m, t_layer(l, L_B1))));
   RC(linear_bwd_input(m, m->d_u, Tr, F, F, Wg(m, t_layer(l, L_W1)), H, m->d_x1, EPI_ADD, m->d_d));
-  HIP_TRY(ln_bwd(m->dtype, m->d_x1, st.xhat1, st.rstd1, Wf(m, t_layer(l, L_LN1G)), m->d_z1, Gf(m, t_layer(l, L_LN1G)),
-                 Gf(m, t_layer(l, L_LN1B)), m->red_scratch, Tr, H, s));
+  RC(ln_backward(m, m->d_x1, st.xhat1, st.rstd1, Wf(m, t_layer(l, L_LN1G)), m->d_z1, Gf(m, t_layer(l, L_LN1G)),
+                 Gf(m, t_layer(l, L_LN1B)), Tr));
   RC(linear_bwd_weight(m, m->d_z1, Tr, H, H, st.ctx, H, Gf(m, t_layer(l, L_WO))));
   RC(bias_grad(m, m->d_z1, H, Tr, H, Gf(m, t_layer(l, L_BO))));
   RC(linear_bwd_input(m, m->d_z1, Tr, H, H, Wg(m, t_layer(l, L_WO)), H, m->d_c, EPI_NONE, nullptr));
   AttnBwdDesc a{st.qkv, st.ctx, m->d_c, st.lse, m->delta, m->d_qkv, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh,
                 m->cfg.mask_bias};
-  if (m->dtype == 1 && attention_mfma_supported(bt->seq, m->dh))
-    HIP_TRY(attention_bwd_mfma(a, s));
-  else
-    HIP_TRY(attention_bwd_simple(m->dtype, a, s));
-  if (Tr > T)  // padded token rows must contribute nothing to the weight gradients
-    HIP_TRY(fill_zero((char*)m->d_qkv + (size_t)T * 3 * H * m->esz, (size_t)(Tr - T) * 3 * H * m->esz, s));
+  {
+    const double TS = (double)bt->batch * bt->seq;
+    ProfScope ps(m, PC_ATTN_BWD, 10.0 * TS * bt->seq * H, 8.0 * TS * H * m->esz);
+    if (m->dtype == 1 && attention_mfma_supported(bt->seq, m->dh))
+      HIP_TRY(attention_bwd_mfma(a, s));
+    else
+      HIP_TRY(attention_bwd_simple(m->dtype, a, s));
+    if (Tr > T)  // padded token rows must contribute nothing to the weight gradients
+      HIP_TRY(fill_zero((char*)m->d_qkv + (size_t)T * 3 * H * m->esz, (size_t)(Tr - T) * 3 * H * m->esz, s));
+  }
   RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_layer(l, L_WQ))));
   RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_layer(l, L_BQ))));
   if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_layer(l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
@@ -522,8 +588,11 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   // S1: embeddings + LayerNorm
   LnStash e0;
   if (train_emb) { e0.xhat = m->xhat0; e0.rstd = m->rstd0; }
-  HIP_TRY(embed_ln_fwd(m->dtype, bt->input_ids, bt->token_type_ids, S, Wf(m, T_WORD), Wf(m, T_POS), Wf(m, T_TYPE),
-                       Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, s));
+  {
+    ProfScope ps(m, PC_EMBED, 0.0, (double)T * H * (4.0 + m->esz * (train_emb ? 2.0 : 1.0)));
+    HIP_TRY(embed_ln_fwd(m->dtype, bt->input_ids, bt->token_type_ids, S, Wf(m, T_WORD), Wf(m, T_POS), Wf(m, T_TYPE),
+                         Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, s));
+  }
   // S2: frozen prefix, forward only, two ping-pong buffers, nothing kept
   const void* x = m->x0;
   for (int l = 0; l < f; ++l) {
@@ -539,26 +608,37 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   }
   // S4-S6: head forward and loss
   const int th = t_head(m, 0);
-  HIP_TRY(gather_rows(m->dtype, x, m->pos, M, Mr, H, m->xm, s));
+  {
+    ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * Mr * H * m->esz);
+    HIP_TRY(gather_rows(m->dtype, x, m->pos, M, Mr, H, m->xm, s));
+  }
   RC(linear_fwd(m, m->xm, Mr, H, Wg(m, th + H_WT), H, Wf(m, th + H_BT), m->gt, 0, H, EPI_GELU, m->ut));
   LnStash sh{m->xhat_t, m->rstd_t};
-  HIP_TRY(add_ln_fwd(m->dtype, m->gt, nullptr, Wf(m, th + H_LNG), Wf(m, th + H_LNB), m->cfg.ln_eps, m->hm, sh, Mr, H, s));
+  RC(ln_forward(m, m->gt, nullptr, Wf(m, th + H_LNG), Wf(m, th + H_LNB), m->hm, sh, Mr));
   RC(linear_fwd(m, m->hm, Mr, H, Wg(m, T_WORD), Vr, Wf(m, th + H_BOUT), m->logits, 1, m->Vp, EPI_NONE, nullptr));
-  HIP_TRY(ce_fwd_bwd(m->dtype, m->logits, m->Vp, m->lab, M, Mr, m->V, m->dz, m->row_loss, m->lse_t, m->loss, s));
+  {
+    ProfScope ps(m, PC_CE, 0.0, (double)M * m->V * 4.0 + (double)Mr * m->Vp * m->esz);
+    HIP_TRY(ce_fwd_bwd(m->dtype, m->logits, m->Vp, m->lab, M, Mr, m->V, m->dz, m->row_loss, m->lse_t, m->loss, s));
+  }
   HIP_TRY(hipMemcpyAsync(m->h_loss, m->loss, 4, hipMemcpyDeviceToHost, s));
   // S7: head backward
   RC(bias_grad(m, m->dz, m->Vp, Mr, m->V, Gf(m, th + H_BOUT)));
   if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD)));
   RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr));
-  HIP_TRY(ln_bwd(m->dtype, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG),
-                 Gf(m, th + H_LNB), m->red_scratch, Mr, H, s));
-  HIP_TRY(mul_gelu_grad(m->dtype, m->d_gt, m->ut, m->d_ut, (size_t)Mr * H, s));
+  RC(ln_backward(m, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG), Gf(m, th + H_LNB), Mr));
+  {
+    ProfScope ps(m, PC_HEAD_MISC, 0.0, 3.0 * Mr * H * m->esz);
+    HIP_TRY(mul_gelu_grad(m->dtype, m->d_gt, m->ut, m->d_ut, (size_t)Mr * H, s));
+  }
   RC(linear_bwd_weight(m, m->d_ut, Mr, H, H, m->xm, H, Gf(m, th + H_WT)));
   RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT)));
   RC(linear_bwd_input(m, m->d_ut, Mr, H, H, Wg(m, th + H_WT), H, m->d_xm, EPI_NONE, nullptr));
   // S8: scatter into the gradient of the top layer's output
   void* dx = m->dxa;
-  HIP_TRY(scatter_rows(m->dtype, m->d_xm, m->inv, Tr, T, H, dx, s));
+  {
+    ProfScope ps(m, PC_HEAD_MISC, 0.0, ((double)Tr + M) * H * m->esz);
+    HIP_TRY(scatter_rows(m->dtype, m->d_xm, m->inv, Tr, T, H, dx, s));
+  }
   // S9: trainable layers backward, top down
   for (int l = f + k - 1; l >= f; --l) {
     const void* xin = (l == f) ? m->last_prefix : m->stash[l - 1].xout;
@@ -569,8 +649,8 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   }
   // S10: embedding backward (first stage / retraining)
   if (train_emb) {
-    HIP_TRY(ln_bwd(m->dtype, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B),
-                   m->red_scratch, T, H, s));
+    RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), T));
+    ProfScope ps(m, PC_EMBED_BWD, 0.0, (double)T * H * (m->esz + 8.0));
     HIP_TRY(embed_bwd(m->dtype, m->d_z0, bt->input_ids, bt->token_type_ids, B, S, H, m->V, m->cfg.type_vocab,
                       Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order,
                       m->cfg.max_pos, m->red_scratch, s));
@@ -641,6 +721,9 @@ extern "C" int mslt_apply_update(mslt_model* m, const mslt_opt* opt) {
   for (int i = 0; i < n; ++i) {
     int t0 = r[i][0], nt = r[i][1] - r[i][0];
     int c0 = m->first_chunk[t0], nc = m->first_chunk[r[i][1]] - c0;
+    size_t n_elems = 0;
+    for (int t = t0; t < r[i][1]; ++t) n_elems += m->table[t].count;
+    ProfScope ps(m, PC_OPT, 0.0, (double)n_elems * ((opt->kind ? 40.0 : 28.0) + (m->dtype ? 2.0 : 0.0)));
     HIP_TRY(bump_steps(m->o_tsteps, t0, nt, m->stream));
     HIP_TRY(optimizer_step(h, m->o_tensors, m->o_tsteps, t0, nt, m->o_chunk_tensor, c0, nc, m->param, m->grad, m->mom1,
                            m->mom2, m->shadow, m->o_chunk_norms, m->o_ratio, m->stream));
@@ -702,5 +785,37 @@ extern "C" int mslt_grow(mslt_model* m, int n_present, int n_new) {
   HIP_TRY(hipMemcpyAsync(m->o_tsteps + t_layer(n_present, 0), z.data(), z.size() * 4, hipMemcpyHostToDevice, m->stream));
   HIP_TRY(hipStreamSynchronize(m->stream));
   m->have_grads = false;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_profile_enable(mslt_model* m, int on) {
+  if (!m) return fail(MSLT_ERR_ARG, "model is null");
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  for (auto& sp : m->prof.spans) { m->prof.pool.push_back(sp.a); m->prof.pool.push_back(sp.b); }
+  m->prof.spans.clear();
+  m->prof.on = on != 0;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_profile_read(mslt_model* m, mslt_profile_entry* out, int cap, int* n) {
+  if (!m || !out || !n) return fail(MSLT_ERR_ARG, "null argument");
+  if (cap < PC_COUNT) return fail(MSLT_ERR_ARG, "profile_read: need room for %d entries", (int)PC_COUNT);
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  for (int c = 0; c < PC_COUNT; ++c) {
+    memset(&out[c], 0, sizeof out[c]);
+    snprintf(out[c].name, sizeof out[c].name, "%s", kProfNames[c]);
+  }
+  for (auto& sp : m->prof.spans) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+    out[sp.cls].launches += 1;
+    out[sp.cls].ms += ms;
+    out[sp.cls].flops += sp.flops;
+    out[sp.cls].bytes += sp.bytes;
+    m->prof.pool.push_back(sp.a);
+    m->prof.pool.push_back(sp.b);
+  }
+  m->prof.spans.clear();
+  *n = PC_COUNT;
   return MSLT_OK;
 }
