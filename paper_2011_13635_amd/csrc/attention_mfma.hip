@@ -1,7 +1,387 @@
-// placeholder, replaced below
+// bf16 MFMA attention for gfx950, head width 64, sequence length a multiple of 128.
+//
+// Forward: softmax(Q K^T / sqrt(d) + key mask) V with the scale, mask and softmax fused between
+// the two products; the S x S scores never leave registers.  Backward: scores are recomputed
+// from Q, K and the stored row log-sum-exp, in two kernels that each keep one operand family
+// resident: a query-side kernel (dQ, and delta = rowsum(dC * C)) and a key-side kernel (dK, dV).
+//
+// All products are v_mfma_f32_32x32x16_bf16 and are arranged transposed, so that the index the
+// softmax runs along sits in a lane's registers:
+//   query side:  S^T[key,q] = K Q^T      -> a lane owns one query column, its registers the keys
+//                O^T[d,q]   = V^T P^T    -> P^T feeds the second product straight from registers
+//   key side:    S[q,key]   = Q K^T      -> a lane owns one key column, its registers the queries
+//                dV^T[d,key] = dC^T P,  dK^T[d,key] = Q^T dS
+// The accumulator layout of one product is used directly as the B operand of the next one by
+// agreeing on a permuted order of the contraction index (the order in which a lane's registers
+// hold it); the A operand (V^T, K^T, Q^T, dC^T) is written to LDS transposed and in that order.
+// One 256-thread workgroup handles 128 queries (or keys) of one (batch, head): 32 per wavefront.
 #include "common.h"
+
 namespace mslt {
-bool attention_mfma_supported(int, int) { return false; }
-hipError_t attention_fwd_mfma(const AttnDesc&, hipStream_t) { return hipErrorNotSupported; }
-hipError_t attention_bwd_mfma(const AttnBwdDesc&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+constexpr int DH = 64;        // head width
+constexpr int TILE = 128;     // rows per LDS tile
+constexpr int TLD = 136;      // row stride (elements) of a transposed tile [64][128+8]
+
+__device__ __forceinline__ int swz8(int row) { return ((row >> 1) & 7) ^ ((row >> 4) & 7); }
+
+// Row-major tile [128][64] from global rows of stride ld, 16-byte chunks XOR-swizzled per row.
+__device__ __forceinline__ void load_tile_rows(bf16* __restrict__ lds, const bf16* __restrict__ g, size_t ld, int tid) {
+  int c = tid & 7, r = tid >> 3;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    int row = r + 32 * p;
+    u32x4_t v = *reinterpret_cast<const u32x4_t*>(g + (size_t)row * ld + 8 * c);
+    *reinterpret_cast<u32x4_t*>(lds + row * DH + 8 * (c ^ swz8(row))) = v;
+  }
 }
+__device__ __forceinline__ bf16x8_t frag_rows(const bf16* __restrict__ lds, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8_t*>(lds + row * DH + 8 * (chunk ^ swz8(row)));
+}
+
+// Position of row r (0..127) of a tile along the contraction axis of a transposed tile: within
+// each block of 32 the order is the one in which an accumulator lane holds its 16 rows, i.e.
+// slot s of lane-half h in the c-th 16-wide MFMA step is row 8*(2c + s/4) + 4h + s%4.
+__device__ __forceinline__ int perm_pos(int r) {
+  int blk = r & ~31, o = r & 31;
+  int c = o >> 4, s4 = (o >> 3) & 1, h = (o >> 2) & 1, j = o & 3;
+  return blk + c * 16 + h * 8 + s4 * 4 + j;
+}
+
+// Transposed tile [64 d][128 rows permuted] from global rows of stride ld: each thread takes 4
+// consecutive rows x 8 d, transposes in registers and writes eight 8-byte pieces.
+__device__ __forceinline__ void put4(bf16* __restrict__ lds, int d, int pos, uint32_t a, uint32_t b, uint32_t c,
+                                     uint32_t e, uint32_t sel) {
+  u32x2_t o;
+  o.x = __builtin_amdgcn_perm(b, a, sel);
+  o.y = __builtin_amdgcn_perm(e, c, sel);
+  *reinterpret_cast<u32x2_t*>(lds + d * TLD + pos) = o;
+}
+__device__ __forceinline__ void load_tile_transposed(bf16* __restrict__ lds, const bf16* __restrict__ g, size_t ld,
+                                                     int tid) {
+  int rg = tid >> 3, dg = tid & 7;  // rows 4rg..4rg+3, d 8dg..8dg+7
+  const bf16* q = g + (size_t)(4 * rg) * ld + 8 * dg;
+  u32x4_t v0 = *reinterpret_cast<const u32x4_t*>(q);
+  u32x4_t v1 = *reinterpret_cast<const u32x4_t*>(q + ld);
+  u32x4_t v2 = *reinterpret_cast<const u32x4_t*>(q + 2 * ld);
+  u32x4_t v3 = *reinterpret_cast<const u32x4_t*>(q + 3 * ld);
+  int pos = perm_pos(4 * rg), d = 8 * dg;
+  const uint32_t LO = 0x05040100u, HI = 0x07060302u;
+  put4(lds, d + 0, pos, v0.x, v1.x, v2.x, v3.x, LO);
+  put4(lds, d + 1, pos, v0.x, v1.x, v2.x, v3.x, HI);
+  put4(lds, d + 2, pos, v0.y, v1.y, v2.y, v3.y, LO);
+  put4(lds, d + 3, pos, v0.y, v1.y, v2.y, v3.y, HI);
+  put4(lds, d + 4, pos, v0.z, v1.z, v2.z, v3.z, LO);
+  put4(lds, d + 5, pos, v0.z, v1.z, v2.z, v3.z, HI);
+  put4(lds, d + 6, pos, v0.w, v1.w, v2.w, v3.w, LO);
+  put4(lds, d + 7, pos, v0.w, v1.w, v2.w, v3.w, HI);
+}
+// A-operand fragment of a transposed tile: row d, the 8 contraction slots of (block kb, step c, half h)
+__device__ __forceinline__ bf16x8_t frag_transposed(const bf16* __restrict__ lds, int d, int kb, int c, int half) {
+  return *reinterpret_cast<const bf16x8_t*>(lds + d * TLD + kb * 32 + c * 16 + half * 8);
+}
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  return (uint32_t)f2bf(a).x | ((uint32_t)f2bf(b).x << 16);
+}
+// registers 8c..8c+7 of an accumulator block -> B operand of the c-th 16-wide step
+__device__ __forceinline__ bf16x8_t pack_frag(const f32x16_t& p, int c) {
+  u32x4_t u;
+  u.x = pack2(p[8 * c + 0], p[8 * c + 1]);
+  u.y = pack2(p[8 * c + 2], p[8 * c + 3]);
+  u.z = pack2(p[8 * c + 4], p[8 * c + 5]);
+  u.w = pack2(p[8 * c + 6], p[8 * c + 7]);
+  return __builtin_bit_cast(bf16x8_t, u);
+}
+__device__ __forceinline__ f32x16_t zero16() {
+  f32x16_t z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
+}
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+// 4 consecutive d of 32 rows: accumulator block (lane = row index n, registers = d) to global
+// out[(row0 + n)*ld + d0 + 8g + 4half + j] with optional scale, 8-byte stores
+__device__ __forceinline__ void store_acc_T(bf16* __restrict__ out, size_t ld, int n, int half, const f32x16_t& a,
+                                            float scale) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    u32x2_t o;
+    o.x = pack2(a[4 * g] * scale, a[4 * g + 1] * scale);
+    o.y = pack2(a[4 * g + 2] * scale, a[4 * g + 3] * scale);
+    *reinterpret_cast<u32x2_t*>(out + (size_t)n * ld + 8 * g + 4 * half) = o;
+  }
+}
+
+// ---- forward --------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+                                                       float* __restrict__ lse, const int32_t* __restrict__ am, int S,
+                                                       int nh, float scale, float mask_bias) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[TILE * DH];
+  __shared__ __attribute__((aligned(16))) bf16 Vt[DH * TLD];
+  __shared__ __attribute__((aligned(16))) float bias[TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+  const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int H = nh * DH;
+  const size_t ld = 3 * (size_t)H;
+  const bf16* base = qkv + (size_t)b * S * ld + h * DH;
+  const int q = qt * TILE + wave * 32 + n;  // this lane's query inside the sequence
+
+  bf16x8_t qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)q * ld + 16 * ks + 8 * half);
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16_t o0 = zero16(), o1 = zero16();
+  for (int kt = 0; kt < S / TILE; ++kt) {
+    if (kt > 0) __syncthreads();
+    load_tile_rows(Ks, base + H + (size_t)kt * TILE * ld, ld, tid);
+    load_tile_transposed(Vt, base + 2 * H + (size_t)kt * TILE * ld, ld, tid);
+    if (tid < TILE) bias[tid] = am[b * S + kt * TILE + tid] ? 0.f : mask_bias;
+    __syncthreads();
+
+    f32x16_t s[4];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      s[kb] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) s[kb] = MFMA(frag_rows(Ks, kb * 32 + n, 2 * ks + half), qf[ks], s[kb]);
+    }
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
+        s[kb][4 * g + 0] = s[kb][4 * g + 0] * scale + bb.x;
+        s[kb][4 * g + 1] = s[kb][4 * g + 1] * scale + bb.y;
+        s[kb][4 * g + 2] = s[kb][4 * g + 2] * scale + bb.z;
+        s[kb][4 * g + 3] = s[kb][4 * g + 3] * scale + bb.w;
+        tmax = fmaxf(tmax, fmaxf(fmaxf(s[kb][4 * g], s[kb][4 * g + 1]), fmaxf(s[kb][4 * g + 2], s[kb][4 * g + 3])));
+      }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    float m_new = fmaxf(m_run, tmax);
+    float alpha = __expf(m_run - m_new);   // 0 on the first tile (m_run = -inf)
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __expf(s[kb][r] - m_new);
+        s[kb][r] = p;
+        psum += p;
+      }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      o0[r] *= alpha;
+      o1[r] *= alpha;
+    }
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        bf16x8_t pf = pack_frag(s[kb], c);
+        o0 = MFMA(frag_transposed(Vt, n, kb, c, half), pf, o0);
+        o1 = MFMA(frag_transposed(Vt, 32 + n, kb, c, half), pf, o1);
+      }
+  }
+  float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  float inv = 1.0f / l_tot;
+  bf16* out = ctx + ((size_t)b * S + qt * TILE + wave * 32) * H + h * DH;
+  store_acc_T(out, H, n, half, o0, inv);
+  store_acc_T(out + 32, H, n, half, o1, inv);
+  if (lse != nullptr && half == 0) lse[((size_t)b * nh + h) * S + q] = m_run + __logf(l_tot);
+}
+
+// ---- backward, query side: delta and dQ -----------------------------------------------------
+__global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+                                                         const bf16* __restrict__ dctx, const float* __restrict__ lse,
+                                                         float* __restrict__ delta, bf16* __restrict__ dqkv,
+                                                         const int32_t* __restrict__ am, int S, int nh, float scale,
+                                                         float mask_bias) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[TILE * DH];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[TILE * DH];
+  __shared__ __attribute__((aligned(16))) bf16 Kt[DH * TLD];
+  __shared__ __attribute__((aligned(16))) float bias[TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+  const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int H = nh * DH;
+  const size_t ld = 3 * (size_t)H;
+  const bf16* base = qkv + (size_t)b * S * ld + h * DH;
+  const int q = qt * TILE + wave * 32 + n;
+  const size_t tok = (size_t)b * S + q;
+
+  bf16x8_t qf[4], gf[4];
+  float dl = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)q * ld + 16 * ks + 8 * half);
+    gf[ks] = *reinterpret_cast<const bf16x8_t*>(dctx + tok * H + h * DH + 16 * ks + 8 * half);
+    bf16x8_t cf = *reinterpret_cast<const bf16x8_t*>(ctx + tok * H + h * DH + 16 * ks + 8 * half);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dl += (float)gf[ks][i] * (float)cf[i];
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  const float l = lse[((size_t)b * nh + h) * S + q];
+  if (half == 0) delta[((size_t)b * nh + h) * S + q] = dl;
+
+  f32x16_t dq0 = zero16(), dq1 = zero16();
+  for (int kt = 0; kt < S / TILE; ++kt) {
+    if (kt > 0) __syncthreads();
+    const bf16* kbase = base + H + (size_t)kt * TILE * ld;
+    load_tile_rows(Ks, kbase, ld, tid);
+    load_tile_rows(Vs, base + 2 * H + (size_t)kt * TILE * ld, ld, tid);
+    load_tile_transposed(Kt, kbase, ld, tid);
+    if (tid < TILE) bias[tid] = am[b * S + kt * TILE + tid] ? 0.f : mask_bias;
+    __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      f32x16_t s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s = MFMA(frag_rows(Ks, kb * 32 + n, 2 * ks + half), qf[ks], s);
+        dp = MFMA(frag_rows(Vs, kb * 32 + n, 2 * ks + half), gf[ks], dp);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
+        float bv[4] = {bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float p = __expf(s[4 * g + j] * scale + bv[j] - l);
+          s[4 * g + j] = p * (dp[4 * g + j] - dl);   // dS^T
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        bf16x8_t df = pack_frag(s, c);
+        dq0 = MFMA(frag_transposed(Kt, n, kb, c, half), df, dq0);
+        dq1 = MFMA(frag_transposed(Kt, 32 + n, kb, c, half), df, dq1);
+      }
+    }
+  }
+  bf16* out = dqkv + ((size_t)b * S + qt * TILE + wave * 32) * ld + h * DH;
+  store_acc_T(out, ld, n, half, dq0, scale);
+  store_acc_T(out + 32, ld, n, half, dq1, scale);
+}
+
+// ---- backward, key side: dK and dV ----------------------------------------------------------
+__global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dctx,
+                                                          const float* __restrict__ lse,
+                                                          const float* __restrict__ delta, bf16* __restrict__ dqkv,
+                                                          const int32_t* __restrict__ am, int S, int nh, float scale,
+                                                          float mask_bias) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_kv[];   // KV_LDS_BYTES
+  bf16* Qs = reinterpret_cast<bf16*>(smem_kv);
+  bf16* Gs = Qs + TILE * DH;
+  bf16* Qt = Gs + TILE * DH;
+  bf16* Gt = Qt + DH * TLD;
+  float* lse_s = reinterpret_cast<float*>(Gt + DH * TLD);
+  float* dl_s = lse_s + TILE;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+  const int kt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int H = nh * DH;
+  const size_t ld = 3 * (size_t)H;
+  const bf16* base = qkv + (size_t)b * S * ld + h * DH;
+  const int key = kt * TILE + wave * 32 + n;  // this lane's key
+
+  bf16x8_t kf[4], vf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    kf[ks] = *reinterpret_cast<const bf16x8_t*>(base + H + (size_t)key * ld + 16 * ks + 8 * half);
+    vf[ks] = *reinterpret_cast<const bf16x8_t*>(base + 2 * H + (size_t)key * ld + 16 * ks + 8 * half);
+  }
+  const float kbias = am[b * S + key] ? 0.f : mask_bias;
+
+  f32x16_t dk0 = zero16(), dk1 = zero16(), dv0 = zero16(), dv1 = zero16();
+  for (int qt = 0; qt < S / TILE; ++qt) {
+    if (qt > 0) __syncthreads();
+    const bf16* qbase = base + (size_t)qt * TILE * ld;
+    const bf16* gbase = dctx + ((size_t)b * S + qt * TILE) * H + h * DH;
+    load_tile_rows(Qs, qbase, ld, tid);
+    load_tile_rows(Gs, gbase, H, tid);
+    load_tile_transposed(Qt, qbase, ld, tid);
+    load_tile_transposed(Gt, gbase, H, tid);
+    if (tid < TILE) {
+      lse_s[tid] = lse[((size_t)b * nh + h) * S + qt * TILE + tid];
+      dl_s[tid] = delta[((size_t)b * nh + h) * S + qt * TILE + tid];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+      f32x16_t s = zero16(), dp = zero16();   // S[q,key] and dP[q,key]: lane = key, registers = queries
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s = MFMA(frag_rows(Qs, qb * 32 + n, 2 * ks + half), kf[ks], s);
+        dp = MFMA(frag_rows(Gs, qb * 32 + n, 2 * ks + half), vf[ks], dp);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float4 ll = *reinterpret_cast<const float4*>(&lse_s[qb * 32 + 8 * g + 4 * half]);
+        float4 dd = *reinterpret_cast<const float4*>(&dl_s[qb * 32 + 8 * g + 4 * half]);
+        float lv[4] = {ll.x, ll.y, ll.z, ll.w}, dv[4] = {dd.x, dd.y, dd.z, dd.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float p = __expf(s[4 * g + j] * scale + kbias - lv[j]);
+          s[4 * g + j] = p;                                   // P
+          dp[4 * g + j] = p * (dp[4 * g + j] - dv[j]);        // dS
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        bf16x8_t pf = pack_frag(s, c), df = pack_frag(dp, c);
+        dv0 = MFMA(frag_transposed(Gt, n, qb, c, half), pf, dv0);
+        dv1 = MFMA(frag_transposed(Gt, 32 + n, qb, c, half), pf, dv1);
+        dk0 = MFMA(frag_transposed(Qt, n, qb, c, half), df, dk0);
+        dk1 = MFMA(frag_transposed(Qt, 32 + n, qb, c, half), df, dk1);
+      }
+    }
+  }
+  bf16* out = dqkv + ((size_t)b * S + kt * TILE + wave * 32) * ld + h * DH;
+  store_acc_T(out + H, ld, n, half, dk0, scale);
+  store_acc_T(out + H + 32, ld, n, half, dk1, scale);
+  store_acc_T(out + 2 * H, ld, n, half, dv0, 1.0f);
+  store_acc_T(out + 2 * H + 32, ld, n, half, dv1, 1.0f);
+}
+
+constexpr int KV_LDS_BYTES = (2 * TILE * DH + 2 * DH * TLD) * 2 + 2 * TILE * 4;
+
+bool attention_mfma_supported(int S, int dh) { return dh == DH && S >= TILE && S % TILE == 0; }
+
+hipError_t attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
+  if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
+  dim3 grid(a.S / TILE, a.nh, a.B);
+  k_attn_fwd_mfma<<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
+                                             1.0f / sqrtf((float)a.dh), a.mask_bias);
+  return hipGetLastError();
+}
+
+hipError_t attention_bwd_mfma(const AttnBwdDesc& a, hipStream_t s) {
+  if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
+  dim3 grid(a.S / TILE, a.nh, a.B);
+  float scale = 1.0f / sqrtf((float)a.dh);
+  k_attn_bwd_q_mfma<<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse,
+                                               a.delta, (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale, a.mask_bias);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  static bool attr_set = false;
+  if (!attr_set) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_bwd_kv_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            KV_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  k_attn_bwd_kv_mfma<<<grid, dim3(256), KV_LDS_BYTES, s>>>((const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.delta, (bf16*)a.dqkv,
+                                                a.attn_mask, a.S, a.nh, scale, a.mask_bias);
+  return hipGetLastError();
+}
+
+}  // namespace mslt
