@@ -139,9 +139,10 @@ hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S,
 // out = LN(a + r) (r may be null)
 hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, const float* b, float eps, void* out,
                       LnStash st, int rows, int H, hipStream_t s);
-// dz from dy, xhat, rstd, gamma; dgamma/dbeta via partials (scratch holds 2*ceil(rows/32)*H floats)
+// dz from dy, xhat, rstd, gamma; dgamma, dbeta and (if dzsum != null) the column sums of dz via
+// partials in scratch (ln_bwd_scratch_floats(rows, H) floats)
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
-                  float* db, float* scratch, int rows, int H, hipStream_t s);
+                  float* db, float* dzsum, float* scratch, int rows, int H, hipStream_t s);
 // column sums of Y[rows, N] (leading dimension ld) into out[N]; scratch holds ceil(rows/64)*N floats
 hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s);
 size_t colsum_scratch_floats(int rows, int N);

@@ -511,10 +511,11 @@ static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, flo
   HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, m->red_scratch, m->stream));
   return MSLT_OK;
 }
+// dzsum (may be null): column sums of dz = bias gradient of the linear layer feeding this LayerNorm
 static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz,
-                       float* dg, float* db, int rows) {
+                       float* dg, float* db, float* dzsum, int rows) {
   ProfScope ps(m, PC_LN_BWD, 0.0, 3.0 * rows * m->H * m->esz);
-  HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, m->red_scratch, rows, m->H, m->stream));
+  HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, m->stream));
   return MSLT_OK;
 }
 
@@ -526,17 +527,15 @@ static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int
   const LayerStash& st = m->stash[l];
   hipStream_t s = m->stream;
   RC(ln_backward(m, dXout, st.xhat2, st.rstd2, Wf(m, t_layer(l, L_LN2G)), m->d_d, Gf(m, t_layer(l, L_LN2G)),
-                 Gf(m, t_layer(l, L_LN2B)), Tr));
+                 Gf(m, t_layer(l, L_LN2B)), Gf(m, t_layer(l, L_B2)), Tr));
   RC(linear_bwd_weight(m, m->d_d, Tr, H, H, st.g, F, Gf(m, t_layer(l, L_W2))));
-  RC(bias_grad(m, m->d_d, H, Tr, H, Gf(m, t_layer(l, L_B2))));
   RC(linear_bwd_input(m, m->d_d, Tr, H, H, Wg(m, t_layer(l, L_W2)), F, m->d_u, EPI_MUL_GELU_GRAD, st.u));
   RC(linear_bwd_weight(m, m->d_u, Tr, F, F, st.x1, H, Gf(m, t_layer(l, L_W1))));
   RC(bias_grad(m, m->d_u, F, Tr, F, Gf(m, t_layer(l, L_B1))));
   RC(linear_bwd_input(m, m->d_u, Tr, F, F, Wg(m, t_layer(l, L_W1)), H, m->d_x1, EPI_ADD, m->d_d));
   RC(ln_backward(m, m->d_x1, st.xhat1, st.rstd1, Wf(m, t_layer(l, L_LN1G)), m->d_z1, Gf(m, t_layer(l, L_LN1G)),
-                 Gf(m, t_layer(l, L_LN1B)), Tr));
+                 Gf(m, t_layer(l, L_LN1B)), Gf(m, t_layer(l, L_BO)), Tr));
   RC(linear_bwd_weight(m, m->d_z1, Tr, H, H, st.ctx, H, Gf(m, t_layer(l, L_WO))));
-  RC(bias_grad(m, m->d_z1, H, Tr, H, Gf(m, t_layer(l, L_BO))));
   RC(linear_bwd_input(m, m->d_z1, Tr, H, H, Wg(m, t_layer(l, L_WO)), H, m->d_c, EPI_NONE, nullptr));
   AttnBwdDesc a{st.qkv, st.ctx, m->d_c, st.lse, m->delta, m->d_qkv, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh,
                 m->cfg.mask_bias};
@@ -625,7 +624,7 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   RC(bias_grad(m, m->dz, m->Vp, Mr, m->V, Gf(m, th + H_BOUT)));
   if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD)));
   RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr));
-  RC(ln_backward(m, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG), Gf(m, th + H_LNB), Mr));
+  RC(ln_backward(m, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG), Gf(m, th + H_LNB), nullptr, Mr));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 3.0 * Mr * H * m->esz);
     HIP_TRY(mul_gelu_grad(m->dtype, m->d_gt, m->ut, m->d_ut, (size_t)Mr * H, s));
@@ -649,7 +648,7 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   }
   // S10: embedding backward (first stage / retraining)
   if (train_emb) {
-    RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), T));
+    RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), nullptr, T));
     ProfScope ps(m, PC_EMBED_BWD, 0.0, (double)T * H * (m->esz + 8.0));
     HIP_TRY(embed_bwd(m->dtype, m->d_z0, bt->input_ids, bt->token_type_ids, B, S, H, m->V, m->cfg.type_vocab,
                       Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order,

@@ -27,8 +27,6 @@ __device__ inline void store4(bf16* p, float4 v) {
   *reinterpret_cast<uint2*>(p) = r;
 }
 
-constexpr int LN_MAXV = 8;  // float4 per lane: H <= 64*4*8 = 2048
-
 // ---- fill / cast ----------------------------------------------------------------------------
 __global__ void k_fill_zero(uint32_t* p, size_t n_words) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -147,20 +145,21 @@ hipError_t batch_scan(const int32_t* ids, const int32_t* tt, const int32_t* am, 
 }
 
 // ---- LayerNorm forward on a row held in registers -------------------------------------------
-template <typename AT>
-__device__ inline void ln_row_finish(float4 (&z)[LN_MAXV], int H, int lane, const float* __restrict__ g,
+// NV = float4 per lane: a row of up to 256*NV elements lives in one wavefront's registers.
+template <typename AT, int NV>
+__device__ inline void ln_row_finish(float4 (&z)[NV], int H, int lane, const float* __restrict__ g,
                                      const float* __restrict__ b, float eps, AT* __restrict__ out,
                                      AT* __restrict__ xhat, float* __restrict__ rstd_out) {
   float sum = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
+  for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
     if (c < H) sum += (z[i].x + z[i].y) + (z[i].z + z[i].w);
   }
   float mu = wave_sum(sum) / (float)H;
   float sq = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
+  for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
     if (c < H) {
       z[i].x -= mu; z[i].y -= mu; z[i].z -= mu; z[i].w -= mu;
@@ -171,7 +170,7 @@ __device__ inline void ln_row_finish(float4 (&z)[LN_MAXV], int H, int lane, cons
   float rstd = 1.0f / sqrtf(var + eps);
   if (rstd_out != nullptr && lane == 0) *rstd_out = rstd;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
+  for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
     if (c < H) {
       float4 xh = make_float4(z[i].x * rstd, z[i].y * rstd, z[i].z * rstd, z[i].w * rstd);
@@ -182,7 +181,7 @@ __device__ inline void ln_row_finish(float4 (&z)[LN_MAXV], int H, int lane, cons
   }
 }
 
-template <typename AT>
+template <typename AT, int NV>
 __global__ void __launch_bounds__(256) k_embed_ln(const int32_t* __restrict__ ids, const int32_t* __restrict__ tt, int S,
                                                   const float* __restrict__ word, const float* __restrict__ pos,
                                                   const float* __restrict__ type, const float* __restrict__ g,
@@ -194,32 +193,40 @@ __global__ void __launch_bounds__(256) k_embed_ln(const int32_t* __restrict__ id
   const float* w = word + (size_t)ids[row] * H;
   const float* p = pos + (size_t)(row % S) * H;
   const float* ty = type + (size_t)tt[row] * H;
-  float4 z[LN_MAXV];
+  float4 z[NV];
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
+  for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
     if (c < H) {
       float4 a = load4(w + c), b2 = load4(p + c), c2 = load4(ty + c);
       z[i] = make_float4(a.x + b2.x + c2.x, a.y + b2.y + c2.y, a.z + b2.z + c2.z, a.w + b2.w + c2.w);
     }
   }
-  ln_row_finish<AT>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
-                    rstd ? rstd + row : nullptr);
+  ln_row_finish<AT, NV>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
+                        rstd ? rstd + row : nullptr);
 }
+static inline int ln_nv(int H) { return H <= 512 ? 2 : H <= 1024 ? 4 : 8; }
+#define LN_DISPATCH(H, CALL)         \
+  switch (ln_nv(H)) {                \
+    case 2: { constexpr int NV = 2; CALL; } break; \
+    case 4: { constexpr int NV = 4; CALL; } break; \
+    default: { constexpr int NV = 8; CALL; } break; \
+  }
 hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S, const float* word, const float* pos,
                         const float* type, const float* g, const float* b, float eps, void* out, LnStash st, int T,
                         int H, hipStream_t s) {
   dim3 grid((T + 3) / 4), block(256);
-  if (dtype == 0)
-    k_embed_ln<float><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (float*)out, (float*)st.xhat,
-                                             st.rstd, T, H);
-  else
-    k_embed_ln<bf16><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (bf16*)out, (bf16*)st.xhat, st.rstd,
-                                            T, H);
+  if (dtype == 0) {
+    LN_DISPATCH(H, (k_embed_ln<float, NV><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (float*)out,
+                                                                 (float*)st.xhat, st.rstd, T, H)));
+  } else {
+    LN_DISPATCH(H, (k_embed_ln<bf16, NV><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (bf16*)out,
+                                                                (bf16*)st.xhat, st.rstd, T, H)));
+  }
   return hipGetLastError();
 }
 
-template <typename AT>
+template <typename AT, int NV>
 __global__ void __launch_bounds__(256) k_add_ln(const AT* __restrict__ a, const AT* __restrict__ r,
                                                 const float* __restrict__ g, const float* __restrict__ b, float eps,
                                                 AT* __restrict__ out, AT* __restrict__ xhat, float* __restrict__ rstd,
@@ -229,9 +236,9 @@ __global__ void __launch_bounds__(256) k_add_ln(const AT* __restrict__ a, const 
   if (row >= rows) return;
   const AT* pa = a + (size_t)row * H;
   const AT* pr = r ? r + (size_t)row * H : nullptr;
-  float4 z[LN_MAXV];
+  float4 z[NV];
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
+  for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
     if (c < H) {
       float4 x = load4(pa + c);
@@ -242,103 +249,138 @@ __global__ void __launch_bounds__(256) k_add_ln(const AT* __restrict__ a, const 
       z[i] = x;
     }
   }
-  ln_row_finish<AT>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
-                    rstd ? rstd + row : nullptr);
+  ln_row_finish<AT, NV>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
+                        rstd ? rstd + row : nullptr);
 }
 hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, const float* b, float eps, void* out,
                       LnStash st, int rows, int H, hipStream_t s) {
   dim3 grid((rows + 3) / 4), block(256);
-  if (dtype == 0)
-    k_add_ln<float><<<grid, block, 0, s>>>((const float*)a, (const float*)r, g, b, eps, (float*)out, (float*)st.xhat,
-                                           st.rstd, rows, H);
-  else
-    k_add_ln<bf16><<<grid, block, 0, s>>>((const bf16*)a, (const bf16*)r, g, b, eps, (bf16*)out, (bf16*)st.xhat,
-                                          st.rstd, rows, H);
+  if (dtype == 0) {
+    LN_DISPATCH(H, (k_add_ln<float, NV><<<grid, block, 0, s>>>((const float*)a, (const float*)r, g, b, eps, (float*)out,
+                                                               (float*)st.xhat, st.rstd, rows, H)));
+  } else {
+    LN_DISPATCH(H, (k_add_ln<bf16, NV><<<grid, block, 0, s>>>((const bf16*)a, (const bf16*)r, g, b, eps, (bf16*)out,
+                                                              (bf16*)st.xhat, st.rstd, rows, H)));
+  }
   return hipGetLastError();
 }
 
-// ---- column-sum finalisation: out[c] = sum over p of partial[p][c], fixed order -------------
-__global__ void k_colsum_final(const float* __restrict__ partial, int n_partials, int N, float* __restrict__ out) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= N) return;
+// ---- reduction of partial column sums: out[c] = sum_p partial[p][c], fixed order ------------
+// 1024 threads = 64 columns x 16 partial-lanes; lane j adds partials j, j+16, ... in order, then
+// the 16 lane sums are added in lane order.
+__global__ void __launch_bounds__(1024) k_reduce_partials(const float* __restrict__ partial, int n_partials, int N,
+                                                          float* __restrict__ out) {
+  __shared__ float sh[16][65];
+  int cl = threadIdx.x & 63, pl = threadIdx.x >> 6;
+  int c = blockIdx.x * 64 + cl;
   float acc = 0.f;
-  for (int p = 0; p < n_partials; ++p) acc += partial[(size_t)p * N + c];
-  out[c] = acc;
+  if (c < N)
+    for (int p = pl; p < n_partials; p += 16) acc += partial[(size_t)p * N + c];
+  sh[pl][cl] = acc;
+  __syncthreads();
+  if (pl == 0 && c < N) {
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v += sh[j][cl];
+    out[c] = v;
+  }
+}
+static hipError_t reduce_partials(const float* partial, int n_partials, int N, float* out, hipStream_t s) {
+  k_reduce_partials<<<dim3((N + 63) / 64), dim3(1024), 0, s>>>(partial, n_partials, N, out);
+  return hipGetLastError();
 }
 
 // ---- LayerNorm backward ---------------------------------------------------------------------
-constexpr int LNB_ROWS_PER_WAVE = 8;
-constexpr int LNB_ROWS_PER_BLOCK = 4 * LNB_ROWS_PER_WAVE;
+// One wavefront handles R consecutive rows (all loads issued before the row reductions), four
+// wavefronts per workgroup; the workgroup leaves one partial row each of dgamma = sum dy*xhat,
+// dbeta = sum dy and sum dz (the bias gradient of the linear layer in front of the LayerNorm).
+static inline int lnb_rows_per_wave(int H) { return ln_nv(H) == 8 ? 2 : 4; }
 size_t ln_bwd_scratch_floats(int rows, int H) {
-  return (size_t)2 * ((rows + LNB_ROWS_PER_BLOCK - 1) / LNB_ROWS_PER_BLOCK) * H;
+  int rpb = 4 * lnb_rows_per_wave(H);
+  return (size_t)3 * ((rows + rpb - 1) / rpb) * H;
 }
 
-template <typename AT>
+template <typename AT, int NV, int R>
 __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const AT* __restrict__ xhat,
                                                 const float* __restrict__ rstd, const float* __restrict__ g,
                                                 AT* __restrict__ dz, float* __restrict__ part_g,
-                                                float* __restrict__ part_b, int rows, int H) {
-  __shared__ float red[3][64 * 4 * LN_MAXV];
-  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float4 gg[LN_MAXV], ag[LN_MAXV], ab[LN_MAXV];
+                                                float* __restrict__ part_b, float* __restrict__ part_z, int rows,
+                                                int H) {
+  __shared__ float red[3][256 * NV];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float4 gg[NV], ag[NV], ab[NV], az[NV];
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
+  for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
-    ag[i] = make_float4(0, 0, 0, 0);
-    ab[i] = make_float4(0, 0, 0, 0);
+    ag[i] = ab[i] = az[i] = make_float4(0, 0, 0, 0);
     gg[i] = (c < H) ? load4(g + c) : make_float4(0, 0, 0, 0);
   }
-  int row0 = blockIdx.x * LNB_ROWS_PER_BLOCK + wave * LNB_ROWS_PER_WAVE;
-  float invH = 1.0f / (float)H;
-  for (int rr = 0; rr < LNB_ROWS_PER_WAVE; ++rr) {
+  const int row0 = (blockIdx.x * 4 + wave) * R;
+  const float invH = 1.0f / (float)H;
+  float4 d[R][NV], x[R][NV];
+  float rs[R];
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
     int row = row0 + rr;
-    if (row >= rows) break;
-    const AT* pdy = dy + (size_t)row * H;
-    const AT* pxh = xhat + (size_t)row * H;
-    float4 d[LN_MAXV], x[LN_MAXV];
-    float s1 = 0.f, s2 = 0.f;
+    bool ok = row < rows;
+    rs[rr] = ok ? rstd[row] : 0.f;
 #pragma unroll
-    for (int i = 0; i < LN_MAXV; ++i) {
+    for (int i = 0; i < NV; ++i) {
       int c = (i * 64 + lane) * 4;
-      if (c < H) {
-        float4 y = load4(pdy + c);
-        x[i] = load4(pxh + c);
-        ag[i].x += y.x * x[i].x; ag[i].y += y.y * x[i].y; ag[i].z += y.z * x[i].z; ag[i].w += y.w * x[i].w;
-        ab[i].x += y.x; ab[i].y += y.y; ab[i].z += y.z; ab[i].w += y.w;
-        d[i] = make_float4(y.x * gg[i].x, y.y * gg[i].y, y.z * gg[i].z, y.w * gg[i].w);
-        s1 += (d[i].x + d[i].y) + (d[i].z + d[i].w);
-        s2 += (d[i].x * x[i].x + d[i].y * x[i].y) + (d[i].z * x[i].z + d[i].w * x[i].w);
+      if (ok && c < H) {
+        d[rr][i] = load4(dy + (size_t)row * H + c);
+        x[rr][i] = load4(xhat + (size_t)row * H + c);
+      } else {
+        d[rr][i] = x[rr][i] = make_float4(0, 0, 0, 0);
       }
-    }
-    float m1 = wave_sum(s1) * invH, m2 = wave_sum(s2) * invH;
-    float rs = rstd[row];
-    AT* pdz = dz + (size_t)row * H;
-#pragma unroll
-    for (int i = 0; i < LN_MAXV; ++i) {
-      int c = (i * 64 + lane) * 4;
-      if (c < H)
-        store4(pdz + c, make_float4((d[i].x - m1 - x[i].x * m2) * rs, (d[i].y - m1 - x[i].y * m2) * rs,
-                                    (d[i].z - m1 - x[i].z * m2) * rs, (d[i].w - m1 - x[i].w * m2) * rs));
     }
   }
-  // cross-wave reduction of the per-column partial sums, waves added in order 0,1,2,3
-  for (int pass = 0; pass < 2; ++pass) {
-    float4* acc = pass == 0 ? ag : ab;
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      float4 y = d[rr][i], xx = x[rr][i];
+      ag[i].x += y.x * xx.x; ag[i].y += y.y * xx.y; ag[i].z += y.z * xx.z; ag[i].w += y.w * xx.w;
+      ab[i].x += y.x; ab[i].y += y.y; ab[i].z += y.z; ab[i].w += y.w;
+      y = make_float4(y.x * gg[i].x, y.y * gg[i].y, y.z * gg[i].z, y.w * gg[i].w);
+      d[rr][i] = y;
+      s1 += (y.x + y.y) + (y.z + y.w);
+      s2 += (y.x * xx.x + y.y * xx.y) + (y.z * xx.z + y.w * xx.w);
+    }
+    float m1 = wave_sum(s1) * invH, m2 = wave_sum(s2) * invH;
+    int row = row0 + rr;
+    if (row < rows) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        int c = (i * 64 + lane) * 4;
+        if (c < H) {
+          float4 y = d[rr][i], xx = x[rr][i];
+          float4 o = make_float4((y.x - m1 - xx.x * m2) * rs[rr], (y.y - m1 - xx.y * m2) * rs[rr],
+                                 (y.z - m1 - xx.z * m2) * rs[rr], (y.w - m1 - xx.w * m2) * rs[rr]);
+          az[i].x += o.x; az[i].y += o.y; az[i].z += o.z; az[i].w += o.w;
+          store4(dz + (size_t)row * H + c, o);
+        }
+      }
+    }
+  }
+  // cross-wave reduction of the three per-column sums, waves added in order 0,1,2,3
+#pragma unroll
+  for (int pass = 0; pass < 3; ++pass) {
+    float4* acc = pass == 0 ? ag : pass == 1 ? ab : az;
     if (wave > 0) {
 #pragma unroll
-      for (int i = 0; i < LN_MAXV; ++i) {
-        int c = (i * 64 + lane) * 4;
-        if (c < H) *reinterpret_cast<float4*>(&red[wave - 1][c]) = acc[i];
-      }
+      for (int i = 0; i < NV; ++i) *reinterpret_cast<float4*>(&red[wave - 1][(i * 64 + lane) * 4]) = acc[i];
     }
     __syncthreads();
     if (wave == 0) {
-      float* dst = (pass == 0 ? part_g : part_b) + (size_t)blockIdx.x * H;
+      float* dst = (pass == 0 ? part_g : pass == 1 ? part_b : part_z) + (size_t)blockIdx.x * H;
 #pragma unroll
-      for (int i = 0; i < LN_MAXV; ++i) {
+      for (int i = 0; i < NV; ++i) {
         int c = (i * 64 + lane) * 4;
         if (c < H) {
           float4 v = acc[i];
+#pragma unroll
           for (int w = 0; w < 3; ++w) {
             float4 o = *reinterpret_cast<float4*>(&red[w][c]);
             v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
@@ -350,28 +392,84 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
     __syncthreads();
   }
 }
-hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
-                  float* db, float* scratch, int rows, int H, hipStream_t s) {
-  int nb = (rows + LNB_ROWS_PER_BLOCK - 1) / LNB_ROWS_PER_BLOCK;
+template <typename AT>
+static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, const float* g, AT* dz, float* dg, float* db,
+                           float* dzsum, float* scratch, int rows, int H, hipStream_t s) {
+  int R = lnb_rows_per_wave(H);
+  int nb = (rows + 4 * R - 1) / (4 * R);
   float* pg = scratch;
-  float* pb = scratch + (size_t)nb * H;
-  if (dtype == 0)
-    k_ln_bwd<float><<<dim3(nb), dim3(256), 0, s>>>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, pg, pb,
-                                                   rows, H);
-  else
-    k_ln_bwd<bf16><<<dim3(nb), dim3(256), 0, s>>>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, pg, pb, rows,
-                                                  H);
+  float* pb = pg + (size_t)nb * H;
+  float* pz = pb + (size_t)nb * H;
+  switch (ln_nv(H)) {
+    case 2: k_ln_bwd<AT, 2, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H); break;
+    case 4: k_ln_bwd<AT, 4, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H); break;
+    default: k_ln_bwd<AT, 8, 2><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H); break;
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  k_colsum_final<<<dim3((H + 255) / 256), dim3(256), 0, s>>>(pg, nb, H, dg);
-  k_colsum_final<<<dim3((H + 255) / 256), dim3(256), 0, s>>>(pb, nb, H, db);
-  return hipGetLastError();
+  if ((e = reduce_partials(pg, nb, H, dg, s)) != hipSuccess) return e;
+  if ((e = reduce_partials(pb, nb, H, db, s)) != hipSuccess) return e;
+  if (dzsum) e = reduce_partials(pz, nb, H, dzsum, s);
+  return e;
+}
+hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
+                  float* db, float* dzsum, float* scratch, int rows, int H, hipStream_t s) {
+  if (dtype == 0)
+    return ln_bwd_t<float>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, dg, db, dzsum, scratch, rows, H, s);
+  return ln_bwd_t<bf16>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dg, db, dzsum, scratch, rows, H, s);
 }
 
 // ---- column sums (bias gradients) -----------------------------------------------------------
-constexpr int CS_ROWS = 64;
+// Vector path (N, ld multiples of 8): a workgroup takes 64 columns x 256 rows as 8 column-threads
+// (8 columns = 16 or 32 bytes each) x 32 row-lanes; row-lanes are added in lane order through LDS.
+constexpr int CS_ROWS = 64;        // rows per partial, scalar path
+constexpr int CSV_ROWS = 256;      // rows per partial, vector path
 size_t colsum_scratch_floats(int rows, int N) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * N; }
 
+__device__ inline void load8(const float* p, float (&v)[8]) {
+  float4 a = load4(p), b = load4(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ inline void load8(const bf16* p, float (&v)[8]) {
+  uint4 r = *reinterpret_cast<const uint4*>(p);
+  v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+  v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+  v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xffff0000u);
+  v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+template <typename AT>
+__global__ void __launch_bounds__(256) k_colsum_vec(const AT* __restrict__ y, int ld, int rows, int N,
+                                                    float* __restrict__ partial) {
+  __shared__ float sh[32][65];
+  int ct = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  int c = blockIdx.x * 64 + ct * 8;
+  int r0 = blockIdx.y * CSV_ROWS;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (c < N) {
+#pragma unroll
+    for (int it = 0; it < CSV_ROWS / 32; ++it) {
+      int r = r0 + it * 32 + rl;
+      if (r < rows) {
+        float v[8];
+        load8(y + (size_t)r * ld + c, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += v[i];
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sh[rl][ct * 8 + i] = acc[i];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    int cc = blockIdx.x * 64 + threadIdx.x;
+    if (cc < N) {
+      float v = 0.f;
+#pragma unroll
+      for (int j = 0; j < 32; ++j) v += sh[j][threadIdx.x];
+      partial[(size_t)blockIdx.y * N + cc] = v;
+    }
+  }
+}
 template <typename AT>
 __global__ void __launch_bounds__(256) k_colsum_partial(const AT* __restrict__ y, int ld, int rows, int N,
                                                         float* __restrict__ partial) {
@@ -383,16 +481,26 @@ __global__ void __launch_bounds__(256) k_colsum_partial(const AT* __restrict__ y
   partial[(size_t)blockIdx.y * N + c] = acc;
 }
 hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s) {
-  int nchunks = (rows + CS_ROWS - 1) / CS_ROWS;
-  dim3 grid((N + 255) / 256, nchunks), block(256);
-  if (dtype == 0)
-    k_colsum_partial<float><<<grid, block, 0, s>>>((const float*)y, ld, rows, N, scratch);
-  else
-    k_colsum_partial<bf16><<<grid, block, 0, s>>>((const bf16*)y, ld, rows, N, scratch);
+  bool vec = (N % 8 == 0) && (ld % 8 == 0) && ((reinterpret_cast<uintptr_t>(y) & 31) == 0);
+  int nchunks;
+  if (vec) {
+    nchunks = (rows + CSV_ROWS - 1) / CSV_ROWS;
+    dim3 grid((N + 63) / 64, nchunks), block(256);
+    if (dtype == 0)
+      k_colsum_vec<float><<<grid, block, 0, s>>>((const float*)y, ld, rows, N, scratch);
+    else
+      k_colsum_vec<bf16><<<grid, block, 0, s>>>((const bf16*)y, ld, rows, N, scratch);
+  } else {
+    nchunks = (rows + CS_ROWS - 1) / CS_ROWS;
+    dim3 grid((N + 255) / 256, nchunks), block(256);
+    if (dtype == 0)
+      k_colsum_partial<float><<<grid, block, 0, s>>>((const float*)y, ld, rows, N, scratch);
+    else
+      k_colsum_partial<bf16><<<grid, block, 0, s>>>((const bf16*)y, ld, rows, N, scratch);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  k_colsum_final<<<dim3((N + 255) / 256), dim3(256), 0, s>>>(scratch, nchunks, N, out);
-  return hipGetLastError();
+  return reduce_partials(scratch, nchunks, N, out, s);
 }
 
 // ---- GELU backward (head only; the layers fuse it into the GEMM epilogue) -------------------
@@ -624,8 +732,7 @@ static hipError_t embed_bwd_t(const AT* dz, const int32_t* ids, const int32_t* t
   int nchunks = (T + CS_ROWS - 1) / CS_ROWS;
   k_type_partial<AT><<<dim3((H + 255) / 256, nchunks), dim3(256), 0, s>>>(dz, tt, T, H, type_vocab, scratch);
   int N = type_vocab * H;
-  k_colsum_final<<<dim3((N + 255) / 256), dim3(256), 0, s>>>(scratch, nchunks, N, gtype);
-  return hipGetLastError();
+  return reduce_partials(scratch, nchunks, N, gtype, s);
 }
 hipError_t embed_bwd(int dtype, const void* dz, const int32_t* ids, const int32_t* tt, int B, int S, int H, int vocab,
                      int type_vocab, float* gword, float* gpos, float* gtype, int32_t* rank, int32_t* cnt,
