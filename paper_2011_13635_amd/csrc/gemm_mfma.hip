@@ -22,6 +22,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // first-class 1
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int PF = 2;                                  // prefetch distance in k tiles
 constexpr int STAGE_ELEMS = (BM + BN) * BK;            // bf16 elements per pipeline stage
 constexpr int EPI_LD = 68;                             // floats per staged row of a wavefront quarter
 constexpr int LDS_BYTES_MAIN = 2 * STAGE_ELEMS * 2;    // 65536
@@ -100,6 +101,38 @@ __device__ __forceinline__ void store_slab(bf16* __restrict__ lds, int tid, cons
   }
 }
 
+// Quarter Q (0..3) of a slab load / store, so that the memory instructions of a k tile can be
+// spread between the MFMAs of the four 16-wide steps.
+template <bool KC, int Q>
+__device__ __forceinline__ void load_slab_part(const bf16* __restrict__ base, int ld, int row0, int k0, int tid, Slab& s) {
+  u32x4_t v;
+  if constexpr (KC)
+    v = *reinterpret_cast<const u32x4_t*>(base + (size_t)(row0 + (tid >> 3) + 32 * Q) * ld + k0 + 8 * (tid & 7));
+  else
+    v = *reinterpret_cast<const u32x4_t*>(base + (size_t)(k0 + 4 * (tid >> 4) + Q) * ld + row0 + 8 * (tid & 15));
+  if constexpr (Q == 0) s.v0 = v;
+  if constexpr (Q == 1) s.v1 = v;
+  if constexpr (Q == 2) s.v2 = v;
+  if constexpr (Q == 3) s.v3 = v;
+}
+template <bool KC, int Q>
+__device__ __forceinline__ void store_slab_part(bf16* __restrict__ lds, int tid, const Slab& s) {
+  if constexpr (KC) {
+    int c = tid & 7, r = (tid >> 3) + 32 * Q;
+    u32x4_t v = Q == 0 ? s.v0 : Q == 1 ? s.v1 : Q == 2 ? s.v2 : s.v3;
+    *reinterpret_cast<u32x4_t*>(lds + r * BK + 8 * (c ^ swz(r))) = v;
+  } else {
+    // rows 8cg+2Q and 8cg+2Q+1: low and high halves of word Q of the four loads (four k values)
+    int cg = tid & 15, kg = tid >> 4, r = 8 * cg + 2 * Q;
+    uint32_t a = Q == 0 ? s.v0.x : Q == 1 ? s.v0.y : Q == 2 ? s.v0.z : s.v0.w;
+    uint32_t b = Q == 0 ? s.v1.x : Q == 1 ? s.v1.y : Q == 2 ? s.v1.z : s.v1.w;
+    uint32_t c = Q == 0 ? s.v2.x : Q == 1 ? s.v2.y : Q == 2 ? s.v2.z : s.v2.w;
+    uint32_t d = Q == 0 ? s.v3.x : Q == 1 ? s.v3.y : Q == 2 ? s.v3.z : s.v3.w;
+    put_row4(lds, r, kg, a, b, c, d, 0x05040100u);
+    put_row4(lds, r + 1, kg, a, b, c, d, 0x07060302u);
+  }
+}
+
 __device__ __forceinline__ bf16x8_t lds_frag(const bf16* __restrict__ lds, int row, int chunk) {
   return *reinterpret_cast<const bf16x8_t*>(lds + row * BK + 8 * (chunk ^ swz(row)));
 }
@@ -171,9 +204,11 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(MfmaParams p) {
   const int tile = pid - split * tiles;
   const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
-  const int kper = p.K / p.splitk;
-  const int kbeg = split * kper;
-  const int nk = kper / BK;
+  // split s takes k tiles [s*nkt/splitk, (s+1)*nkt/splitk): sizes differ by at most one tile
+  const int nkt = p.K / BK;
+  const int kt_lo = (int)((long long)split * nkt / p.splitk);
+  const int kbeg = kt_lo * BK;
+  const int nk = (int)((long long)(split + 1) * nkt / p.splitk) - kt_lo;
 
   f32x16_t acc[2][2];
 #pragma unroll
@@ -183,39 +218,74 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(MfmaParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  Slab ra, rb;
-  load_slab<A_KC>(p.A, p.lda, m0, kbeg, tid, ra);
-  load_slab<B_KC>(p.B, p.ldb, n0, kbeg, tid, rb);
-  store_slab<A_KC>(lds, tid, ra);
-  store_slab<B_KC>(lds + BM * BK, tid, rb);
+  // Software pipeline: PF register sets hold the slabs of tiles kt+1 .. kt+PF while tile kt is
+  // multiplied out of LDS, so a global load has PF-1 full iterations to land before its data is
+  // written to LDS.  Tile t lives in set t % PF; the loop is unrolled by PF so that every set has
+  // a static name, and its body is branch-free (tile indices past the end are clamped: the
+  // duplicate loads and the last LDS store are never consumed), which lets the compiler keep the
+  // loads of later tiles in flight across iterations instead of draining them at every join.
+  Slab ra[PF], rb[PF];
+#pragma unroll
+  for (int j = 0; j < PF; ++j) {
+    int t = j < nk ? j : nk - 1;
+    load_slab<A_KC>(p.A, p.lda, m0, kbeg + t * BK, tid, ra[j]);
+    load_slab<B_KC>(p.B, p.ldb, n0, kbeg + t * BK, tid, rb[j]);
+  }
+  store_slab<A_KC>(lds, tid, ra[0]);
+  store_slab<B_KC>(lds + BM * BK, tid, rb[0]);
   __syncthreads();
 
   const int arow = 64 * wm + (lane & 31), brow = 64 * wn + (lane & 31), half = lane >> 5;
-  for (int kt = 0; kt < nk; ++kt) {
+  auto body = [&](Slab& la, Slab& lb, const Slab& na, const Slab& nb, int kt) {
+    // la/lb: set of tile kt (free: refilled with tile kt+PF); na/nb: set of tile kt+1 (goes to LDS).
+    // The four 16-wide steps each carry a quarter of the global loads and of the LDS stores and
+    // prefetch the fragments of the next step, so that memory instructions issue in the shadow of
+    // the MFMAs instead of in separate phases; sched_barrier keeps the steps apart.
     const bf16* sa = lds + (kt & 1) * STAGE_ELEMS;
     const bf16* sb = sa + BM * BK;
-    if (kt + 1 < nk) {
-      load_slab<A_KC>(p.A, p.lda, m0, kbeg + (kt + 1) * BK, tid, ra);
-      load_slab<B_KC>(p.B, p.ldb, n0, kbeg + (kt + 1) * BK, tid, rb);
+    bf16* da = lds + ((kt + 1) & 1) * STAGE_ELEMS;
+    bf16* db = da + BM * BK;
+    const int tn = kt + PF < nk ? kt + PF : nk - 1;
+    const int kn = kbeg + tn * BK;
+    bf16x8_t fa[2][2], fb[2][2];
+    fa[0][0] = lds_frag(sa, arow, half);
+    fa[0][1] = lds_frag(sa, arow + 32, half);
+    fb[0][0] = lds_frag(sb, brow, half);
+    fb[0][1] = lds_frag(sb, brow + 32, half);
+#define MSLT_GEMM_STEP(KS)                                                                          \
+    {                                                                                               \
+      constexpr int cur = (KS) & 1, nxt = cur ^ 1;                                                  \
+      if constexpr ((KS) < 3) {                                                                     \
+        fa[nxt][0] = lds_frag(sa, arow, 2 * ((KS) + 1) + half);                                     \
+        fa[nxt][1] = lds_frag(sa, arow + 32, 2 * ((KS) + 1) + half);                                \
+        fb[nxt][0] = lds_frag(sb, brow, 2 * ((KS) + 1) + half);                                     \
+        fb[nxt][1] = lds_frag(sb, brow + 32, 2 * ((KS) + 1) + half);                                \
+      }                                                                                             \
+      load_slab_part<A_KC, (KS)>(p.A, p.lda, m0, kn, tid, la);                                      \
+      load_slab_part<B_KC, (KS)>(p.B, p.ldb, n0, kn, tid, lb);                                      \
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][0], acc[0][0], 0, 0, 0); \
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][1], acc[0][1], 0, 0, 0); \
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][0], acc[1][0], 0, 0, 0); \
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][1], acc[1][1], 0, 0, 0); \
+      store_slab_part<A_KC, (KS)>(da, tid, na);                                                     \
+      store_slab_part<B_KC, (KS)>(db, tid, nb);                                                     \
+      __builtin_amdgcn_sched_barrier(0);                                                            \
     }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8_t fa0 = lds_frag(sa, arow, 2 * ks + half);
-      bf16x8_t fa1 = lds_frag(sa, arow + 32, 2 * ks + half);
-      bf16x8_t fb0 = lds_frag(sb, brow, 2 * ks + half);
-      bf16x8_t fb1 = lds_frag(sb, brow + 32, 2 * ks + half);
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb1, acc[1][1], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      bf16* da = lds + ((kt + 1) & 1) * STAGE_ELEMS;
-      store_slab<A_KC>(da, tid, ra);
-      store_slab<B_KC>(da + BM * BK, tid, rb);
-    }
+    MSLT_GEMM_STEP(0)
+    MSLT_GEMM_STEP(1)
+    MSLT_GEMM_STEP(2)
+    MSLT_GEMM_STEP(3)
+#undef MSLT_GEMM_STEP
     __syncthreads();
+  };
+  int kt = 0;
+  for (; kt + PF <= nk; kt += PF) {
+#pragma unroll
+    for (int j = 0; j < PF; ++j) body(ra[j], rb[j], ra[(j + 1) % PF], rb[(j + 1) % PF], kt + j);
   }
+#pragma unroll
+  for (int j = 0; j < PF - 1; ++j)
+    if (kt + j < nk) body(ra[j], rb[j], ra[(j + 1) % PF], rb[(j + 1) % PF], kt + j);
 
   // stage this wavefront's 64x64 quarter in LDS (all operand reads are behind the last barrier)
   float* stage = reinterpret_cast<float*>(smem) + wave * 64 * EPI_LD;
@@ -289,7 +359,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
 
 hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s) {
   if (!gemm_mfma_supported(d)) return hipErrorInvalidValue;
-  if (splitk < 1 || d.K % (splitk * BK) != 0) return hipErrorInvalidValue;
+  if (splitk < 1 || splitk > d.K / BK) return hipErrorInvalidValue;
   if (splitk > 1 && partials == nullptr) return hipErrorInvalidValue;
   MfmaParams p;
   p.A = reinterpret_cast<const bf16*>(d.A);

@@ -417,11 +417,12 @@ extern "C" int mslt_get_params(const mslt_model* m, float* host, size_t n_floats
 
 // ---- GEMM dispatch --------------------------------------------------------------------------
 static int pick_splitk(int M, int N, int K) {
+  // enough workgroups to fill 256 CUs x 2 resident workgroups, at least 4 k tiles of 64 per split
   int tiles = (M / 128) * (N / 128);
   if (tiles >= 256 || K < 1024) return 1;
   int s = (512 + tiles - 1) / tiles;
   if (s > 16) s = 16;
-  while (s > 1 && (K % (s * 64) != 0 || K / s < 256)) --s;
+  while (s > 1 && K / 64 / s < 4) --s;
   return s;
 }
 static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false) {
@@ -455,12 +456,12 @@ static int linear_fwd(mslt_model* m, const void* X, int rows, int K, const void*
 }
 // dX[rows,K] = dY[rows,N] W[N,K]  (+ addend | * gelu'(U))
 static int linear_bwd_input(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* W, int K, void* dX,
-                            int act, const void* aux) {
+                            int act, const void* aux, bool allow_splitk = false) {
   GemmDesc d;
   d.A = dY; d.lda = ldy; d.a_kcontig = 1; d.M = rows;
   d.B = W; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = N;
   d.epi.out = dX; d.epi.ldo = K; d.epi.act = act; d.epi.aux = aux; d.epi.ldaux = K;
-  return run_gemm(m, d);
+  return run_gemm(m, d, allow_splitk);
 }
 // dW[N,K] = dY[rows,N]^T X[rows,K]   (fp32 out, contraction over rows)
 static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* X, int K, float* dW) {
@@ -623,7 +624,8 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   // S7: head backward
   RC(bias_grad(m, m->dz, m->Vp, Mr, m->V, Gf(m, th + H_BOUT)));
   if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD)));
-  RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr));
+  // few output tiles, contraction over the whole vocabulary: split it
+  RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr, true));
   RC(ln_backward(m, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG), Gf(m, th + H_LNB), nullptr, Mr));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 3.0 * Mr * H * m->esz);
