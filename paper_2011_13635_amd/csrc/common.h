@@ -150,6 +150,8 @@ size_t ln_bwd_scratch_floats(int rows, int H);
 
 hipError_t mul_gelu_grad(int dtype, const void* dg, const void* u, void* du, size_t n, hipStream_t s);
 hipError_t gather_rows(int dtype, const void* x, const int32_t* pos, int M, int Mpad, int H, void* out, hipStream_t s);
+// out[j] = j < M ? x[pos[j]] : 0 for j < Mpad
+hipError_t gather_f32(const float* x, const int32_t* pos, int M, int Mpad, float* out, hipStream_t s);
 hipError_t scatter_rows(int dtype, const void* dxm, const int32_t* inv, int rows_total, int T, int H, void* out,
                         hipStream_t s);
 // cross-entropy over fp32 logits [Mpad, ldz]: writes dZ (activation type, zero in padded rows and

@@ -88,6 +88,7 @@ struct mslt_model {
   float *delta;
   int32_t *pos, *lab, *inv, *counters;
   void *xm, *ut, *gt, *xhat_t, *hm, *dz, *d_hm, *d_gt, *d_ut, *d_xm;
+  void *c_g, *c_u, *c_du;              // compacted FFN rows of the top layer [Mp, F]
   float *rstd_t, *logits, *row_loss, *lse_t, *loss;
   float *red_scratch; size_t red_floats;
   float *splitk; size_t splitk_floats;
@@ -231,6 +232,7 @@ static size_t carve(mslt_model* m, char* base) {
   m->xm = b.take<void>(MH); m->ut = b.take<void>(MH); m->gt = b.take<void>(MH); m->xhat_t = b.take<void>(MH);
   m->hm = b.take<void>(MH); m->dz = b.take<void>(Mp * Vp * e); m->d_hm = b.take<void>(MH); m->d_gt = b.take<void>(MH);
   m->d_ut = b.take<void>(MH); m->d_xm = b.take<void>(MH);
+  m->c_g = b.take<void>(Mp * F * e); m->c_u = b.take<void>(Mp * F * e); m->c_du = b.take<void>(Mp * F * e);
   m->rstd_t = b.take<float>(Mp * 4); m->logits = b.take<float>(Mp * Vp * 4); m->row_loss = b.take<float>(Mp * 4);
   m->lse_t = b.take<float>(Mp * 4); m->loss = b.take<float>(64);
   // reduction scratch: the largest of LayerNorm-backward partials, column-sum partials, token-type partials
@@ -520,24 +522,37 @@ static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const fl
   return MSLT_OK;
 }
 
-// dXout: gradient w.r.t. the layer output; dXin: where to put the gradient w.r.t. the layer input,
-// or null when nothing below needs it (the block below is frozen: Section 3.1).
-static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, const void* dXout,
-                          void* dXin) {
-  const int H = m->H, F = m->F;
+// Backward of the row-local upper part of a layer (LayerNorm 2, FFN, LayerNorm 1, output
+// projection), on `rows` rows.  Used on all token rows, or on the compacted predicted rows of the
+// top layer (see layer_backward_top).
+struct UpperRows {
+  const void *xhat2, *g, *u, *x1, *xhat1, *ctx;  // stash rows
+  const float *rstd2, *rstd1;
+  void *dz2, *du, *dx1, *dz1, *dc;               // gradient buffers
+  int rows;
+};
+static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const UpperRows& r) {
+  const int H = m->H, F = m->F, R = r.rows;
+  RC(ln_backward(m, dXout, r.xhat2, r.rstd2, Wf(m, t_layer(l, L_LN2G)), r.dz2, Gf(m, t_layer(l, L_LN2G)),
+                 Gf(m, t_layer(l, L_LN2B)), Gf(m, t_layer(l, L_B2)), R));
+  RC(linear_bwd_weight(m, r.dz2, R, H, H, r.g, F, Gf(m, t_layer(l, L_W2))));
+  RC(linear_bwd_input(m, r.dz2, R, H, H, Wg(m, t_layer(l, L_W2)), F, r.du, EPI_MUL_GELU_GRAD, r.u));
+  RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_layer(l, L_W1))));
+  RC(bias_grad(m, r.du, F, R, F, Gf(m, t_layer(l, L_B1))));
+  RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_layer(l, L_W1)), H, r.dx1, EPI_ADD, r.dz2));
+  RC(ln_backward(m, r.dx1, r.xhat1, r.rstd1, Wf(m, t_layer(l, L_LN1G)), r.dz1, Gf(m, t_layer(l, L_LN1G)),
+                 Gf(m, t_layer(l, L_LN1B)), Gf(m, t_layer(l, L_BO)), R));
+  RC(linear_bwd_weight(m, r.dz1, R, H, H, r.ctx, H, Gf(m, t_layer(l, L_WO))));
+  RC(linear_bwd_input(m, r.dz1, R, H, H, Wg(m, t_layer(l, L_WO)), H, r.dc, EPI_NONE, nullptr));
+  return MSLT_OK;
+}
+// Attention backward and the QKV projection backward, from dC and dz1 (both [Tr, H], all token rows).
+// dXin: where to put the gradient w.r.t. the layer input, or null when nothing below needs it
+// (the block below is frozen: Section 3.1).
+static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, void* dXin) {
+  const int H = m->H;
   const LayerStash& st = m->stash[l];
   hipStream_t s = m->stream;
-  RC(ln_backward(m, dXout, st.xhat2, st.rstd2, Wf(m, t_layer(l, L_LN2G)), m->d_d, Gf(m, t_layer(l, L_LN2G)),
-                 Gf(m, t_layer(l, L_LN2B)), Gf(m, t_layer(l, L_B2)), Tr));
-  RC(linear_bwd_weight(m, m->d_d, Tr, H, H, st.g, F, Gf(m, t_layer(l, L_W2))));
-  RC(linear_bwd_input(m, m->d_d, Tr, H, H, Wg(m, t_layer(l, L_W2)), F, m->d_u, EPI_MUL_GELU_GRAD, st.u));
-  RC(linear_bwd_weight(m, m->d_u, Tr, F, F, st.x1, H, Gf(m, t_layer(l, L_W1))));
-  RC(bias_grad(m, m->d_u, F, Tr, F, Gf(m, t_layer(l, L_B1))));
-  RC(linear_bwd_input(m, m->d_u, Tr, F, F, Wg(m, t_layer(l, L_W1)), H, m->d_x1, EPI_ADD, m->d_d));
-  RC(ln_backward(m, m->d_x1, st.xhat1, st.rstd1, Wf(m, t_layer(l, L_LN1G)), m->d_z1, Gf(m, t_layer(l, L_LN1G)),
-                 Gf(m, t_layer(l, L_LN1B)), Gf(m, t_layer(l, L_BO)), Tr));
-  RC(linear_bwd_weight(m, m->d_z1, Tr, H, H, st.ctx, H, Gf(m, t_layer(l, L_WO))));
-  RC(linear_bwd_input(m, m->d_z1, Tr, H, H, Wg(m, t_layer(l, L_WO)), H, m->d_c, EPI_NONE, nullptr));
   AttnBwdDesc a{st.qkv, st.ctx, m->d_c, st.lse, m->delta, m->d_qkv, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh,
                 m->cfg.mask_bias};
   {
@@ -554,6 +569,43 @@ static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int
   RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_layer(l, L_BQ))));
   if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_layer(l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
   return MSLT_OK;
+}
+// dXout: gradient w.r.t. the layer output on all token rows.
+static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, const void* dXout,
+                          void* dXin) {
+  const LayerStash& st = m->stash[l];
+  UpperRows r{st.xhat2, st.g, st.u, st.x1, st.xhat1, st.ctx, st.rstd2, st.rstd1, m->d_d, m->d_u, m->d_x1, m->d_z1, m->d_c, Tr};
+  RC(layer_backward_upper(m, l, dXout, r));
+  return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin);
+}
+// Top trainable layer: the gradient of its output is non-zero only in the M predicted rows, and
+// everything above the attention is row-local, so that part runs on the compacted rows (exact, not
+// an approximation); dC and dz1 are scattered back to token rows for the attention and QKV backward.
+static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, int M, int Mr, const void* Xin,
+                              const void* dXm, void* dXin) {
+  const int H = m->H, F = m->F;
+  const LayerStash& st = m->stash[l];
+  hipStream_t s = m->stream;
+  {
+    ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * Mr * (4.0 * H + 2.0 * F) * m->esz);
+    HIP_TRY(gather_rows(m->dtype, st.xhat2, m->pos, M, Mr, H, m->xm, s));
+    HIP_TRY(gather_rows(m->dtype, st.x1, m->pos, M, Mr, H, m->ut, s));
+    HIP_TRY(gather_rows(m->dtype, st.xhat1, m->pos, M, Mr, H, m->gt, s));
+    HIP_TRY(gather_rows(m->dtype, st.ctx, m->pos, M, Mr, H, m->xhat_t, s));
+    HIP_TRY(gather_rows(m->dtype, st.g, m->pos, M, Mr, F, m->c_g, s));
+    HIP_TRY(gather_rows(m->dtype, st.u, m->pos, M, Mr, F, m->c_u, s));
+    HIP_TRY(gather_f32(st.rstd2, m->pos, M, Mr, m->rstd_t, s));
+    HIP_TRY(gather_f32(st.rstd1, m->pos, M, Mr, m->lse_t, s));
+  }
+  UpperRows r{m->xm, m->c_g, m->c_u, m->ut, m->gt, m->xhat_t, m->rstd_t, m->lse_t,
+              m->hm, m->c_du, m->d_hm, m->d_gt, m->d_ut, Mr};
+  RC(layer_backward_upper(m, l, dXm, r));
+  {
+    ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * ((double)Tr + M) * H * m->esz);
+    HIP_TRY(scatter_rows(m->dtype, m->d_ut, m->inv, Tr, T, H, m->d_c, s));
+    HIP_TRY(scatter_rows(m->dtype, m->d_gt, m->inv, Tr, T, H, m->d_z1, s));
+  }
+  return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin);
 }
 
 // ---- the stage step -------------------------------------------------------------------------
@@ -634,18 +686,17 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   RC(linear_bwd_weight(m, m->d_ut, Mr, H, H, m->xm, H, Gf(m, th + H_WT)));
   RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT)));
   RC(linear_bwd_input(m, m->d_ut, Mr, H, H, Wg(m, th + H_WT), H, m->d_xm, EPI_NONE, nullptr));
-  // S8: scatter into the gradient of the top layer's output
+  // S8/S9: trainable layers backward, top down.  The top layer works on the compacted predicted rows
+  // and scatters inside; the layers below get dense gradients.
   void* dx = m->dxa;
-  {
-    ProfScope ps(m, PC_HEAD_MISC, 0.0, ((double)Tr + M) * H * m->esz);
-    HIP_TRY(scatter_rows(m->dtype, m->d_xm, m->inv, Tr, T, H, dx, s));
-  }
-  // S9: trainable layers backward, top down
   for (int l = f + k - 1; l >= f; --l) {
     const void* xin = (l == f) ? m->last_prefix : m->stash[l - 1].xout;
     bool need_dx = (l > f) || train_emb;
     void* dxin = need_dx ? (dx == m->dxa ? m->dxb : m->dxa) : nullptr;
-    RC(layer_backward(m, l, bt, T, Tr, xin, dx, dxin));
+    if (l == f + k - 1)
+      RC(layer_backward_top(m, l, bt, T, Tr, M, Mr, xin, m->d_xm, dxin));
+    else
+      RC(layer_backward(m, l, bt, T, Tr, xin, dx, dxin));
     if (dxin) dx = dxin;
   }
   // S10: embedding backward (first stage / retraining)

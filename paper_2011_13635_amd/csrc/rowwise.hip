@@ -266,27 +266,39 @@ hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, c
 }
 
 // ---- reduction of partial column sums: out[c] = sum_p partial[p][c], fixed order ------------
-// 1024 threads = 64 columns x 16 partial-lanes; lane j adds partials j, j+16, ... in order, then
-// the 16 lane sums are added in lane order.
-__global__ void __launch_bounds__(1024) k_reduce_partials(const float* __restrict__ partial, int n_partials, int N,
-                                                          float* __restrict__ out) {
-  __shared__ float sh[16][65];
-  int cl = threadIdx.x & 63, pl = threadIdx.x >> 6;
-  int c = blockIdx.x * 64 + cl;
+// Up to three arrays per launch (blockIdx.y).  1024 threads = 32 columns x 32 partial-lanes; lane
+// j adds partials j, j+32, ... in order, then the 32 lane sums are added in lane order.
+struct ReduceArgs {
+  const float* partial[3];
+  float* out[3];
+};
+__global__ void __launch_bounds__(1024) k_reduce_partials(ReduceArgs a, int n_partials, int N) {
+  __shared__ float sh[32][33];
+  const float* __restrict__ partial = a.partial[blockIdx.y];
+  int cl = threadIdx.x & 31, pl = threadIdx.x >> 5;
+  int c = blockIdx.x * 32 + cl;
   float acc = 0.f;
-  if (c < N)
-    for (int p = pl; p < n_partials; p += 16) acc += partial[(size_t)p * N + c];
+  if (c < N) {
+    int p = pl;
+    for (; p + 96 < n_partials; p += 128) {   // four independent loads in flight
+      float v0 = partial[(size_t)p * N + c], v1 = partial[(size_t)(p + 32) * N + c];
+      float v2 = partial[(size_t)(p + 64) * N + c], v3 = partial[(size_t)(p + 96) * N + c];
+      acc += v0; acc += v1; acc += v2; acc += v3;
+    }
+    for (; p < n_partials; p += 32) acc += partial[(size_t)p * N + c];
+  }
   sh[pl][cl] = acc;
   __syncthreads();
   if (pl == 0 && c < N) {
     float v = 0.f;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) v += sh[j][cl];
-    out[c] = v;
+    for (int j = 0; j < 32; ++j) v += sh[j][cl];
+    a.out[blockIdx.y][c] = v;
   }
 }
 static hipError_t reduce_partials(const float* partial, int n_partials, int N, float* out, hipStream_t s) {
-  k_reduce_partials<<<dim3((N + 63) / 64), dim3(1024), 0, s>>>(partial, n_partials, N, out);
+  ReduceArgs a{{partial, nullptr, nullptr}, {out, nullptr, nullptr}};
+  k_reduce_partials<<<dim3((N + 31) / 32, 1), dim3(1024), 0, s>>>(a, n_partials, N);
   return hipGetLastError();
 }
 
@@ -407,10 +419,9 @@ static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, cons
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if ((e = reduce_partials(pg, nb, H, dg, s)) != hipSuccess) return e;
-  if ((e = reduce_partials(pb, nb, H, db, s)) != hipSuccess) return e;
-  if (dzsum) e = reduce_partials(pz, nb, H, dzsum, s);
-  return e;
+  ReduceArgs a{{pg, pb, pz}, {dg, db, dzsum}};
+  k_reduce_partials<<<dim3((H + 31) / 32, dzsum ? 3 : 2), dim3(1024), 0, s>>>(a, nb, H);
+  return hipGetLastError();
 }
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
                   float* db, float* dzsum, float* scratch, int rows, int H, hipStream_t s) {
@@ -539,6 +550,16 @@ hipError_t gather_rows(int dtype, const void* x, const int32_t* pos, int M, int 
     k_gather_rows<float><<<dim3(Mpad), dim3(64), 0, s>>>((const float*)x, pos, M, H, (float*)out);
   else
     k_gather_rows<bf16><<<dim3(Mpad), dim3(64), 0, s>>>((const bf16*)x, pos, M, H, (bf16*)out);
+  return hipGetLastError();
+}
+
+__global__ void k_gather_f32(const float* __restrict__ x, const int32_t* __restrict__ pos, int M, int Mpad,
+                             float* __restrict__ out) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < Mpad) out[j] = j < M ? x[pos[j]] : 0.f;
+}
+hipError_t gather_f32(const float* x, const int32_t* pos, int M, int Mpad, float* out, hipStream_t s) {
+  k_gather_f32<<<dim3((Mpad + 255) / 256), dim3(256), 0, s>>>(x, pos, M, Mpad, out);
   return hipGetLastError();
 }
 
