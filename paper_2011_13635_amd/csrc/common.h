@@ -88,7 +88,9 @@ hipError_t gemm_simt(int dtype, const GemmDesc& d, hipStream_t s);
 // bounds by construction (padded buffers).  splitk > 1 writes fp32 partials to `partials`
 // ([splitk][M][N]) and reduces them in fixed order into the epilogue.
 bool gemm_mfma_supported(const GemmDesc& d);
-hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s);
+// force_tile_m: 0 = choose the M-tile height (128 or 256 rows) from the shape.
+int gemm_mfma_tile_m(const GemmDesc& d);
+hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s, int force_tile_m = 0);
 
 // ---- attention ------------------------------------------------------------------------------
 struct AttnDesc {

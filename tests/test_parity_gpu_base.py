@@ -37,3 +37,47 @@ def test_base_stage2_benchmark_configuration():
     print("base 3/3 64x128", assert_parity(r, 1, "base-bench"))
     assert len(r["pos"]) == 64 * 19
     r["model"].close()
+
+
+def test_base_final_stage_long_sequence():
+    # final stage of the Base schedule at sequence length 512 (attention tiled over keys), reduced batch
+    sh = synth.bert_base_shape(4)
+    r = run_case(sh, 2, 512, 3, 1, False, 1, seed=3, full_backprop=False)
+    print("base 3/1 2x512", assert_parity(r, 1, "base-512"))
+    r["model"].close()
+
+
+def test_large_stage_with_lamb_update():
+    # BERT-Large shapes (hidden 1024, 16 heads, FFN 4096), 1 frozen + 2 trainable layers, LAMB update
+    import numpy as np
+    from oracle import mslt_oracle as O
+    from paper_2011_13635_amd import binding
+    sh = synth.bert_large_shape(3)
+    r = run_case(sh, 8, 128, 1, 2, False, 1, seed=4, full_backprop=False)
+    print("large 1/2 8x128", assert_parity(r, 1, "large"))
+    m = r["model"]
+    before = synth.unpack_weights(sh, m.mslt_get_params())
+    opt = binding.lamb(lr=0.00088)
+    m.mslt_apply_update(opt)
+    after = synth.unpack_weights(sh, m.mslt_get_params())
+    trainable = set(synth.trainable_names(sh, 1, 2, False))
+    W64 = O.to_f64({n: r["W"][n] for n in trainable})
+    st = O.new_opt_state(W64)
+    new_ref, ratios = O.optimizer_update(W64, r["ref_grads"], st, kind="lamb", lr=0.00088)
+    for name in before:
+        if name not in trainable:
+            assert np.array_equal(before[name], after[name]), name
+            continue
+        dw = after[name].astype(np.float64) - before[name].astype(np.float64)
+        if name.endswith(".bk"):
+            continue
+        wn = np.linalg.norm(before[name].astype(np.float64))
+        if wn > 0:   # LAMB: the step of every tensor with a non-zero norm has length lr*|w|
+            assert abs(np.linalg.norm(dw) - 0.00088 * wn) < 2e-3 * 0.00088 * wn, name
+        # (the element-wise update is compared in fp32 mode in test_parity_gpu.py; in bf16 mode the adaptive
+        #  direction g/(|g|+eps) turns gradient noise of small entries into sign flips, so only the direction
+        #  as a whole is compared here)
+        dref = new_ref[name] - W64[name]
+        cos = float((dw * dref).sum() / (np.linalg.norm(dw) * np.linalg.norm(dref) + 1e-300))
+        assert cos > 0.8, (name, cos)
+    m.close()
