@@ -86,9 +86,7 @@ __device__ __forceinline__ bf16x8_t frag_transposed(const bf16* __restrict__ lds
   return *reinterpret_cast<const bf16x8_t*>(lds + d * TLD + kb * 32 + c * 16 + half * 8);
 }
 
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)f2bf(a).x | ((uint32_t)f2bf(b).x << 16);
-}
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }
 // registers 8c..8c+7 of an accumulator block -> B operand of the c-th 16-wide step
 __device__ __forceinline__ bf16x8_t pack_frag(const f32x16_t& p, int c) {
   u32x4_t u;

@@ -16,17 +16,16 @@ __host__ __device__ inline float bf2f(bf16 v) {
   c.u = ((uint32_t)v.x) << 16;
   return c.f;
 }
-__host__ __device__ inline bf16 f2bf(float f) {
-  union { uint32_t u; float f; } c;
-  c.f = f;
-  uint32_t u = c.u;
+typedef __bf16 hw_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2_t __attribute__((ext_vector_type(2)));
+// fp32 -> bf16, round to nearest even, in hardware (v_cvt_pk_bf16_f32 on gfx950)
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  hw_f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, hw_bf16x2_t));
+}
+__device__ inline bf16 f2bf(float f) {
   bf16 r;
-  if ((u & 0x7fffffffu) > 0x7f800000u) {  // NaN stays NaN
-    r.x = (uint16_t)((u >> 16) | 0x40);
-    return r;
-  }
-  u += 0x7fffu + ((u >> 16) & 1u);
-  r.x = (uint16_t)(u >> 16);
+  r.x = (uint16_t)(pack_bf16x2(f, 0.f) & 0xffffu);
   return r;
 }
 

@@ -144,7 +144,7 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   uint4 u;
   uint32_t* w = reinterpret_cast<uint32_t*>(&u);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(f[2 * i]).x | ((uint32_t)f2bf(f[2 * i + 1]).x << 16);
+  for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
   return u;
 }
 __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float (&v)[8], const float (&bias)[8]) {

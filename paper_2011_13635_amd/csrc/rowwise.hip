@@ -22,8 +22,8 @@ __device__ inline float4 load4(const bf16* p) {
 __device__ inline void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ inline void store4(bf16* p, float4 v) {
   uint2 r;
-  r.x = (uint32_t)f2bf(v.x).x | ((uint32_t)f2bf(v.y).x << 16);
-  r.y = (uint32_t)f2bf(v.z).x | ((uint32_t)f2bf(v.w).x << 16);
+  r.x = pack_bf16x2(v.x, v.y);
+  r.y = pack_bf16x2(v.z, v.w);
   *reinterpret_cast<uint2*>(p) = r;
 }
 
