@@ -54,6 +54,29 @@ __device__ inline float gelu_grad_f(float u) {
   return cdf + u * pdf;
 }
 
+// Fast variants for the bf16 path: erf from the three-term rational-exponential formula of
+// Abramowitz & Stegun 7.1.25 (|error| <= 2.5e-5, far below bf16 resolution); the Gaussian factor
+// is shared between Phi and phi.  One reciprocal and one exp2 per element.
+__device__ inline void gelu_parts_fast(float u, float& cdf, float& pdf) {
+  float x = fabsf(u) * 0.70710678118654752440f;
+  float t = __builtin_amdgcn_rcpf(fmaf(0.47047f, x, 1.0f));
+  float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);   // exp(-x^2) = exp(-u^2/2)
+  float poly = t * fmaf(t, fmaf(t, 0.7478556f, -0.0958798f), 0.3480242f);
+  float erfc_half = 0.5f * poly * e;                                 // (1 - erf(x)) / 2
+  cdf = u >= 0.f ? 1.0f - erfc_half : erfc_half;
+  pdf = 0.39894228040143267794f * e;
+}
+__device__ inline float gelu_fast(float u) {
+  float c, p;
+  gelu_parts_fast(u, c, p);
+  return u * c;
+}
+__device__ inline float gelu_grad_fast(float u) {
+  float c, p;
+  gelu_parts_fast(u, c, p);
+  return fmaf(u, p, c);
+}
+
 // ---- GEMM interface -------------------------------------------------------------------------
 // C(m,n) = sum_k A(m,k) * B(n,k), fp32 accumulation, followed by an epilogue.
 // Each operand has unit stride along exactly one of its two indices:

@@ -154,12 +154,12 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
   if (e.act == EPI_GELU) {
     if (e.out2) *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(e.out2) + o) = pack8(v);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = gelu_f(v[i]);
+    for (int i = 0; i < 8; ++i) v[i] = gelu_fast(v[i]);
   } else if (e.act == EPI_MUL_GELU_GRAD) {
     float u[8];
     unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n), u);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_f(u[i]);
+    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_fast(u[i]);
   } else if (e.act == EPI_ADD) {
     float u[8];
     unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n), u);

@@ -674,7 +674,8 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   }
   HIP_TRY(hipMemcpyAsync(m->h_loss, m->loss, 4, hipMemcpyDeviceToHost, s));
   // S7: head backward
-  RC(bias_grad(m, m->dz, m->Vp, Mr, m->V, Gf(m, th + H_BOUT)));
+  // over the padded vocabulary (the padded columns of dZ are zero and the output bias reserves them)
+  RC(bias_grad(m, m->dz, m->Vp, Mr, m->Vp, Gf(m, th + H_BOUT)));
   if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD)));
   // few output tiles, contraction over the whole vocabulary: split it
   RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr, true));

@@ -634,6 +634,65 @@ __global__ void __launch_bounds__(256) k_ce(const float* __restrict__ logits, in
     lse_out[j] = lse;
   }
 }
+// Same, with the row of logits resident in LDS (V*4 bytes of dynamic LDS): one global read of the
+// logits and one write of dZ per row, 1024 threads per row.
+template <typename AT>
+__global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
+                                                 int M, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
+                                                 float* __restrict__ lse_out) {
+  extern __shared__ __attribute__((aligned(16))) float row[];
+  __shared__ float sh[16];
+  const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  AT* d = dz + (size_t)j * ldz;
+  if (j >= M) {
+    for (int c = tid * 4; c < ldz; c += 4096) store4(d + c, make_float4(0, 0, 0, 0));
+    return;
+  }
+  const float* z = logits + (size_t)j * ldz;
+  const int V4 = V & ~3;
+  float mx = -INFINITY;
+  for (int c = tid * 4; c < V4; c += 4096) {
+    float4 v = load4(z + c);
+    *reinterpret_cast<float4*>(row + c) = v;
+    mx = fmaxf(mx, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+  }
+  for (int c = V4 + tid; c < V; c += 1024) {
+    float v = z[c];
+    row[c] = v;
+    mx = fmaxf(mx, v);
+  }
+  mx = wave_max(mx);
+  if (lane == 0) sh[wave] = mx;
+  __syncthreads();
+  mx = sh[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, sh[w]);
+  float se = 0.f;
+  for (int c = tid; c < V; c += 1024) se += __expf(row[c] - mx);
+  se = wave_sum(se);
+  __syncthreads();
+  if (lane == 0) sh[wave] = se;
+  __syncthreads();
+  se = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) se += sh[w];
+  const float lse = mx + __logf(se);
+  const int y = lab[j];
+  const float invM = 1.0f / (float)M;
+  for (int c = tid * 4; c < ldz; c += 4096) {
+    float o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int cc = c + i;
+      o[i] = cc < V ? (__expf(row[cc] - lse) - (cc == y ? 1.0f : 0.0f)) * invM : 0.f;
+    }
+    store4(d + c, make_float4(o[0], o[1], o[2], o[3]));
+  }
+  if (tid == 0) {
+    row_loss[j] = lse - row[y];
+    lse_out[j] = lse;
+  }
+}
 __global__ void __launch_bounds__(256) k_mean_rows(const float* __restrict__ v, int M, float* __restrict__ out) {
   __shared__ float sh[256];
   float acc = 0.f;
@@ -648,11 +707,27 @@ __global__ void __launch_bounds__(256) k_mean_rows(const float* __restrict__ v, 
 }
 hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mpad, int V, void* dz,
                       float* row_loss, float* lse, float* loss_out, hipStream_t s) {
-  if (dtype == 0)
+  const size_t row_bytes = (size_t)V * 4;
+  hipError_t e;
+  if (row_bytes <= 150 * 1024 && ldz % 4 == 0) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_ce_lds<float>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024)) != hipSuccess) return e;
+      if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_ce_lds<bf16>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024)) != hipSuccess) return e;
+      attr_set = true;
+    }
+    if (dtype == 0)
+      k_ce_lds<float><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, V, (float*)dz, row_loss, lse);
+    else
+      k_ce_lds<bf16><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, V, (bf16*)dz, row_loss, lse);
+  } else if (dtype == 0) {
     k_ce<float><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, V, (float*)dz, row_loss, lse);
-  else
+  } else {
     k_ce<bf16><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, V, (bf16*)dz, row_loss, lse);
-  hipError_t e = hipGetLastError();
+  }
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   k_mean_rows<<<dim3(1), dim3(256), 0, s>>>(row_loss, M, loss_out);
   return hipGetLastError();
