@@ -60,6 +60,22 @@ def profile_steps(model, cbatches, f, k, emb, opt, steps):
     return prof
 
 
+PMC_TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_gemm_mfma_base_3f3t_64x128_pmc_traffic.txt")
+
+
+def recorded_gemm_traffic():
+    """HBM-side bytes per GEMM launch from the committed rocprofv3 --pmc summary, or None if the kernel
+    source has changed since those counters were taken (or no summary exists)."""
+    from paper_2011_13635_amd.pmc_summary import kernel_source_hash
+    try:
+        fields = dict(line.split(":", 1) for line in open(PMC_TRAFFIC_FILE) if ":" in line and not line.startswith(" "))
+        if fields["kernel_source_sha256"].strip() != kernel_source_hash():
+            return None
+        return float(fields["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +83,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-compare", action="store_true", help="skip the final-stage vs full-step comparison")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference dispatch for scaling FETCH_SIZE/WRITE_SIZE "
+                         "counters when this script runs under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -89,6 +108,14 @@ def main():
     model.mslt_load_params(synth.pack_weights(shape, W))
     cb = [model.device_batch(b) for b in batches]
     opt = binding.adam(lr=1e-4)
+
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")   # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     sec, loss = time_steps(torch, model, cb, f, k, False, opt, args.steps, args.warmup)
     tokens = B * S
@@ -127,7 +154,9 @@ def main():
                    "predicted_per_step": int(len(batches[0]["masked_positions"])), "loss": round(float(loss), 5)},
         "roofline": {"bound": "mfma", "kernel": "k_gemm_mfma (all layouts)", "achieved": round(achieved, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "launches_per_step": round(g_launch, 1),
+                     "traffic": recorded_gemm_traffic(), "traffic_unit": "bytes per launch (L2-miss side, FETCH_SIZE + "
+                     "WRITE_SIZE scaled by a 256 MiB copy)", "algorithmic_bytes_per_launch":
+                     round(sum(v["bytes"] for v in gemm) / max(g_launch, 1)), "launches_per_step": round(g_launch, 1),
                      "avg_launch_us": round(g_ms * 1e3 / max(g_launch, 1), 2),
                      "gemm_ms_per_step": round(g_ms, 4), "gemm_gflop_per_step": round(g_flops / 1e9, 1)},
         "kernel_classes": classes,

@@ -1,0 +1,59 @@
+"""Summarises two rocprofv3 --pmc runs of bench.py (FETCH_SIZE, WRITE_SIZE; csv output) into the HBM-side traffic of
+the MFMA GEMM kernel per launch, scaled by what the same counters read for the plain 256 MiB device copy that
+`bench.py --copy-calibration` issues.  Also records the hash of the kernel source so that bench.py can tell
+whether the figure still belongs to the kernel it times.
+
+usage: python -m paper_2011_13635_amd.pmc_summary <fetch_counter_collection.csv> <write_counter_collection.csv> <steps_in_run>
+"""
+from __future__ import annotations
+
+import csv
+import hashlib
+import os
+import sys
+
+KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "gemm_mfma.hip")
+COPY_BYTES = 256 * 1024 * 1024
+
+
+def kernel_source_hash() -> str:
+    return hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+
+
+def read_counter(path):
+    copy_kib, gemm = 0.0, {}
+    for r in csv.DictReader(open(path)):
+        name, v = r["Kernel_Name"], float(r["Counter_Value"])
+        if "copyBuffer" in name:
+            copy_kib = max(copy_kib, v)
+        elif "k_gemm_mfma" in name:
+            n, s = gemm.get(name, (0, 0.0))
+            gemm[name] = (n + 1, s + v)
+    return copy_kib, gemm
+
+
+def main():
+    fetch_csv, write_csv, steps = sys.argv[1], sys.argv[2], int(sys.argv[3])
+    out = [f"kernel_source_sha256: {kernel_source_hash()}"]
+    total = 0.0
+    launches = 0
+    for label, path in (("FETCH_SIZE", fetch_csv), ("WRITE_SIZE", write_csv)):
+        copy_kib, gemm = read_counter(path)
+        factor = COPY_BYTES / (copy_kib * 1024.0)
+        out.append(f"{label}: 256 MiB copy reads {copy_kib:.0f} KiB -> scale factor {factor:.4f}")
+        n_all = 0
+        for name, (n, s) in sorted(gemm.items()):
+            out.append(f"  {name}: {n} dispatches, {s:.0f} KiB raw, {s * 1024 * factor / steps / 1e9:.4f} GB per step")
+            total += s * 1024 * factor
+            n_all += n
+        launches = n_all
+    per_step = total / steps
+    out.append(f"steps_in_run: {steps}")
+    out.append(f"gemm_launches_per_step: {launches / steps:.1f}")
+    out.append(f"traffic_bytes_per_step: {per_step:.0f}")
+    out.append(f"traffic_bytes_per_launch: {per_step / (launches / steps):.0f}")
+    sys.stdout.write("\n".join(out) + "\n")
+
+
+if __name__ == "__main__":
+    main()
