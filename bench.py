@@ -76,6 +76,53 @@ def recorded_gemm_traffic():
         return None
 
 
+def gemm_roofline(prof):
+    gemm = [v for n, v in prof.items() if n.startswith("gemm_mfma")]
+    flops, ms = sum(v["flops"] for v in gemm), sum(v["ms"] for v in gemm)
+    tf = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+    return {"achieved_TFLOPs": round(tf, 1), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4), "gemm_ms": round(ms, 4)}
+
+
+def extra_workloads(torch, binding, synth, steps):
+    """The other configurations of the stage step (parity-test cases, timed here for the record): each MSLT step
+    next to the same kernels with every layer and the embeddings trainable."""
+    res = {}
+    cases = [
+        ("base_final_64x128", synth.bert_base_shape(12), 64, 128, [(9, 3, False)], binding.adam(lr=1e-4)),
+        ("base_final_16x512", synth.bert_base_shape(12), 16, 512, [(9, 3, False)], binding.adam(lr=1e-4)),
+        ("large_final_64x128_lamb", synth.bert_large_shape(24), 64, 128, [(18, 6, False)], binding.lamb()),
+        ("large_sweep_32x512_lamb", synth.bert_large_shape(24), 32, 512,
+         [(0, 6, True), (6, 6, False), (12, 6, False), (18, 6, False)], binding.lamb()),
+    ]
+    for name, shape, B, S, stages, opt in cases:
+        W = synth.make_weights(shape, seed=0)
+        batches = [synth.make_batch(shape, B, S, seed=1 + i) for i in range(2)]
+        n_pred = max(len(b["masked_positions"]) for b in batches)
+        m = binding.Model(binding.make_config(shape, B, S, 1, max_predictions=n_pred + 64))
+        m.mslt_load_params(synth.pack_weights(shape, W))
+        del W
+        cb = [m.device_batch(b) for b in batches]
+        tokens = B * S
+        entry = {"tokens_per_step": tokens, "stages": []}
+        for f, k, emb in stages:
+            sec, loss = time_steps(torch, m, cb, f, k, emb, opt, steps, 2)
+            prof = profile_steps(m, cb, f, k, emb, opt, min(steps, 4))
+            entry["stages"].append({"frozen": f, "trainable": k, "train_embeddings": emb, "ms_per_step": round(sec * 1e3, 4),
+                                    "tokens_per_s": round(tokens / sec, 1), **gemm_roofline(prof)})
+        sec_full, _ = time_steps(torch, m, cb, 0, shape.n_layers, True, opt, steps, 2)
+        entry["full_step_ms"] = round(sec_full * 1e3, 4)
+        entry["full_tokens_per_s"] = round(tokens / sec_full, 1)
+        entry["speedup_last_stage_vs_full"] = round(sec_full / (entry["stages"][-1]["ms_per_step"] * 1e-3), 3)
+        if len(stages) > 1:   # schedule: equal step counts per stage against the same number of full steps
+            total = sum(st["ms_per_step"] for st in entry["stages"])
+            entry["schedule_time_ratio_full_over_mslt"] = round(len(stages) * sec_full * 1e3 / total, 3)
+        res[name] = entry
+        m.close()
+        del m
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +130,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-compare", action="store_true", help="skip the final-stage vs full-step comparison")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time the BERT-Base final stage (64x128, 16x512), BERT-Large final stage and the "
+                         "BERT-Large stage sweep at 32x512 (several minutes)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling FETCH_SIZE/WRITE_SIZE "
                          "counters when this script runs under rocprofv3 --pmc)")
@@ -204,6 +254,8 @@ def main():
                                "sample": "one full stage step + Adam update of the same workload "
                                          f"(batch 64 x seq 128, {tokens} tokens), float64 numpy",
                                "seconds": round(dt, 2), "oracle_loss": round(float(ref_loss), 5)}
+    if args.all_configs:
+        out["other_configs"] = extra_workloads(torch, binding, synth, max(4, min(args.steps, 8)))
     print(json.dumps(out))
     return 0
 

@@ -112,7 +112,9 @@ hipError_t gemm_simt(int dtype, const GemmDesc& d, hipStream_t s);
 bool gemm_mfma_supported(const GemmDesc& d);
 // force_tile_m: 0 = choose the M-tile height (128 or 256 rows) from the shape.
 int gemm_mfma_tile_m(const GemmDesc& d);
-hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s, int force_tile_m = 0);
+// force_dma: -1 = default choice, 0/1 = k-contiguous operands through registers / direct to LDS.
+hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s, int force_tile_m = 0,
+                     int force_dma = -1);
 
 // ---- attention ------------------------------------------------------------------------------
 struct AttnDesc {

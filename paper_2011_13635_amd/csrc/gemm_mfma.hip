@@ -127,6 +127,31 @@ __device__ __forceinline__ void store_slab(bf16* __restrict__ lds, int tid, cons
   store_part<KC, ROWS, NT, 3>(lds, tid, s);
 }
 
+// Direct global -> LDS load of quarter Q of a k-contiguous slab (no register staging): lane i of
+// a wavefront lands at its LDS base + 16*i bytes, i.e. eight whole 128-byte rows per instruction,
+// so each lane fetches the global chunk that belongs at its (row, swizzled chunk) position.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+template <int ROWS, int NT, int Q>
+__device__ __forceinline__ void dma_part(const bf16* __restrict__ base, int ld, int row0, int k0, int tid, bf16* lds) {
+  constexpr int LPT = ROWS * 8 / NT;
+  if constexpr (LPT == 4 || (Q & 1) == 0) {
+    constexpr int I = LPT == 4 ? Q : Q / 2;
+    const int row = (tid >> 3) + (NT / 8) * I;
+    const int c = (tid & 7) ^ swz(row);
+    const bf16* src = base + (size_t)(row0 + row) * ld + k0 + 8 * c;
+    const int wave_row0 = __builtin_amdgcn_readfirstlane((tid >> 6) * 8 + (NT / 8) * I);
+    __builtin_amdgcn_global_load_lds((global_void_t*)src, (lds_void_t*)(lds + wave_row0 * BK), 16, 0, 0);
+  }
+}
+template <int ROWS, int NT>
+__device__ __forceinline__ void dma_slab(const bf16* __restrict__ base, int ld, int row0, int k0, int tid, bf16* lds) {
+  dma_part<ROWS, NT, 0>(base, ld, row0, k0, tid, lds);
+  dma_part<ROWS, NT, 1>(base, ld, row0, k0, tid, lds);
+  dma_part<ROWS, NT, 2>(base, ld, row0, k0, tid, lds);
+  dma_part<ROWS, NT, 3>(base, ld, row0, k0, tid, lds);
+}
+
 __device__ __forceinline__ bf16x8_t lds_frag(const bf16* __restrict__ lds, int row, int chunk) {
   return *reinterpret_cast<const bf16x8_t*>(lds + row * BK + 8 * (chunk ^ swz(row)));
 }
@@ -176,8 +201,13 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
 }
 
 // ---- the kernel -----------------------------------------------------------------------------
-template <int BM, bool A_KC, bool B_KC>
+// Operand modes: how an operand slab gets from global memory into LDS.
+enum { OP_STRIDED = 0, OP_KC = 1, OP_KC_DMA = 2 };
+
+template <int BM, int AMODE, int BMODE>
 __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
+  constexpr bool A_KC = AMODE != OP_STRIDED, B_KC = BMODE != OP_STRIDED;
+  constexpr bool A_DMA = AMODE == OP_KC_DMA, B_DMA = BMODE == OP_KC_DMA;
   constexpr int NT = 2 * BM;                       // threads: BM/64 x 2 wavefronts
   constexpr int STAGE_ELEMS = (BM + BN) * BK;      // bf16 elements per pipeline stage
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -219,15 +249,20 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
   // set has a static name, and its body is branch-free (tile indices past the end are clamped: the
   // duplicate loads and the last LDS store are never consumed), which lets the compiler keep the
   // loads of later tiles in flight across iterations instead of draining them at every join.
+  // An operand in OP_KC_DMA mode skips the registers: the slab of tile kt+1 is loaded straight into
+  // LDS stage (kt+1)&1 during iteration kt and awaited (vmcnt) before the closing barrier.
   Slab ra[PF], rb[PF];
 #pragma unroll
   for (int j = 0; j < PF; ++j) {
     int t = j < nk ? j : nk - 1;
-    load_slab<A_KC, BM, NT>(p.A, p.lda, m0, kbeg + t * BK, tid, ra[j]);
-    load_slab<B_KC, BN, NT>(p.B, p.ldb, n0, kbeg + t * BK, tid, rb[j]);
+    if constexpr (!A_DMA) load_slab<A_KC, BM, NT>(p.A, p.lda, m0, kbeg + t * BK, tid, ra[j]);
+    if constexpr (!B_DMA) load_slab<B_KC, BN, NT>(p.B, p.ldb, n0, kbeg + t * BK, tid, rb[j]);
   }
-  store_slab<A_KC, BM, NT>(lds, tid, ra[0]);
-  store_slab<B_KC, BN, NT>(lds + BM * BK, tid, rb[0]);
+  if constexpr (A_DMA) dma_slab<BM, NT>(p.A, p.lda, m0, kbeg, tid, lds);
+  else store_slab<A_KC, BM, NT>(lds, tid, ra[0]);
+  if constexpr (B_DMA) dma_slab<BN, NT>(p.B, p.ldb, n0, kbeg, tid, lds + BM * BK);
+  else store_slab<B_KC, BN, NT>(lds + BM * BK, tid, rb[0]);
+  if constexpr (A_DMA || B_DMA) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
 
   const int arow = 64 * wm + (lane & 31), brow = 64 * wn + (lane & 31), half = lane >> 5;
@@ -241,7 +276,8 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
     bf16* da = lds + ((kt + 1) & 1) * STAGE_ELEMS;
     bf16* db = da + BM * BK;
     const int tn2 = kt + PF < nk ? kt + PF : nk - 1;
-    const int kn = kbeg + tn2 * BK;
+    const int kn = kbeg + tn2 * BK;                                  // register prefetch: tile kt+PF
+    const int kd = kbeg + (kt + 1 < nk ? kt + 1 : nk - 1) * BK;      // direct loads: tile kt+1
     bf16x8_t fa[2][2], fb[2][2];
     fa[0][0] = lds_frag(sa, arow, half);
     fa[0][1] = lds_frag(sa, arow + 32, half);
@@ -256,14 +292,16 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
         fb[nxt][0] = lds_frag(sb, brow, 2 * ((KS) + 1) + half);                                     \
         fb[nxt][1] = lds_frag(sb, brow + 32, 2 * ((KS) + 1) + half);                                \
       }                                                                                             \
-      load_part<A_KC, BM, NT, (KS)>(p.A, p.lda, m0, kn, tid, la);                                   \
-      load_part<B_KC, BN, NT, (KS)>(p.B, p.ldb, n0, kn, tid, lb);                                   \
+      if constexpr (A_DMA) dma_part<BM, NT, (KS)>(p.A, p.lda, m0, kd, tid, da);                     \
+      else load_part<A_KC, BM, NT, (KS)>(p.A, p.lda, m0, kn, tid, la);                              \
+      if constexpr (B_DMA) dma_part<BN, NT, (KS)>(p.B, p.ldb, n0, kd, tid, db);                     \
+      else load_part<B_KC, BN, NT, (KS)>(p.B, p.ldb, n0, kn, tid, lb);                              \
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][0], acc[0][0], 0, 0, 0); \
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][1], acc[0][1], 0, 0, 0); \
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][0], acc[1][0], 0, 0, 0); \
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur][1], acc[1][1], 0, 0, 0); \
-      store_part<A_KC, BM, NT, (KS)>(da, tid, na);                                                  \
-      store_part<B_KC, BN, NT, (KS)>(db, tid, nb);                                                  \
+      if constexpr (!A_DMA) store_part<A_KC, BM, NT, (KS)>(da, tid, na);                            \
+      if constexpr (!B_DMA) store_part<B_KC, BN, NT, (KS)>(db, tid, nb);                            \
       __builtin_amdgcn_sched_barrier(0);                                                            \
     }
     MSLT_GEMM_STEP(0)
@@ -271,6 +309,7 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
     MSLT_GEMM_STEP(2)
     MSLT_GEMM_STEP(3)
 #undef MSLT_GEMM_STEP
+    if constexpr (A_DMA || B_DMA) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): direct loads landed
     __syncthreads();
   };
   int kt = 0;
@@ -359,33 +398,32 @@ int gemm_mfma_tile_m(const GemmDesc& d) {
   return (d.M % 256 == 0 && d.K >= 4096 && (d.M / 256) * (d.N / BN) >= 256) ? 256 : 128;
 }
 
-template <int BM>
-static hipError_t launch(const GemmDesc& d, const MfmaParams& p, dim3 grid, hipStream_t s) {
+template <int BM, int AMODE, int BMODE>
+static hipError_t launch_mode(const MfmaParams& p, dim3 grid, hipStream_t s) {
   constexpr int LDS = lds_bytes(BM);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e;
-    const void* fns[4] = {reinterpret_cast<const void*>(k_gemm_mfma<BM, true, true>),
-                          reinterpret_cast<const void*>(k_gemm_mfma<BM, true, false>),
-                          reinterpret_cast<const void*>(k_gemm_mfma<BM, false, true>),
-                          reinterpret_cast<const void*>(k_gemm_mfma<BM, false, false>)};
-    for (const void* f : fns)
-      if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, LDS)) != hipSuccess) return e;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_mfma<BM, AMODE, BMODE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 block(2 * BM);
-  if (d.a_kcontig && d.b_kcontig)
-    k_gemm_mfma<BM, true, true><<<grid, block, LDS, s>>>(p);
-  else if (d.a_kcontig && !d.b_kcontig)
-    k_gemm_mfma<BM, true, false><<<grid, block, LDS, s>>>(p);
-  else if (!d.a_kcontig && d.b_kcontig)
-    k_gemm_mfma<BM, false, true><<<grid, block, LDS, s>>>(p);
-  else
-    k_gemm_mfma<BM, false, false><<<grid, block, LDS, s>>>(p);
+  k_gemm_mfma<BM, AMODE, BMODE><<<grid, dim3(2 * BM), LDS, s>>>(p);
   return hipGetLastError();
 }
+// k-contiguous operands go global -> LDS directly (use_dma) or through registers
+template <int BM>
+static hipError_t launch(const GemmDesc& d, const MfmaParams& p, dim3 grid, hipStream_t s, bool use_dma) {
+  if (d.a_kcontig && d.b_kcontig)
+    return use_dma ? launch_mode<BM, OP_KC_DMA, OP_KC_DMA>(p, grid, s) : launch_mode<BM, OP_KC, OP_KC>(p, grid, s);
+  if (d.a_kcontig && !d.b_kcontig)
+    return use_dma ? launch_mode<BM, OP_KC_DMA, OP_STRIDED>(p, grid, s) : launch_mode<BM, OP_KC, OP_STRIDED>(p, grid, s);
+  if (!d.a_kcontig && d.b_kcontig)
+    return use_dma ? launch_mode<BM, OP_STRIDED, OP_KC_DMA>(p, grid, s) : launch_mode<BM, OP_STRIDED, OP_KC>(p, grid, s);
+  return launch_mode<BM, OP_STRIDED, OP_STRIDED>(p, grid, s);
+}
 
-hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s, int force_tile_m) {
+hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s, int force_tile_m, int force_dma) {
   if (!gemm_mfma_supported(d)) return hipErrorInvalidValue;
   if (splitk < 1 || splitk > d.K / BK) return hipErrorInvalidValue;
   if (splitk > 1 && partials == nullptr) return hipErrorInvalidValue;
@@ -401,7 +439,11 @@ hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t
   p.partials = partials;
   p.epi = d.epi;
   dim3 grid((unsigned)(p.tiles_m * p.tiles_n * splitk));
-  hipError_t e = bm == 256 ? launch<256>(d, p, grid, s) : launch<128>(d, p, grid, s);
+  // Direct global -> LDS loads hide only one iteration of latency (two LDS stages); measured, they win
+  // for NT products whose tiles fit in one round of resident workgroups and lose otherwise.
+  const bool dma_default = d.a_kcontig && d.b_kcontig && bm == 128 && p.tiles_m * p.tiles_n * splitk <= 512;
+  const bool use_dma = force_dma >= 0 ? force_dma != 0 : dma_default;
+  hipError_t e = bm == 256 ? launch<256>(d, p, grid, s, use_dma) : launch<128>(d, p, grid, s, use_dma);
   if (e != hipSuccess || splitk == 1) return e;
   size_t n8 = (size_t)d.M * d.N / 8;
   k_splitk_reduce<<<dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s>>>(partials, splitk, d.M, d.N, d.epi);
