@@ -187,10 +187,13 @@ hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* la
 
 // embedding backward (first stage / retraining only): adds the gather contribution into gword,
 // writes gpos (all gpos_rows rows) and gtype.  rank/order hold T ints, cnt/start round_up(vocab,4)
-// ints, scratch ceil(T/64)*type_vocab*H floats.
+// ints, blockcnt embed_bwd_int_scratch(T, vocab) ints, scratch ceil(T/64)*type_vocab*H floats,
+// partial T*H floats.
+size_t embed_bwd_int_scratch(int T, int vocab);
 hipError_t embed_bwd(int dtype, const void* dz, const int32_t* ids, const int32_t* tt, int B, int S, int H, int vocab,
                      int type_vocab, float* gword, float* gpos, float* gtype, int32_t* rank, int32_t* cnt,
-                     int32_t* start, int32_t* order, int gpos_rows, float* scratch, hipStream_t s);
+                     int32_t* start, int32_t* order, int32_t* blockcnt, int gpos_rows, float* scratch, float* partial,
+                     hipStream_t s);
 
 // ---- optimizer ------------------------------------------------------------------------------
 struct OptTensor {   // one logical tensor, device-side descriptor

@@ -92,7 +92,8 @@ struct mslt_model {
   float *rstd_t, *logits, *row_loss, *lse_t, *loss;
   float *red_scratch; size_t red_floats;
   float *splitk; size_t splitk_floats;
-  int32_t *e_rank, *e_cnt, *e_start, *e_order;
+  int32_t *e_rank, *e_cnt, *e_start, *e_order, *e_blockcnt;
+  float* e_partial;                    // [Tp, H] run sums of the embedding backward
   OptTensor* o_tensors; int32_t* o_chunk_tensor; int32_t* o_tsteps; float* o_chunk_norms; float* o_ratio;
   std::vector<int> first_chunk;  // per tensor, plus total at the end
   // pinned host scalars
@@ -252,6 +253,8 @@ static size_t carve(mslt_model* m, char* base) {
   m->splitk = b.take<float>(m->splitk_floats * 4);
   m->e_rank = b.take<int32_t>(Tp * 4); m->e_order = b.take<int32_t>(Tp * 4);
   m->e_cnt = b.take<int32_t>(rup(m->V, 4) * 4); m->e_start = b.take<int32_t>(rup(m->V, 4) * 4);
+  m->e_partial = b.take<float>(Tp * H * 4);
+  m->e_blockcnt = b.take<int32_t>(rup(embed_bwd_int_scratch((int)Tp, m->V), 4) * 4);
   size_t nt = m->table.size();
   size_t nchunks = (size_t)m->first_chunk.back();
   m->o_tensors = b.take<OptTensor>(nt * sizeof(OptTensor));
@@ -705,8 +708,8 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
     RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), nullptr, T));
     ProfScope ps(m, PC_EMBED_BWD, 0.0, (double)T * H * (m->esz + 8.0));
     HIP_TRY(embed_bwd(m->dtype, m->d_z0, bt->input_ids, bt->token_type_ids, B, S, H, m->V, m->cfg.type_vocab,
-                      Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order,
-                      m->cfg.max_pos, m->red_scratch, s));
+                      Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order, m->e_blockcnt,
+                      m->cfg.max_pos, m->red_scratch, m->e_partial, s));
   }
   HIP_TRY(hipStreamSynchronize(s));
   *loss_out = *m->h_loss;

@@ -734,57 +734,133 @@ hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* la
 }
 
 // ---- embedding backward (first stage and retraining only) -----------------------------------
-// Word rows: tokens are grouped by id with their original order kept inside a group (stable
-// rank by counting earlier equal ids), so each vocabulary row is summed by one workgroup in
-// ascending token order: deterministic, no floating-point atomics.
-__global__ void k_token_rank(const int32_t* __restrict__ ids, int T, int32_t* __restrict__ rank, int32_t* __restrict__ cnt) {
+// Word rows: tokens are grouped by id with their original order kept inside a group (a stable
+// counting sort), so each vocabulary row is summed in ascending token order: deterministic, no
+// floating-point atomics.  Stable position of token t = start[id] + (occurrences of id in earlier
+// blocks of 256 tokens) + (occurrences earlier in t's own block).
+constexpr int RK_BLOCK = 256;
+__global__ void __launch_bounds__(RK_BLOCK) k_rank_local(const int32_t* __restrict__ ids, int T, int V,
+                                                        int32_t* __restrict__ rank, int32_t* __restrict__ blockcnt) {
+  __shared__ int tile[RK_BLOCK];
+  const int t = blockIdx.x * RK_BLOCK + threadIdx.x;
+  const int id = t < T ? ids[t] : -1;
+  tile[threadIdx.x] = id;
+  __syncthreads();
+  int before = 0, after = 0;
+#pragma unroll 8
+  for (int j = 0; j < RK_BLOCK; ++j) {
+    int same = tile[j] == id ? 1 : 0;
+    before += (j < (int)threadIdx.x) ? same : 0;
+    after += (j > (int)threadIdx.x) ? same : 0;
+  }
+  if (t < T) {
+    rank[t] = before;
+    if (after == 0) blockcnt[(size_t)blockIdx.x * V + id] = before + 1;   // last occurrence in the block
+  }
+}
+// per id: exclusive prefix over the blocks (in place) and the total count
+__global__ void k_block_prefix(int32_t* __restrict__ blockcnt, int nblocks, int V, int32_t* __restrict__ cnt) {
+  int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= V) return;
+  int run = 0;
+  for (int b = 0; b < nblocks; ++b) {
+    int c = blockcnt[(size_t)b * V + v];
+    blockcnt[(size_t)b * V + v] = run;
+    run += c;
+  }
+  cnt[v] = run;
+}
+// exclusive scan of n ints in three small launches: 1024-element blocks, their totals, the fix-up
+__global__ void __launch_bounds__(1024) k_scan_blocks(const int32_t* __restrict__ in, int n, int32_t* __restrict__ out,
+                                                      int32_t* __restrict__ totals) {
+  __shared__ int sc[1024];
+  int i = blockIdx.x * 1024 + threadIdx.x;
+  int v = i < n ? in[i] : 0;
+  sc[threadIdx.x] = v;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int a = (int)threadIdx.x >= o ? sc[threadIdx.x - o] : 0;
+    __syncthreads();
+    sc[threadIdx.x] += a;
+    __syncthreads();
+  }
+  if (i < n) out[i] = sc[threadIdx.x] - v;
+  if (threadIdx.x == 1023) totals[blockIdx.x] = sc[1023];
+}
+__global__ void __launch_bounds__(1024) k_scan_totals(int32_t* __restrict__ totals, int nb) {
+  __shared__ int sc[1024];
+  int v = (int)threadIdx.x < nb ? totals[threadIdx.x] : 0;
+  sc[threadIdx.x] = v;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int a = (int)threadIdx.x >= o ? sc[threadIdx.x - o] : 0;
+    __syncthreads();
+    sc[threadIdx.x] += a;
+    __syncthreads();
+  }
+  if ((int)threadIdx.x < nb) totals[threadIdx.x] = sc[threadIdx.x] - v;
+}
+__global__ void __launch_bounds__(1024) k_scan_add(int32_t* __restrict__ out, int n, const int32_t* __restrict__ totals) {
+  int i = blockIdx.x * 1024 + threadIdx.x;
+  if (i < n) out[i] += totals[blockIdx.x];
+}
+__global__ void k_token_order(const int32_t* __restrict__ ids, const int32_t* __restrict__ rank,
+                              const int32_t* __restrict__ start, const int32_t* __restrict__ blockcnt, int T, int V,
+                              int32_t* __restrict__ order) {
   int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= T) return;
   int id = ids[t];
-  int r = 0;
-  for (int u = 0; u < t; ++u) r += (ids[u] == id) ? 1 : 0;
-  rank[t] = r;
-  atomicAdd(&cnt[id], 1);
+  order[start[id] + blockcnt[(size_t)(t / RK_BLOCK) * V + id] + rank[t]] = t;
 }
-__global__ void __launch_bounds__(1024) k_exclusive_scan(const int32_t* __restrict__ cnt, int n, int32_t* __restrict__ start) {
-  __shared__ int sc[1024];
-  int tid = threadIdx.x;
-  int per = (n + 1023) / 1024;
-  int b = tid * per, e = min(n, b + per);
-  int c = 0;
-  for (int i = b; i < e; ++i) c += cnt[i];
-  sc[tid] = c;
-  __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    int v = tid >= o ? sc[tid - o] : 0;
-    __syncthreads();
-    sc[tid] += v;
-    __syncthreads();
-  }
-  int off = sc[tid] - c;
-  for (int i = b; i < e; ++i) {
-    start[i] = off;
-    off += cnt[i];
-  }
+size_t embed_bwd_int_scratch(int T, int vocab) {   // ints: per-block counts + scan totals
+  return (size_t)((T + RK_BLOCK - 1) / RK_BLOCK) * vocab + 1024;
 }
-__global__ void k_token_order(const int32_t* __restrict__ ids, const int32_t* __restrict__ rank,
-                              const int32_t* __restrict__ start, int T, int32_t* __restrict__ order) {
-  int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= T) return;
-  order[start[ids[t]] + rank[t]] = t;
-}
+// Level 1: the id-sorted token list is cut into chunks of WG_CHUNK positions; a workgroup adds, in
+// order, the rows of every run of equal ids inside its chunk and leaves the sum at the row of the
+// run's first position in `partial` [T, H].
+constexpr int WG_CHUNK = 32;
 template <typename AT>
-__global__ void __launch_bounds__(256) k_word_grad(const AT* __restrict__ dz, const int32_t* __restrict__ cnt,
-                                                   const int32_t* __restrict__ start, const int32_t* __restrict__ order,
-                                                   int H, float* __restrict__ gword) {
-  int v = blockIdx.x;
-  int n = cnt[v];
+__global__ void __launch_bounds__(256) k_word_grad_chunks(const AT* __restrict__ dz, const int32_t* __restrict__ ids,
+                                                          const int32_t* __restrict__ order, int T, int H,
+                                                          float* __restrict__ partial) {
+  __shared__ int tok[WG_CHUNK], tid_of[WG_CHUNK];
+  const int p0 = blockIdx.x * WG_CHUNK, n = min(WG_CHUNK, T - p0);
+  if ((int)threadIdx.x < n) {
+    int t = order[p0 + threadIdx.x];
+    tok[threadIdx.x] = t;
+    tid_of[threadIdx.x] = ids[t];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x * 4; c < H; c += 1024) {
+    float4 acc = make_float4(0, 0, 0, 0);
+    int run_start = 0;
+    for (int i = 0; i < n; ++i) {
+      if (i > 0 && tid_of[i] != tid_of[i - 1]) {
+        store4(partial + (size_t)(p0 + run_start) * H + c, acc);
+        acc = make_float4(0, 0, 0, 0);
+        run_start = i;
+      }
+      float4 v = load4(dz + (size_t)tok[i] * H + c);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    store4(partial + (size_t)(p0 + run_start) * H + c, acc);
+  }
+}
+// Level 2: one workgroup per vocabulary row adds the row's chunk partials in chunk order.
+__global__ void __launch_bounds__(256) k_word_grad_rows(const float* __restrict__ partial, const int32_t* __restrict__ cnt,
+                                                        const int32_t* __restrict__ start, int H,
+                                                        float* __restrict__ gword) {
+  const int v = blockIdx.x, n = cnt[v];
   if (n == 0) return;
-  int s0 = start[v];
-  for (int c = threadIdx.x; c < H; c += 256) {
-    float acc = 0.f;
-    for (int i = 0; i < n; ++i) acc += ldf(dz + (size_t)order[s0 + i] * H + c);
-    gword[(size_t)v * H + c] += acc;
+  const int s0 = start[v], s1 = s0 + n;
+  for (int c = threadIdx.x * 4; c < H; c += 1024) {
+    float4 acc = make_float4(0, 0, 0, 0);
+    for (int p = s0; p < s1; p = (p / WG_CHUNK + 1) * WG_CHUNK) {   // run of v in each chunk starts at p
+      float4 x = load4(partial + (size_t)p * H + c);
+      acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    }
+    float4 g = load4(gword + (size_t)v * H + c);
+    store4(gword + (size_t)v * H + c, make_float4(g.x + acc.x, g.y + acc.y, g.z + acc.z, g.w + acc.w));
   }
 }
 template <typename AT>
@@ -815,14 +891,22 @@ __global__ void __launch_bounds__(256) k_type_partial(const AT* __restrict__ dz,
 template <typename AT>
 static hipError_t embed_bwd_t(const AT* dz, const int32_t* ids, const int32_t* tt, int B, int S, int H, int vocab,
                               int type_vocab, float* gword, float* gpos, float* gtype, int32_t* rank, int32_t* cnt,
-                              int32_t* start, int32_t* order, int gpos_rows, float* scratch, hipStream_t s) {
+                              int32_t* start, int32_t* order, int32_t* blockcnt, int gpos_rows, float* scratch, float* partial,
+                              hipStream_t s) {
   int T = B * S;
-  hipError_t e = fill_zero(cnt, (size_t)((vocab + 3) / 4) * 16, s);
+  int nblk = (T + RK_BLOCK - 1) / RK_BLOCK, nsb = (vocab + 1023) / 1024;
+  if (nsb > 1024) return hipErrorInvalidValue;   // vocabulary above 2^20 rows is not supported here
+  int32_t* totals = blockcnt + (size_t)nblk * vocab;
+  hipError_t e = fill_zero(blockcnt, ((size_t)nblk * vocab + 3) / 4 * 16, s);
   if (e != hipSuccess) return e;
-  k_token_rank<<<dim3((T + 255) / 256), dim3(256), 0, s>>>(ids, T, rank, cnt);
-  k_exclusive_scan<<<dim3(1), dim3(1024), 0, s>>>(cnt, vocab, start);
-  k_token_order<<<dim3((T + 255) / 256), dim3(256), 0, s>>>(ids, rank, start, T, order);
-  k_word_grad<AT><<<dim3(vocab), dim3(256), 0, s>>>(dz, cnt, start, order, H, gword);
+  k_rank_local<<<dim3(nblk), dim3(RK_BLOCK), 0, s>>>(ids, T, vocab, rank, blockcnt);
+  k_block_prefix<<<dim3((vocab + 255) / 256), dim3(256), 0, s>>>(blockcnt, nblk, vocab, cnt);
+  k_scan_blocks<<<dim3(nsb), dim3(1024), 0, s>>>(cnt, vocab, start, totals);
+  k_scan_totals<<<dim3(1), dim3(1024), 0, s>>>(totals, nsb);
+  k_scan_add<<<dim3(nsb), dim3(1024), 0, s>>>(start, vocab, totals);
+  k_token_order<<<dim3((T + 255) / 256), dim3(256), 0, s>>>(ids, rank, start, blockcnt, T, vocab, order);
+  k_word_grad_chunks<AT><<<dim3((T + WG_CHUNK - 1) / WG_CHUNK), dim3(256), 0, s>>>(dz, ids, order, T, H, partial);
+  k_word_grad_rows<<<dim3(vocab), dim3(256), 0, s>>>(partial, cnt, start, H, gword);
   size_t np = (size_t)gpos_rows * H;
   k_pos_grad<AT><<<dim3((unsigned)((np + 255) / 256)), dim3(256), 0, s>>>(dz, B, S, H, gpos_rows, gpos);
   int nchunks = (T + CS_ROWS - 1) / CS_ROWS;
@@ -832,12 +916,13 @@ static hipError_t embed_bwd_t(const AT* dz, const int32_t* ids, const int32_t* t
 }
 hipError_t embed_bwd(int dtype, const void* dz, const int32_t* ids, const int32_t* tt, int B, int S, int H, int vocab,
                      int type_vocab, float* gword, float* gpos, float* gtype, int32_t* rank, int32_t* cnt,
-                     int32_t* start, int32_t* order, int gpos_rows, float* scratch, hipStream_t s) {
+                     int32_t* start, int32_t* order, int32_t* blockcnt, int gpos_rows, float* scratch, float* partial,
+                     hipStream_t s) {
   if (dtype == 0)
     return embed_bwd_t<float>((const float*)dz, ids, tt, B, S, H, vocab, type_vocab, gword, gpos, gtype, rank, cnt,
-                              start, order, gpos_rows, scratch, s);
+                              start, order, blockcnt, gpos_rows, scratch, partial, s);
   return embed_bwd_t<bf16>((const bf16*)dz, ids, tt, B, S, H, vocab, type_vocab, gword, gpos, gtype, rank, cnt, start,
-                           order, gpos_rows, scratch, s);
+                           order, blockcnt, gpos_rows, scratch, partial, s);
 }
 
 // ---- fused multi-tensor Adam / LAMB ---------------------------------------------------------
