@@ -92,6 +92,9 @@ struct mslt_model {
   float *rstd_t, *logits, *row_loss, *lse_t, *loss;
   float *red_scratch; size_t red_floats;
   float *splitk; size_t splitk_floats;
+  // side stream: weight-gradient products and bias column sums overlap the data-gradient chain
+  hipStream_t side; hipEvent_t ev_fork, ev_join; bool side_forked;
+  float *splitk2, *red2;
   int32_t *e_rank, *e_cnt, *e_start, *e_order, *e_blockcnt;
   float* e_partial;                    // [Tp, H] run sums of the embedding backward
   OptTensor* o_tensors; int32_t* o_chunk_tensor; int32_t* o_tsteps; float* o_chunk_norms; float* o_ratio;
@@ -251,6 +254,8 @@ static size_t carve(mslt_model* m, char* base) {
   m->red_scratch = b.take<float>(red * 4);
   m->splitk_floats = m->mfma ? (size_t)1024 * 128 * 128 : 0;
   m->splitk = b.take<float>(m->splitk_floats * 4);
+  m->splitk2 = b.take<float>(m->splitk_floats * 4);
+  m->red2 = b.take<float>(red * 4);
   m->e_rank = b.take<int32_t>(Tp * 4); m->e_order = b.take<int32_t>(Tp * 4);
   m->e_cnt = b.take<int32_t>(rup(m->V, 4) * 4); m->e_start = b.take<int32_t>(rup(m->V, 4) * 4);
   m->e_partial = b.take<float>(Tp * H * 4);
@@ -336,6 +341,10 @@ extern "C" int mslt_init_model(const mslt_config* cfg, void* param_arena, void* 
     return fail(MSLT_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e));                   \
   }
   INIT_TRY(hipHostMalloc((void**)&m->h_counters, 64, hipHostMallocDefault));
+  INIT_TRY(hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking));
+  INIT_TRY(hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming));
+  INIT_TRY(hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming));
+  m->side_forked = false;
   m->h_loss = reinterpret_cast<float*>(m->h_counters + 8);
   INIT_TRY(fill_zero(m->param, m->arena_elems * 4, m->stream));
   INIT_TRY(fill_zero(m->grad, m->arena_elems * 4, m->stream));
@@ -364,6 +373,9 @@ extern "C" int mslt_init_model(const mslt_config* cfg, void* param_arena, void* 
 extern "C" int mslt_destroy(mslt_model* m) {
   if (!m) return MSLT_OK;
   hipStreamSynchronize(m->stream);
+  if (m->side) { hipStreamSynchronize(m->side); hipStreamDestroy(m->side); }
+  if (m->ev_fork) hipEventDestroy(m->ev_fork);
+  if (m->ev_join) hipEventDestroy(m->ev_join);
   if (m->h_counters) hipHostFree(m->h_counters);
   for (auto& sp : m->prof.spans) { hipEventDestroy(sp.a); hipEventDestroy(sp.b); }
   for (auto e : m->prof.pool) hipEventDestroy(e);
@@ -430,7 +442,31 @@ static int pick_splitk(int M, int N, int K) {
   while (s > 1 && K / 64 / s < 4) --s;
   return s;
 }
-static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false) {
+// Weight-gradient products and bias column sums only consume what the main stream has already
+// produced and write tensors nothing else touches, so they run on a side stream next to the
+// data-gradient chain (which is what the layer below waits for).  side_fork makes the side stream
+// see the main stream's work so far; side_join makes the main stream wait for the side stream and
+// is called before any buffer the side work reads is overwritten.  Off while event profiling.
+static int side_fork(mslt_model* m, hipStream_t* st, float** partials, float** red) {
+  *st = m->stream; *partials = m->splitk; *red = m->red_scratch;
+  if (m->prof.on) return MSLT_OK;
+  HIP_TRY(hipEventRecord(m->ev_fork, m->stream));
+  HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+  m->side_forked = true;
+  *st = m->side; *partials = m->splitk2; *red = m->red2;
+  return MSLT_OK;
+}
+static int side_join(mslt_model* m) {
+  if (!m->side_forked) return MSLT_OK;
+  HIP_TRY(hipEventRecord(m->ev_join, m->side));
+  HIP_TRY(hipStreamWaitEvent(m->stream, m->ev_join, 0));
+  m->side_forked = false;
+  return MSLT_OK;
+}
+
+static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false, hipStream_t st = nullptr,
+                    float* partials = nullptr) {
+  if (!st) { st = m->stream; partials = m->splitk; }
   const bool use_mfma = m->mfma && gemm_mfma_supported(d);
   const double out_esz = d.epi.out_f32 ? 4.0 : (double)m->esz;
   ProfScope ps(m, !use_mfma ? PC_GEMM_SIMT : (d.a_kcontig ? (d.b_kcontig ? PC_GEMM_NT : PC_GEMM_NN) : PC_GEMM_TN),
@@ -438,9 +474,9 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false)
   if (use_mfma) {
     int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
     while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
-    HIP_TRY(gemm_mfma(d, sk, m->splitk, m->stream));
+    HIP_TRY(gemm_mfma(d, sk, partials, st));
   } else {
-    HIP_TRY(gemm_simt(m->dtype, d, m->stream));
+    HIP_TRY(gemm_simt(m->dtype, d, st));
   }
   return MSLT_OK;
 }
@@ -474,7 +510,9 @@ static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int
   d.A = dY; d.lda = ldy; d.a_kcontig = 0; d.M = N;
   d.B = X; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = rows;
   d.epi.out = dW; d.epi.ldo = K; d.epi.out_f32 = 1;
-  return run_gemm(m, d, true);
+  hipStream_t st; float *partials, *red;
+  RC(side_fork(m, &st, &partials, &red));
+  return run_gemm(m, d, true, st, partials);
 }
 
 static int ln_forward(mslt_model* m, const void* a, const void* r, const float* g, const float* b, void* out, LnStash st,
@@ -514,7 +552,9 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
 
 static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, float* out) {
   ProfScope ps(m, PC_COLSUM, (double)rows * N, (double)rows * N * m->esz);
-  HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, m->red_scratch, m->stream));
+  hipStream_t st; float *partials, *red;
+  RC(side_fork(m, &st, &partials, &red));
+  HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, red, st));
   return MSLT_OK;
 }
 // dzsum (may be null): column sums of dz = bias gradient of the linear layer feeding this LayerNorm
@@ -571,7 +611,7 @@ static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int 
   RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_layer(l, L_WQ))));
   RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_layer(l, L_BQ))));
   if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_layer(l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
-  return MSLT_OK;
+  return side_join(m);   // the next layer reuses the gradient buffers the side stream reads
 }
 // dXout: gradient w.r.t. the layer output on all token rows.
 static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, const void* dXout,
@@ -623,6 +663,7 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   if (bt->batch < 1 || bt->batch > m->cfg.max_batch || bt->seq < 1 || bt->seq > m->cfg.max_seq)
     return fail(MSLT_ERR_ARG, "stage_step: batch %dx%d outside 1..%dx1..%d", bt->batch, bt->seq, m->cfg.max_batch,
                 m->cfg.max_seq);
+  RC(side_join(m));      // only pending after a step that failed half-way
   hipStream_t s = m->stream;
   const int H = m->H, B = bt->batch, S = bt->seq, T = B * S;
   m->have_grads = false;
@@ -690,6 +731,7 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   RC(linear_bwd_weight(m, m->d_ut, Mr, H, H, m->xm, H, Gf(m, th + H_WT)));
   RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT)));
   RC(linear_bwd_input(m, m->d_ut, Mr, H, H, Wg(m, th + H_WT), H, m->d_xm, EPI_NONE, nullptr));
+  RC(side_join(m));      // the top layer's backward reuses the head buffers
   // S8/S9: trainable layers backward, top down.  The top layer works on the compacted predicted rows
   // and scatters inside; the layers below get dense gradients.
   void* dx = m->dxa;

@@ -81,3 +81,12 @@ def test_large_stage_with_lamb_update():
         cos = float((dw * dref).sum() / (np.linalg.norm(dw) * np.linalg.norm(dref) + 1e-300))
         assert cos > 0.8, (name, cos)
     m.close()
+
+
+def test_base_final_stage_full_size():
+    # final stage of the BERT-Base schedule at full size: 12 layers, bottom 9 frozen, top 3 trainable,
+    # batch 64 x seq 128; every gradient element against the oracle
+    sh = synth.bert_base_shape(12)
+    r = run_case(sh, 64, 128, 9, 3, False, 1, full_backprop=False)
+    print("base 9/3 64x128", assert_parity(r, 1, "base-final"))
+    r["model"].close()
