@@ -172,7 +172,17 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
   return u;
 }
-__device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float (&v)[8], const float (&bias)[8]) {
+// true when the epilogue reads the per-element operand (pre-activation or addend)
+__device__ __forceinline__ bool epilogue_reads_aux(const Epilogue& e) {
+  return e.act == EPI_MUL_GELU_GRAD || e.act == EPI_ADD;
+}
+__device__ __forceinline__ uint4 load_aux8(const Epilogue& e, int m, int n) {
+  return *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n);
+}
+// raw: the 8 per-element operand values of this position (only read when the epilogue uses them);
+// callers load it well ahead so its latency is not paid here
+__device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float (&v)[8], const float (&bias)[8],
+                                          const uint4& raw) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[i] += bias[i];
   size_t o = (size_t)m * e.ldo + n;
@@ -182,12 +192,12 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
     for (int i = 0; i < 8; ++i) v[i] = gelu_fast(v[i]);
   } else if (e.act == EPI_MUL_GELU_GRAD) {
     float u[8];
-    unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n), u);
+    unpack8(raw, u);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_fast(u[i]);
   } else if (e.act == EPI_ADD) {
     float u[8];
-    unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n), u);
+    unpack8(raw, u);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] += u[i];
   }
@@ -321,6 +331,35 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
   for (int j = 0; j < PF - 1; ++j)
     if (kt + j < nk) body(ra[j], rb[j], ra[(j + 1) % PF], rb[(j + 1) % PF], kt + j);
 
+  // Epilogue operands first: the bias and the per-element operand are requested before the
+  // accumulators are staged, so their memory latency runs under the staging and its barrier.
+  const int cc = 8 * (lane & 7);
+  const int n = n0 + 64 * wn + cc;
+  const int mrow = m0 + 64 * wm + (lane >> 3);      // first of this lane's 8 rows (stride 8)
+  Epilogue e = p.epi;
+  float bias[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) bias[i] = 0.f;
+  uint4 raw[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) raw[i] = make_uint4(0, 0, 0, 0);
+  if (p.splitk > 1) {
+    e = Epilogue();
+    e.out = p.partials + (size_t)split * p.M * p.N;
+    e.ldo = p.N;
+    e.out_f32 = 1;
+  } else {
+    if (epilogue_reads_aux(e)) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) raw[i] = load_aux8(e, mrow + 8 * i, n);
+    }
+    if (e.bias) {
+      float4 b0 = *reinterpret_cast<const float4*>(e.bias + n), b1 = *reinterpret_cast<const float4*>(e.bias + n + 4);
+      bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
+      bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
+    }
+  }
+
   // stage this wavefront's 64x64 quarter in LDS (all operand reads are behind the last barrier)
   float* stage = reinterpret_cast<float*>(smem) + wave * 64 * EPI_LD;
 #pragma unroll
@@ -334,29 +373,13 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
       }
   __syncthreads();
 
-  const int cc = 8 * (lane & 7);
-  const int n = n0 + 64 * wn + cc;
-  Epilogue e = p.epi;
-  float bias[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) bias[i] = 0.f;
-  if (p.splitk > 1) {
-    e = Epilogue();
-    e.out = p.partials + (size_t)split * p.M * p.N;
-    e.ldo = p.N;
-    e.out_f32 = 1;
-  } else if (e.bias) {
-    float4 b0 = *reinterpret_cast<const float4*>(e.bias + n), b1 = *reinterpret_cast<const float4*>(e.bias + n + 4);
-    bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
-    bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
-  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     int row = 8 * i + (lane >> 3);
     float4 x0 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc);
     float4 x1 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc + 4);
     float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-    epilogue8(e, m0 + 64 * wm + row, n, v, bias);
+    epilogue8(e, mrow + 8 * i, n, v, bias, raw[i]);
   }
 }
 
@@ -366,6 +389,8 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float* __restrict__
   size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (idx >= (size_t)M * N) return;
   int m = (int)(idx / N), n = (int)(idx % N);
+  uint4 raw = make_uint4(0, 0, 0, 0);
+  if (epilogue_reads_aux(e)) raw = load_aux8(e, m, n);
   float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int s = 0; s < splitk; ++s) {
     const float* q = partials + (size_t)s * M * N + idx;
@@ -378,7 +403,7 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float* __restrict__
 #pragma unroll
     for (int i = 0; i < 8; ++i) bias[i] = e.bias[n + i];
   }
-  epilogue8(e, m, n, v, bias);
+  epilogue8(e, m, n, v, bias, raw);
 }
 
 bool gemm_mfma_supported(const GemmDesc& d) {

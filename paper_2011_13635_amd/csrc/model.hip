@@ -434,13 +434,27 @@ extern "C" int mslt_get_params(const mslt_model* m, float* host, size_t n_floats
 
 // ---- GEMM dispatch --------------------------------------------------------------------------
 static int pick_splitk(int M, int N, int K) {
-  // enough workgroups to fill 256 CUs x 2 resident workgroups, at least 4 k tiles of 64 per split
-  int tiles = (M / 128) * (N / 128);
-  if (tiles >= 256 || K < 1024) return 1;
-  int s = (512 + tiles - 1) / tiles;
-  if (s > 16) s = 16;
-  while (s > 1 && K / 64 / s < 4) --s;
-  return s;
+  // Few output tiles and a long contraction: split k.  The factor minimises a small cost model
+  // fitted to measured launches (microseconds): one 64-wide k tile of a 128x128 workgroup takes
+  // about 0.65 us while a CU holds one workgroup (up to 256 workgroups) and 0.95 us once it holds
+  // two (up to 512); workgroups beyond 512 run as a second round; the fp32 partials cost their
+  // write plus read at about 5 TB/s (they stay in the last-level cache) and the summing kernel a
+  // fixed 5 us.
+  const int tiles = (M / 128) * (N / 128), nkt = K / 64;
+  if (nkt < 16) return 1;
+  double best = 0.0;
+  int pick = 1;
+  for (int s = 1; s <= 16 && nkt / s >= 4; ++s) {
+    const int wgs = tiles * s;
+    const double it = (double)((nkt + s - 1) / s);
+    const int full = wgs / 512, rem = wgs % 512;
+    double t;
+    if (full == 0) t = it * (rem <= 256 ? 0.65 : 0.95);
+    else t = it * 0.95 * full + (rem ? it * (rem <= 256 ? 0.65 : 0.95) : 0.0);
+    if (s > 1) t += 5.0 + (double)s * M * N * 8.0 / 5.0e6;
+    if (s == 1 || t < best) { best = t; pick = s; }
+  }
+  return pick;
 }
 // Weight-gradient products and bias column sums only consume what the main stream has already
 // produced and write tensors nothing else touches, so they run on a side stream next to the
