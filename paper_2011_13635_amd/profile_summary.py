@@ -22,6 +22,11 @@ def summarize(db_path: str, command: str = "") -> str:
     lines.append(f"{'calls':>7} {'total_us':>11} {'avg_us':>9} {'min_us':>9} {'max_us':>9} {'%':>6}  kernel")
     for name, n, tot, avg, mn, mx in rows:
         lines.append(f"{n:7d} {tot / 1e3:11.1f} {avg / 1e3:9.2f} {mn / 1e3:9.2f} {mx / 1e3:9.2f} {100 * tot / total:6.2f}  {name}")
+    # the MFMA GEMM is one templated kernel: its variants together, for comparison with bench.py's avg_launch_us
+    g = [r for r in rows if "k_gemm_mfma" in r[0]]
+    if g:
+        n, tot = sum(r[1] for r in g), sum(r[2] for r in g)
+        lines.append(f"k_gemm_mfma, all variants: {n} dispatches, avg {tot / n / 1e3:.2f} us, {100 * tot / total:.2f} % of kernel time")
     return "\n".join(lines) + "\n"
 
 
