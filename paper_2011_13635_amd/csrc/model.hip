@@ -94,6 +94,10 @@ struct mslt_model {
   float *splitk; size_t splitk_floats;
   // side stream: weight-gradient products and bias column sums overlap the data-gradient chain
   hipStream_t side; hipEvent_t ev_fork, ev_join; bool side_forked;
+  // the gradient buffers the side stream reads exist twice and alternate by layer, so a layer's
+  // side work only has to finish before the layer two below starts
+  struct GradSet { void *d_d, *d_u, *d_z1, *d_qkv; } gset[2];
+  hipEvent_t ev_set[2]; bool set_busy[2];
   float *splitk2, *red2;
   int32_t *e_rank, *e_cnt, *e_start, *e_order, *e_blockcnt;
   float* e_partial;                    // [Tp, H] run sums of the embedding backward
@@ -227,8 +231,13 @@ static size_t carve(mslt_model* m, char* base) {
     s.xhat2 = b.take<void>(TH);
     s.lse = b.take<float>(lse_bytes); s.rstd1 = b.take<float>(Tp * 4); s.rstd2 = b.take<float>(Tp * 4);
   }
-  m->dxa = b.take<void>(TH); m->dxb = b.take<void>(TH); m->d_d = b.take<void>(TH); m->d_u = b.take<void>(TF);
-  m->d_x1 = b.take<void>(TH); m->d_z1 = b.take<void>(TH); m->d_c = b.take<void>(TH); m->d_qkv = b.take<void>(3 * TH);
+  m->dxa = b.take<void>(TH); m->dxb = b.take<void>(TH);
+  for (int i = 0; i < 2; ++i) {
+    m->gset[i].d_d = b.take<void>(TH); m->gset[i].d_u = b.take<void>(TF);
+    m->gset[i].d_z1 = b.take<void>(TH); m->gset[i].d_qkv = b.take<void>(3 * TH);
+  }
+  m->d_d = m->gset[0].d_d; m->d_u = m->gset[0].d_u; m->d_z1 = m->gset[0].d_z1; m->d_qkv = m->gset[0].d_qkv;
+  m->d_x1 = b.take<void>(TH); m->d_c = b.take<void>(TH);
   m->d_z0 = b.take<void>(TH);
   m->delta = b.take<float>(lse_bytes);
   m->pos = b.take<int32_t>((size_t)m->cap * 4); m->lab = b.take<int32_t>((size_t)m->cap * 4);
@@ -345,6 +354,10 @@ extern "C" int mslt_init_model(const mslt_config* cfg, void* param_arena, void* 
   INIT_TRY(hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming));
   INIT_TRY(hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming));
   m->side_forked = false;
+  for (int i = 0; i < 2; ++i) {
+    INIT_TRY(hipEventCreateWithFlags(&m->ev_set[i], hipEventDisableTiming));
+    m->set_busy[i] = false;
+  }
   m->h_loss = reinterpret_cast<float*>(m->h_counters + 8);
   INIT_TRY(fill_zero(m->param, m->arena_elems * 4, m->stream));
   INIT_TRY(fill_zero(m->grad, m->arena_elems * 4, m->stream));
@@ -376,6 +389,8 @@ extern "C" int mslt_destroy(mslt_model* m) {
   if (m->side) { hipStreamSynchronize(m->side); hipStreamDestroy(m->side); }
   if (m->ev_fork) hipEventDestroy(m->ev_fork);
   if (m->ev_join) hipEventDestroy(m->ev_join);
+  for (int i = 0; i < 2; ++i)
+    if (m->ev_set[i]) hipEventDestroy(m->ev_set[i]);
   if (m->h_counters) hipHostFree(m->h_counters);
   for (auto& sp : m->prof.spans) { hipEventDestroy(sp.a); hipEventDestroy(sp.b); }
   for (auto e : m->prof.pool) hipEventDestroy(e);
@@ -475,6 +490,24 @@ static int side_join(mslt_model* m) {
   HIP_TRY(hipEventRecord(m->ev_join, m->side));
   HIP_TRY(hipStreamWaitEvent(m->stream, m->ev_join, 0));
   m->side_forked = false;
+  m->set_busy[0] = m->set_busy[1] = false;
+  return MSLT_OK;
+}
+// Layer l's backward uses gradient-buffer set l & 1: wait for the side work of layer l + 2, the
+// last reader of that set, before anything is written there.
+static int layer_backward_begin(mslt_model* m, int l) {
+  const int p = l & 1;
+  if (m->set_busy[p]) {
+    HIP_TRY(hipStreamWaitEvent(m->stream, m->ev_set[p], 0));
+    m->set_busy[p] = false;
+  }
+  m->d_d = m->gset[p].d_d; m->d_u = m->gset[p].d_u; m->d_z1 = m->gset[p].d_z1; m->d_qkv = m->gset[p].d_qkv;
+  return MSLT_OK;
+}
+static int layer_backward_end(mslt_model* m, int l) {
+  if (!m->side_forked) return MSLT_OK;
+  HIP_TRY(hipEventRecord(m->ev_set[l & 1], m->side));
+  m->set_busy[l & 1] = true;
   return MSLT_OK;
 }
 
@@ -625,12 +658,13 @@ static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int 
   RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_layer(l, L_WQ))));
   RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_layer(l, L_BQ))));
   if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_layer(l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
-  return side_join(m);   // the next layer reuses the gradient buffers the side stream reads
+  return layer_backward_end(m, l);
 }
 // dXout: gradient w.r.t. the layer output on all token rows.
 static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, const void* dXout,
                           void* dXin) {
   const LayerStash& st = m->stash[l];
+  RC(layer_backward_begin(m, l));
   UpperRows r{st.xhat2, st.g, st.u, st.x1, st.xhat1, st.ctx, st.rstd2, st.rstd1, m->d_d, m->d_u, m->d_x1, m->d_z1, m->d_c, Tr};
   RC(layer_backward_upper(m, l, dXout, r));
   return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin);
@@ -643,6 +677,7 @@ static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T,
   const int H = m->H, F = m->F;
   const LayerStash& st = m->stash[l];
   hipStream_t s = m->stream;
+  RC(layer_backward_begin(m, l));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * Mr * (4.0 * H + 2.0 * F) * m->esz);
     HIP_TRY(gather_rows(m->dtype, st.xhat2, m->pos, M, Mr, H, m->xm, s));
@@ -759,6 +794,7 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
       RC(layer_backward(m, l, bt, T, Tr, xin, dx, dxin));
     if (dxin) dx = dxin;
   }
+  RC(side_join(m));      // all weight gradients are complete when the step returns
   // S10: embedding backward (first stage / retraining)
   if (train_emb) {
     RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), nullptr, T));
