@@ -19,6 +19,11 @@ __device__ inline float4 load4(const bf16* p) {
   o.w = __uint_as_float(r.y & 0xffff0000u);
   return o;
 }
+// Loads of a row's tail are made unconditional: lanes past the row end re-read column 0 (always in
+// bounds) and drop the value, so that all loads of a thread issue back to back instead of one
+// guarded load-and-wait at a time.
+__device__ inline int ldcol(int c, int H) { return c < H ? c : 0; }
+__device__ inline float4 keep4(bool keep, float4 v) { return keep ? v : make_float4(0.f, 0.f, 0.f, 0.f); }
 __device__ inline void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ inline void store4(bf16* p, float4 v) {
   uint2 r;
@@ -86,54 +91,57 @@ __global__ void __launch_bounds__(1024) k_batch_scan(const int32_t* __restrict__
                                                      const int32_t* __restrict__ am, const int32_t* __restrict__ labels,
                                                      int T, int vocab, int type_vocab, int cap, int32_t* pos,
                                                      int32_t* lab, int32_t* inv, int32_t* counters) {
-  __shared__ int sc[1024];
+  // One workgroup walks the tokens in chunks of 1024 (coalesced); inside a chunk the rank of a
+  // predicted position is a wavefront ballot prefix plus the totals of the wavefronts before it.
+  __shared__ int wtot[16];
   __shared__ int bad_all;
-  int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   if (tid == 0) bad_all = 0;
-  int per = (T + 1023) / 1024;
-  int b = tid * per, e = min(T, b + per);
-  int c = 0, bad = 0;
-  for (int t = b; t < e; ++t) {
-    int id = ids[t];
-    if (id < 0 || id >= vocab) bad |= 1;
-    int ty = tt[t];
-    if (ty < 0 || ty >= type_vocab) bad |= 2;
-    int l = labels[t];
-    if (l != -100) {
-      if (l < 0 || l >= vocab) bad |= 4;
-      ++c;
-    }
-    int a = am[t];
-    if (a != 0 && a != 1) bad |= 8;
-  }
-  sc[tid] = c;
   __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    int v = tid >= o ? sc[tid - o] : 0;
+  int base = 0, bad = 0;
+  for (int c0 = 0; c0 < T; c0 += 1024) {
+    const int t = c0 + tid;
+    const bool in = t < T;
+    int l = -100;
+    if (in) {
+      int id = ids[t];
+      if (id < 0 || id >= vocab) bad |= 1;
+      int ty = tt[t];
+      if (ty < 0 || ty >= type_vocab) bad |= 2;
+      int a = am[t];
+      if (a != 0 && a != 1) bad |= 8;
+      l = labels[t];
+    }
+    const bool v = in && l != -100;
+    if (v && (l < 0 || l >= vocab)) bad |= 4;
+    const unsigned long long mask = __ballot(v);
+    const int within = __popcll(mask & ((1ull << lane) - 1ull));
+    if (lane == 0) wtot[w] = __popcll(mask);
     __syncthreads();
-    sc[tid] += v;
-    __syncthreads();
-  }
-  if (bad) atomicOr(&bad_all, bad);
-  int off = sc[tid] - c;
-  for (int t = b; t < e; ++t) {
-    int l = labels[t];
-    if (l != -100) {
-      if (off < cap) {
+    int before = 0, tot = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      int x = wtot[j];
+      before += j < w ? x : 0;
+      tot += x;
+    }
+    if (in) {
+      const int off = base + before + within;
+      if (v && off < cap) {
         pos[off] = t;
         lab[off] = l;
         inv[t] = off;
       } else {
         inv[t] = -1;
       }
-      ++off;
-    } else {
-      inv[t] = -1;
     }
+    base += tot;
+    __syncthreads();
   }
+  if (bad) atomicOr(&bad_all, bad);
   __syncthreads();
-  if (tid == 1023) {
-    counters[0] = sc[1023];
+  if (tid == 0) {
+    counters[0] = base;
     counters[1] = bad_all;
   }
 }
@@ -169,14 +177,21 @@ __device__ inline void ln_row_finish(float4 (&z)[NV], int H, int lane, const flo
   float var = wave_sum(sq) / (float)H;
   float rstd = 1.0f / sqrtf(var + eps);
   if (rstd_out != nullptr && lane == 0) *rstd_out = rstd;
+  float4 gg[NV], bb[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int c = ldcol((i * 64 + lane) * 4, H);
+    gg[i] = load4(g + c);
+    bb[i] = load4(b + c);
+  }
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
     if (c < H) {
       float4 xh = make_float4(z[i].x * rstd, z[i].y * rstd, z[i].z * rstd, z[i].w * rstd);
       if (xhat != nullptr) store4(xhat + c, xh);
-      float4 gg = load4(g + c), bb = load4(b + c);
-      store4(out + c, make_float4(xh.x * gg.x + bb.x, xh.y * gg.y + bb.y, xh.z * gg.z + bb.z, xh.w * gg.w + bb.w));
+      store4(out + c, make_float4(xh.x * gg[i].x + bb[i].x, xh.y * gg[i].y + bb[i].y, xh.z * gg[i].z + bb[i].z,
+                                  xh.w * gg[i].w + bb[i].w));
     }
   }
 }
@@ -196,11 +211,9 @@ __global__ void __launch_bounds__(256) k_embed_ln(const int32_t* __restrict__ id
   float4 z[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    int c = (i * 64 + lane) * 4;
-    if (c < H) {
-      float4 a = load4(w + c), b2 = load4(p + c), c2 = load4(ty + c);
-      z[i] = make_float4(a.x + b2.x + c2.x, a.y + b2.y + c2.y, a.z + b2.z + c2.z, a.w + b2.w + c2.w);
-    }
+    int c = ldcol((i * 64 + lane) * 4, H);
+    float4 a = load4(w + c), b2 = load4(p + c), c2 = load4(ty + c);
+    z[i] = make_float4(a.x + b2.x + c2.x, a.y + b2.y + c2.y, a.z + b2.z + c2.z, a.w + b2.w + c2.w);
   }
   ln_row_finish<AT, NV>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
                         rstd ? rstd + row : nullptr);
@@ -238,15 +251,12 @@ __global__ void __launch_bounds__(256) k_add_ln(const AT* __restrict__ a, const 
   const AT* pr = r ? r + (size_t)row * H : nullptr;
   float4 z[NV];
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    int c = (i * 64 + lane) * 4;
-    if (c < H) {
-      float4 x = load4(pa + c);
-      if (pr) {
-        float4 y = load4(pr + c);
-        x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w;
-      }
-      z[i] = x;
+  for (int i = 0; i < NV; ++i) z[i] = load4(pa + ldcol((i * 64 + lane) * 4, H));
+  if (pr) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      float4 y = load4(pr + ldcol((i * 64 + lane) * 4, H));
+      z[i].x += y.x; z[i].y += y.y; z[i].z += y.z; z[i].w += y.w;
     }
   }
   ln_row_finish<AT, NV>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
@@ -325,7 +335,7 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
   for (int i = 0; i < NV; ++i) {
     int c = (i * 64 + lane) * 4;
     ag[i] = ab[i] = az[i] = make_float4(0, 0, 0, 0);
-    gg[i] = (c < H) ? load4(g + c) : make_float4(0, 0, 0, 0);
+    gg[i] = keep4(c < H, load4(g + ldcol(c, H)));
   }
   const int row0 = (blockIdx.x * 4 + wave) * R;
   const float invH = 1.0f / (float)H;
@@ -333,18 +343,26 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
   float rs[R];
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
-    int row = row0 + rr;
-    bool ok = row < rows;
-    rs[rr] = ok ? rstd[row] : 0.f;
+    const int row = row0 + rr;
+    const bool ok = row < rows;
+    const size_t ro = (size_t)(ok ? row : rows - 1) * H;     // rows past the end re-read the last row
+    rs[rr] = rstd[ok ? row : rows - 1];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      int c = (i * 64 + lane) * 4;
-      if (ok && c < H) {
-        d[rr][i] = load4(dy + (size_t)row * H + c);
-        x[rr][i] = load4(xhat + (size_t)row * H + c);
-      } else {
-        d[rr][i] = x[rr][i] = make_float4(0, 0, 0, 0);
-      }
+      const int c = (i * 64 + lane) * 4;
+      d[rr][i] = load4(dy + ro + ldcol(c, H));
+      x[rr][i] = load4(xhat + ro + ldcol(c, H));
+    }
+  }
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    const bool ok = row0 + rr < rows;
+    if (!ok) rs[rr] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const bool keep = ok && (i * 64 + lane) * 4 < H;
+      d[rr][i] = keep4(keep, d[rr][i]);
+      x[rr][i] = keep4(keep, x[rr][i]);
     }
   }
 #pragma unroll
@@ -457,15 +475,18 @@ __global__ void __launch_bounds__(256) k_colsum_vec(const AT* __restrict__ y, in
   int r0 = blockIdx.y * CSV_ROWS;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (c < N) {
+    // rows past the end re-read the last row and are dropped, so the loads issue back to back
+    float v[CSV_ROWS / 32][8];
 #pragma unroll
     for (int it = 0; it < CSV_ROWS / 32; ++it) {
       int r = r0 + it * 32 + rl;
-      if (r < rows) {
-        float v[8];
-        load8(y + (size_t)r * ld + c, v);
+      load8(y + (size_t)(r < rows ? r : rows - 1) * ld + c, v[it]);
+    }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] += v[i];
-      }
+    for (int it = 0; it < CSV_ROWS / 32; ++it) {
+      const bool ok = r0 + it * 32 + rl < rows;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += ok ? v[it][i] : 0.f;
     }
   }
 #pragma unroll
