@@ -32,8 +32,8 @@ PEAK_HBM_GBS = 8000.0
 def run_steps(model, cbatches, f, k, emb, opt, n):
     loss = None
     for i in range(n):
-        loss = model.mslt_stage_step(f, k, emb, cbatches[i % len(cbatches)])
-        model.mslt_apply_update(opt)
+        # one call = stage step + optimizer update (the same work as mslt_stage_step + mslt_apply_update)
+        loss = model.mslt_train_step(f, k, emb, cbatches[i % len(cbatches)], opt)
     return loss
 
 

@@ -142,6 +142,17 @@ int mslt_get_grads(const mslt_model* m, float* host_fp32_out, size_t n_floats);
  * without a new step is an error. */
 int mslt_apply_update(mslt_model* m, const mslt_opt* opt);
 
+/* One training step of a stage in one call: mslt_stage_step() followed by mslt_apply_update()
+ * (Sections 3.1 and 3.2), with the same requirements, results and error codes as the two calls
+ * made one after the other.  The update is queued right behind the step, before the host has
+ * seen the loss, so the device does not idle between the two; on the device it does nothing when
+ * the loss is not finite, and the call then returns MSLT_ERR_NONFINITE with the parameters, the
+ * moments and the step counts unchanged.  *loss_out (HOST) as in mslt_stage_step(); the call
+ * waits for the stream.  The gradients are consumed: mslt_get_grads() needs a new
+ * mslt_stage_step(). */
+int mslt_train_step(mslt_model* m, int frozen_layers, int trainable_layers, int train_embeddings,
+                    const mslt_batch* batch, const mslt_opt* opt, float* loss_out);
+
 /* Predicted positions (ascending flat index b*seq+s) and their labels as found by the last
  * step, to HOST arrays of at least max_predictions entries; *m_out = their number.  Blocks. */
 int mslt_debug_masked(const mslt_model* m, int32_t* pos_out, int32_t* label_out, int* m_out);

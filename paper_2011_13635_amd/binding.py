@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_PKG, "libmslt.so")
 
 EXPORTS = [
     "mslt_query_sizes", "mslt_init_model", "mslt_tensor_table", "mslt_load_params", "mslt_get_params",
-    "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_debug_masked",
+    "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_train_step",
+    "mslt_debug_masked",
     "mslt_debug_prefix_output", "mslt_grow", "mslt_sync", "mslt_destroy", "mslt_last_error",
     "mslt_profile_enable", "mslt_profile_read",
 ]
@@ -78,6 +79,7 @@ def load_library():
     lib.mslt_grad_count.argtypes = [vp, P(sz)]
     lib.mslt_get_grads.argtypes = [vp, vp, sz]
     lib.mslt_apply_update.argtypes = [vp, P(Opt)]
+    lib.mslt_train_step.argtypes = [vp, C.c_int, C.c_int, C.c_int, P(Batch), P(Opt), P(C.c_float)]
     lib.mslt_debug_masked.argtypes = [vp, vp, vp, P(C.c_int)]
     lib.mslt_debug_prefix_output.argtypes = [vp, vp, sz]
     lib.mslt_grow.argtypes = [vp, C.c_int, C.c_int]
@@ -189,6 +191,12 @@ class Model:
 
     def mslt_apply_update(self, opt: Opt):
         _check(self.lib.mslt_apply_update(self.handle, C.byref(opt)))
+
+    def mslt_train_step(self, frozen_layers, trainable_layers, train_embeddings, cbatch: Batch, opt: Opt, allow=()):
+        loss = C.c_float()
+        rc = _check(self.lib.mslt_train_step(self.handle, frozen_layers, trainable_layers, int(train_embeddings),
+                                             C.byref(cbatch), C.byref(opt), C.byref(loss)), allow)
+        return loss.value if rc == 0 else rc
 
     def mslt_debug_masked(self):
         cap = self.cfg.max_predictions or self.cfg.max_batch * self.cfg.max_seq

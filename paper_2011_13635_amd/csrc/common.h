@@ -161,7 +161,7 @@ struct LnStash {
 };
 hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S, const float* word, const float* pos,
                         const float* type, const float* g, const float* b, float eps, void* out, LnStash st, int T,
-                        int H, hipStream_t s);
+                        int H, int vocab, int type_vocab, hipStream_t s);
 // out = LN(a + r) (r may be null)
 hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, const float* b, float eps, void* out,
                       LnStash st, int rows, int H, hipStream_t s);
@@ -208,12 +208,16 @@ struct OptHyper {
   int kind;
   float lr, beta1, beta2, eps, wd;
   int bias_correction;
+  // device pointer to the loss of the step whose gradients are applied, or null: when set, the
+  // update kernels do nothing unless that value is finite (lets an update be queued behind a step
+  // before the host has seen its loss)
+  const float* gate = nullptr;
 };
 constexpr int OPT_CHUNK = 16384;  // elements per workgroup
 // Updates tensors [tensor0, tensor0+n_tensors), whose chunks are [chunk0, chunk0+n_chunks).
 // tsteps[i] is tensor i's step count (already incremented for this update).
 // chunk_norms: 2 floats per chunk; ratio: 1 float per tensor (LAMB only).
-hipError_t bump_steps(int32_t* tsteps, int tensor0, int n_tensors, hipStream_t s);
+hipError_t bump_steps(int32_t* tsteps, int tensor0, int n_tensors, const float* gate, hipStream_t s);
 hipError_t optimizer_step(const OptHyper& h, const OptTensor* tensors, const int32_t* tsteps, int tensor0,
                           int n_tensors, const int32_t* chunk_tensor, int chunk0, int n_chunks, float* w,
                           const float* g, float* m, float* v, bf16* shadow, float* chunk_norms, float* ratio,

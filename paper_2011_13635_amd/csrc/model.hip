@@ -98,6 +98,7 @@ struct mslt_model {
   // side work only has to finish before the layer two below starts
   struct GradSet { void *d_d, *d_u, *d_z1, *d_qkv; } gset[2];
   hipEvent_t ev_set[2]; bool set_busy[2];
+  hipEvent_t ev_scan;      // batch check done and its verdict copied to the host
   float *splitk2, *red2;
   int32_t *e_rank, *e_cnt, *e_start, *e_order, *e_blockcnt;
   float* e_partial;                    // [Tp, H] run sums of the embedding backward
@@ -354,6 +355,7 @@ extern "C" int mslt_init_model(const mslt_config* cfg, void* param_arena, void* 
   INIT_TRY(hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming));
   INIT_TRY(hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming));
   m->side_forked = false;
+  INIT_TRY(hipEventCreateWithFlags(&m->ev_scan, hipEventDisableTiming));
   for (int i = 0; i < 2; ++i) {
     INIT_TRY(hipEventCreateWithFlags(&m->ev_set[i], hipEventDisableTiming));
     m->set_busy[i] = false;
@@ -389,6 +391,7 @@ extern "C" int mslt_destroy(mslt_model* m) {
   if (m->side) { hipStreamSynchronize(m->side); hipStreamDestroy(m->side); }
   if (m->ev_fork) hipEventDestroy(m->ev_fork);
   if (m->ev_join) hipEventDestroy(m->ev_join);
+  if (m->ev_scan) hipEventDestroy(m->ev_scan);
   for (int i = 0; i < 2; ++i)
     if (m->ev_set[i]) hipEventDestroy(m->ev_set[i]);
   if (m->h_counters) hipHostFree(m->h_counters);
@@ -701,8 +704,9 @@ static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T,
 }
 
 // ---- the stage step -------------------------------------------------------------------------
-extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const mslt_batch* bt, float* loss_out) {
-  if (!m || !bt || !loss_out) return fail(MSLT_ERR_ARG, "null argument");
+// Queues one whole stage step (everything but the final wait) on the model's streams.
+static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const mslt_batch* bt) {
+  if (!m || !bt) return fail(MSLT_ERR_ARG, "null argument");
   if (k < 1 || f < 0 || f + k > m->L)
     return fail(MSLT_ERR_ARG, "stage_step: bad layer split frozen=%d trainable=%d (layers %d)", f, k, m->L);
   if (train_emb != 0 && train_emb != 1) return fail(MSLT_ERR_ARG, "stage_step: train_embeddings must be 0 or 1");
@@ -721,22 +725,20 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
   HIP_TRY(batch_scan(bt->input_ids, bt->token_type_ids, bt->attn_mask, bt->labels, T, m->V, m->cfg.type_vocab, m->cap,
                      m->pos, m->lab, m->inv, m->counters, s));
   HIP_TRY(hipMemcpyAsync(m->h_counters, m->counters, 8, hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  const int M = m->h_counters[0], bad = m->h_counters[1];
-  if (bad) return fail(MSLT_ERR_DATA, "stage_step: batch content out of range (bits %d: 1 id, 2 type, 4 label, 8 mask)", bad);
-  if (M < 1) return fail(MSLT_ERR_DATA, "stage_step: no predicted position in the batch");
-  if (M > m->cap) return fail(MSLT_ERR_DATA, "stage_step: %d predicted positions exceed max_predictions %d", M, m->cap);
+  HIP_TRY(hipEventRecord(m->ev_scan, s));
   const int Tr = m->mfma ? (int)rup(T, 128) : T;
-  const int Mr = m->mfma ? (int)rup(M, 128) : M;
   const int Vr = m->mfma ? m->Vp : m->V;
 
+  // The encoder forward does not depend on the verdict of the batch check (the embedding lookup
+  // clamps its indices), so it is queued before the host waits for that verdict: the device then
+  // has work while the host reads the count of predicted positions the head is sized by.
   // S1: embeddings + LayerNorm
   LnStash e0;
   if (train_emb) { e0.xhat = m->xhat0; e0.rstd = m->rstd0; }
   {
     ProfScope ps(m, PC_EMBED, 0.0, (double)T * H * (4.0 + m->esz * (train_emb ? 2.0 : 1.0)));
     HIP_TRY(embed_ln_fwd(m->dtype, bt->input_ids, bt->token_type_ids, S, Wf(m, T_WORD), Wf(m, T_POS), Wf(m, T_TYPE),
-                         Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, s));
+                         Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, m->V, m->cfg.type_vocab, s));
   }
   // S2: frozen prefix, forward only, two ping-pong buffers, nothing kept
   const void* x = m->x0;
@@ -751,6 +753,15 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
     RC(layer_forward(m, l, bt, Tr, x, m->stash[l].xout, &m->stash[l]));
     x = m->stash[l].xout;
   }
+  HIP_TRY(hipEventSynchronize(m->ev_scan));
+  const int M = m->h_counters[0], bad = m->h_counters[1];
+  if (bad || M < 1 || M > m->cap) {
+    HIP_TRY(hipStreamSynchronize(s));   // let the queued forward drain before reporting
+    if (bad) return fail(MSLT_ERR_DATA, "stage_step: batch content out of range (bits %d: 1 id, 2 type, 4 label, 8 mask)", bad);
+    if (M < 1) return fail(MSLT_ERR_DATA, "stage_step: no predicted position in the batch");
+    return fail(MSLT_ERR_DATA, "stage_step: %d predicted positions exceed max_predictions %d", M, m->cap);
+  }
+  const int Mr = m->mfma ? (int)rup(M, 128) : M;
   // S4-S6: head forward and loss
   const int th = t_head(m, 0);
   {
@@ -803,12 +814,22 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
                       Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order, m->e_blockcnt,
                       m->cfg.max_pos, m->red_scratch, m->e_partial, s));
   }
-  HIP_TRY(hipStreamSynchronize(s));
-  *loss_out = *m->h_loss;
-  m->have_grads = true;
   m->last_f = f; m->last_k = k; m->last_emb = train_emb; m->last_B = B; m->last_S = S; m->last_M = M;
+  return MSLT_OK;
+}
+// Waits for the queued step and hands out its loss.
+static int stage_step_finish(mslt_model* m, float* loss_out) {
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  *loss_out = *m->h_loss;
   if (!std::isfinite(*loss_out)) return fail(MSLT_ERR_NONFINITE, "stage_step: loss is not finite");
   return MSLT_OK;
+}
+
+extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const mslt_batch* bt, float* loss_out) {
+  if (!loss_out) return fail(MSLT_ERR_ARG, "null argument");
+  RC(stage_step_enqueue(m, f, k, train_emb, bt));
+  m->have_grads = true;     // the gradients are well defined even when the loss turns out non-finite
+  return stage_step_finish(m, loss_out);
 }
 
 // trainable tensor ranges of the last step, as [first, last) index pairs in table order
@@ -857,13 +878,15 @@ extern "C" int mslt_get_grads(const mslt_model* m, float* host, size_t n_floats)
   return MSLT_OK;
 }
 
-extern "C" int mslt_apply_update(mslt_model* m, const mslt_opt* opt) {
-  if (!m || !opt) return fail(MSLT_ERR_ARG, "null argument");
-  if (!m->have_grads) return fail(MSLT_ERR_STATE, "apply_update: no gradients from a preceding stage_step");
-  if (opt->kind != 0 && opt->kind != 1) return fail(MSLT_ERR_ARG, "apply_update: kind must be 0 (Adam) or 1 (LAMB)");
+static int check_opt(const mslt_opt* opt, const char* who) {
+  if (opt->kind != 0 && opt->kind != 1) return fail(MSLT_ERR_ARG, "%s: kind must be 0 (Adam) or 1 (LAMB)", who);
   if (!(opt->beta1 >= 0.f && opt->beta1 < 1.f && opt->beta2 >= 0.f && opt->beta2 < 1.f && opt->eps >= 0.f))
-    return fail(MSLT_ERR_ARG, "apply_update: bad beta or eps");
-  OptHyper h{opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay, opt->bias_correction};
+    return fail(MSLT_ERR_ARG, "%s: bad beta or eps", who);
+  return MSLT_OK;
+}
+// Queues the update of the tensors the last step trained; gate: see OptHyper::gate.
+static int update_enqueue(mslt_model* m, const mslt_opt* opt, const float* gate) {
+  OptHyper h{opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay, opt->bias_correction, gate};
   int r[3][2];
   int n = trainable_ranges(m, r);
   for (int i = 0; i < n; ++i) {
@@ -872,12 +895,31 @@ extern "C" int mslt_apply_update(mslt_model* m, const mslt_opt* opt) {
     size_t n_elems = 0;
     for (int t = t0; t < r[i][1]; ++t) n_elems += m->table[t].count;
     ProfScope ps(m, PC_OPT, 0.0, (double)n_elems * ((opt->kind ? 40.0 : 28.0) + (m->dtype ? 2.0 : 0.0)));
-    HIP_TRY(bump_steps(m->o_tsteps, t0, nt, m->stream));
+    HIP_TRY(bump_steps(m->o_tsteps, t0, nt, gate, m->stream));
     HIP_TRY(optimizer_step(h, m->o_tensors, m->o_tsteps, t0, nt, m->o_chunk_tensor, c0, nc, m->param, m->grad, m->mom1,
                            m->mom2, m->shadow, m->o_chunk_norms, m->o_ratio, m->stream));
   }
+  return MSLT_OK;
+}
+
+extern "C" int mslt_apply_update(mslt_model* m, const mslt_opt* opt) {
+  if (!m || !opt) return fail(MSLT_ERR_ARG, "null argument");
+  if (!m->have_grads) return fail(MSLT_ERR_STATE, "apply_update: no gradients from a preceding stage_step");
+  RC(check_opt(opt, "apply_update"));
+  RC(update_enqueue(m, opt, nullptr));
   m->have_grads = false;
   return MSLT_OK;
+}
+
+extern "C" int mslt_train_step(mslt_model* m, int f, int k, int train_emb, const mslt_batch* bt, const mslt_opt* opt,
+                               float* loss_out) {
+  if (!m || !opt || !loss_out) return fail(MSLT_ERR_ARG, "null argument");
+  RC(check_opt(opt, "train_step"));
+  RC(stage_step_enqueue(m, f, k, train_emb, bt));
+  // the update goes in right behind the step; on the device it does nothing if the loss is not finite
+  RC(update_enqueue(m, opt, m->loss));
+  m->have_grads = false;
+  return stage_step_finish(m, loss_out);
 }
 
 extern "C" int mslt_debug_masked(const mslt_model* m, int32_t* pos_out, int32_t* label_out, int* m_out) {

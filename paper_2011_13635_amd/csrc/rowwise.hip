@@ -201,13 +201,16 @@ __global__ void __launch_bounds__(256) k_embed_ln(const int32_t* __restrict__ id
                                                   const float* __restrict__ word, const float* __restrict__ pos,
                                                   const float* __restrict__ type, const float* __restrict__ g,
                                                   const float* __restrict__ b, float eps, AT* __restrict__ out,
-                                                  AT* __restrict__ xhat, float* __restrict__ rstd, int T, int H) {
+                                                  AT* __restrict__ xhat, float* __restrict__ rstd, int T, int H,
+                                                  int vocab, int type_vocab) {
   int lane = threadIdx.x & 63;
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= T) return;
-  const float* w = word + (size_t)ids[row] * H;
+  // ids are clamped for memory safety only: a batch with ids out of range is rejected by the
+  // batch check, whose verdict the host reads while this kernel may already be running
+  const float* w = word + (size_t)min(max(ids[row], 0), vocab - 1) * H;
   const float* p = pos + (size_t)(row % S) * H;
-  const float* ty = type + (size_t)tt[row] * H;
+  const float* ty = type + (size_t)min(max(tt[row], 0), type_vocab - 1) * H;
   float4 z[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -227,14 +230,14 @@ static inline int ln_nv(int H) { return H <= 512 ? 2 : H <= 1024 ? 4 : 8; }
   }
 hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S, const float* word, const float* pos,
                         const float* type, const float* g, const float* b, float eps, void* out, LnStash st, int T,
-                        int H, hipStream_t s) {
+                        int H, int vocab, int type_vocab, hipStream_t s) {
   dim3 grid((T + 3) / 4), block(256);
   if (dtype == 0) {
     LN_DISPATCH(H, (k_embed_ln<float, NV><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (float*)out,
-                                                                 (float*)st.xhat, st.rstd, T, H)));
+                                                                 (float*)st.xhat, st.rstd, T, H, vocab, type_vocab)));
   } else {
     LN_DISPATCH(H, (k_embed_ln<bf16, NV><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (bf16*)out,
-                                                                (bf16*)st.xhat, st.rstd, T, H)));
+                                                                (bf16*)st.xhat, st.rstd, T, H, vocab, type_vocab)));
   }
   return hipGetLastError();
 }
@@ -951,13 +954,15 @@ hipError_t embed_bwd(int dtype, const void* dz, const int32_t* ids, const int32_
 // Pass 1 updates the moments; Adam also applies the step.  LAMB leaves per-chunk sums of w^2 and
 // u^2, a second kernel adds them per tensor in chunk order, and pass 2 recomputes u from the new
 // moments and applies the step with the tensor's trust ratio.
-__global__ void k_bump_steps(int32_t* tsteps, int tensor0, int n) {
+__device__ inline bool gate_closed(const float* gate) { return gate != nullptr && !isfinite(*gate); }
+__global__ void k_bump_steps(int32_t* tsteps, int tensor0, int n, const float* gate) {
+  if (gate_closed(gate)) return;
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) tsteps[tensor0 + i] += 1;
 }
-hipError_t bump_steps(int32_t* tsteps, int tensor0, int n_tensors, hipStream_t s) {
+hipError_t bump_steps(int32_t* tsteps, int tensor0, int n_tensors, const float* gate, hipStream_t s) {
   if (n_tensors <= 0) return hipSuccess;
-  k_bump_steps<<<dim3((n_tensors + 63) / 64), dim3(64), 0, s>>>(tsteps, tensor0, n_tensors);
+  k_bump_steps<<<dim3((n_tensors + 63) / 64), dim3(64), 0, s>>>(tsteps, tensor0, n_tensors, gate);
   return hipGetLastError();
 }
 __device__ inline void opt_corrections(const OptHyper& h, int t, float& c1, float& c2) {
@@ -976,6 +981,7 @@ __global__ void __launch_bounds__(256) k_opt_pass1(OptHyper h, const OptTensor* 
                                                    float* __restrict__ m, float* __restrict__ v,
                                                    bf16* __restrict__ shadow, float* __restrict__ chunk_norms) {
   __shared__ float sh[4];
+  if (gate_closed(h.gate)) return;
   int chunk = chunk0 + blockIdx.x;
   int ti = chunk_tensor[chunk];
   OptTensor tn = tensors[ti];
@@ -1030,6 +1036,7 @@ __global__ void __launch_bounds__(256) k_lamb_pass2(OptHyper h, const OptTensor*
                                                     float* __restrict__ w, const float* __restrict__ m,
                                                     const float* __restrict__ v, bf16* __restrict__ shadow,
                                                     const float* __restrict__ ratio) {
+  if (gate_closed(h.gate)) return;
   int chunk = chunk0 + blockIdx.x;
   int ti = chunk_tensor[chunk];
   OptTensor tn = tensors[ti];

@@ -198,3 +198,54 @@ def test_argument_and_data_errors_leave_state_untouched():
     assert np.array_equal(before, m.mslt_get_params())
     assert m.mslt_stage_step(2, 1, 0, cb) > 0  # and the model still works
     m.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("precision,kind", [(0, "adam"), (1, "lamb")])
+def test_train_step_equals_stage_step_then_update(precision, kind):
+    """The one-call training step leaves bit-identical parameters and losses to the two calls it
+    stands for (Sections 3.1 and 3.2), over a first stage (embeddings trained), a later stage and
+    a batch change; data errors and a non-finite loss leave the parameters untouched."""
+    sh = synth.tiny_shape()
+    W = synth.make_weights(sh, 3, std=0.05)
+    opt = binding.adam(lr=1e-3) if kind == "adam" else binding.lamb(lr=1e-3)
+    batches = [synth.make_batch(sh, 4, 64, seed=s, ragged=(s == 2)) for s in (1, 2)]
+    a = make_model(sh, 4, 64, precision)
+    b = make_model(sh, 4, 64, precision)
+    for m in (a, b):
+        m.mslt_load_params(synth.pack_weights(sh, W))
+    ca = [a.device_batch(x) for x in batches]
+    cb = [b.device_batch(x) for x in batches]
+    schedule = [(0, 2, 1, 0), (0, 2, 1, 1), (2, 1, 0, 0), (2, 1, 0, 1), (1, 2, 0, 0)]
+    for f, k, emb, i in schedule:
+        la = a.mslt_stage_step(f, k, emb, ca[i])
+        a.mslt_apply_update(opt)
+        lb = b.mslt_train_step(f, k, emb, cb[i], opt)
+        assert la == lb
+    pa, pb = a.mslt_get_params(), b.mslt_get_params()
+    assert np.array_equal(pa, pb)
+    assert not np.array_equal(pa, synth.pack_weights(sh, W))
+    with pytest.raises(binding.MsltError):     # the one-call step consumed its gradients
+        b.mslt_get_grads()
+    # data error: nothing changes
+    bad = {k: v.copy() for k, v in batches[0].items()}
+    bad["input_ids"][0, 5] = -3
+    E = binding
+    assert b.mslt_train_step(2, 1, 0, b.device_batch(bad), opt, allow=(E.MSLT_ERR_DATA,)) == E.MSLT_ERR_DATA
+    assert np.array_equal(pb, b.mslt_get_params())
+    # non-finite loss: the queued update must not touch parameters, moments or step counts
+    Wbad = {k: v.copy() for k, v in W.items()}
+    Wbad["head.b_out"][:] = np.inf
+    b.mslt_load_params(synth.pack_weights(sh, Wbad))
+    before = b.mslt_get_params()
+    assert b.mslt_train_step(2, 1, 0, cb[0], opt, allow=(E.MSLT_ERR_NONFINITE,)) == E.MSLT_ERR_NONFINITE
+    assert np.array_equal(before, b.mslt_get_params(), equal_nan=True)
+    # and the moments and step counts did not move either: from the same parameters both models continue alike
+    b.mslt_load_params(pa)
+    a.mslt_load_params(pa)
+    la = a.mslt_stage_step(2, 1, 0, ca[1])
+    a.mslt_apply_update(opt)
+    lb = b.mslt_train_step(2, 1, 0, cb[1], opt)
+    assert la == lb and np.array_equal(a.mslt_get_params(), b.mslt_get_params())
+    a.close()
+    b.close()
