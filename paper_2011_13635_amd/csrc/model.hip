@@ -547,7 +547,7 @@ static int linear_fwd(mslt_model* m, const void* X, int rows, int K, const void*
 }
 // dX[rows,K] = dY[rows,N] W[N,K]  (+ addend | * gelu'(U))
 static int linear_bwd_input(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* W, int K, void* dX,
-                            int act, const void* aux, bool allow_splitk = false) {
+                            int act, const void* aux, bool allow_splitk = true) {
   GemmDesc d;
   d.A = dY; d.lda = ldy; d.a_kcontig = 1; d.M = rows;
   d.B = W; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = N;
