@@ -29,11 +29,14 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU, dense
 PEAK_HBM_GBS = 8000.0
 
 
-def run_steps(model, cbatches, f, k, emb, opt, n):
+def run_steps(model, cbatches, f, k, emb, opt, n, stamps=None):
     loss = None
     for i in range(n):
-        # one call = stage step + optimizer update (the same work as mslt_stage_step + mslt_apply_update)
+        # one call = stage step + optimizer update (the same work as mslt_stage_step + mslt_apply_update);
+        # it returns once the loss is on the host, i.e. after the step's kernels (the update may still run)
         loss = model.mslt_train_step(f, k, emb, cbatches[i % len(cbatches)], opt)
+        if stamps is not None:
+            stamps.append(time.perf_counter())
     return loss
 
 
@@ -42,10 +45,12 @@ def time_steps(torch, model, cbatches, f, k, emb, opt, steps, warmup):
     model.mslt_sync()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    loss = run_steps(model, cbatches, f, k, emb, opt, steps)
+    stamps = [t0]
+    loss = run_steps(model, cbatches, f, k, emb, opt, steps, stamps)
     model.mslt_sync()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    time_steps.per_step_ms = sorted((b - a) * 1e3 for a, b in zip(stamps, stamps[1:]))
     return dt / steps, loss
 
 
@@ -169,6 +174,8 @@ def main():
 
     sec, loss = time_steps(torch, model, cb, f, k, False, opt, args.steps, args.warmup)
     tokens = B * S
+    ps = time_steps.per_step_ms     # host time between consecutive step returns
+    step_quantiles = [round(ps[len(ps) // 2], 4), round(ps[len(ps) // 10], 4), round(ps[(len(ps) * 9) // 10], 4)]
     prof = profile_steps(model, cb, f, k, False, opt, min(args.steps, 20))
 
     gemm = [v for n, v in prof.items() if n.startswith("gemm_mfma")]
@@ -193,6 +200,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 4),
+        "ms_per_step_median_p10_p90": step_quantiles,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -249,3 +249,41 @@ def test_train_step_equals_stage_step_then_update(precision, kind):
     assert la == lb and np.array_equal(a.mslt_get_params(), b.mslt_get_params())
     a.close()
     b.close()
+
+
+@pytest.mark.gpu
+def test_whole_schedule_follows_the_oracle():
+    """Two stages and the joint retraining of a 4-layer model through the schedule harness (Section 3.2),
+    against the oracle walking the same schedule: losses of every step and the final parameters."""
+    from paper_2011_13635_amd import schedule as SCH
+    sh = synth.tiny_shape(4)
+    W = synth.make_weights(sh, 6)
+    m = make_model(sh, 4, 64, 0)
+    m.mslt_load_params(synth.pack_weights(sh, W))
+    stages = SCH.mslt_schedule(4, 2, steps_per_stage=3, retrain_steps=2, lr=0.004, retrain_lr=0.001)
+    batches = [synth.make_batch(sh, 4, 64, seed=30 + i, ragged=(i % 2 == 1)) for i in range(8)]
+    losses = SCH.run_schedule(m, stages, next_batch=lambda g: m.device_batch(batches[g]),
+                              make_opt=lambda lr: binding.lamb(lr=lr), warmup_steps=4)
+    ref = O.to_f64(W)
+    st = O.new_opt_state(ref)
+    g = 0
+    present = 0
+    for stage, got in zip(stages, losses):
+        if stage.grow_first:
+            ref = O.grow(ref, present, stage.grow_first)
+            for i in range(stage.grow_first):
+                for t in O.LAYER_TENSORS:
+                    n = f"layer{present + i}.{t}"
+                    st[n] = {"m": np.zeros_like(ref[n]), "v": np.zeros_like(ref[n]), "t": 0}
+        present = max(present, stage.frozen + stage.trainable)
+        for i in range(stage.steps):
+            lr = stage.lr * SCH.warmup_factor(g, 4)
+            rl, rg, _ = O.stage_step(sh, ref, batches[g], stage.frozen, stage.trainable, stage.train_embeddings)
+            ref, _ = O.optimizer_update(ref, rg, st, kind="lamb", lr=lr)
+            assert abs(got[i] - rl) / rl < 2e-4, (stage.name, i, got[i], rl)
+            g += 1
+    got = synth.unpack_weights(sh, m.mslt_get_params())
+    for name in got:
+        d = np.abs(got[name] - ref[name]).max()
+        assert d < 3e-3 * max(np.abs(ref[name]).max(), 1e-3), (name, d)
+    m.close()
