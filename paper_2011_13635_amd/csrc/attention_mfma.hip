@@ -350,6 +350,157 @@ __global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict
   store_acc_T(out + 2 * H + 32, ld, n, half, dv1, 1.0f);
 }
 
+// ---- backward for one-tile sequences (S = 128): both sides in one launch ----------------------
+// One 512-thread workgroup per (batch, head).  All eight wavefronts first stage Q, K, V and dC
+// (row tiles for the first products, transposed tiles for the second ones), the row log-sum-exp,
+// the key bias and delta = rowsum(dC * C) in LDS; then wavefronts 0..3 run the query side (dQ)
+// and wavefronts 4..7 the key side (dK, dV) next to each other, with the same arithmetic as the
+// two kernels above.  Every operand is read from memory once and delta never leaves the chip.
+constexpr int ONE_LDS_BYTES = (4 * TILE * DH + 3 * DH * TLD) * 2 + 3 * TILE * 4;
+
+__global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+                                                           const bf16* __restrict__ dctx,
+                                                           const float* __restrict__ lse, bf16* __restrict__ dqkv,
+                                                           const int32_t* __restrict__ am, int nh, float scale,
+                                                           float mask_bias) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_one[];   // ONE_LDS_BYTES
+  bf16* Ks = reinterpret_cast<bf16*>(smem_one);
+  bf16* Vs = Ks + TILE * DH;
+  bf16* Qs = Vs + TILE * DH;
+  bf16* Gs = Qs + TILE * DH;
+  bf16* Kt = Gs + TILE * DH;
+  bf16* Qt = Kt + DH * TLD;
+  bf16* Gt = Qt + DH * TLD;
+  float* lse_s = reinterpret_cast<float*>(Gt + DH * TLD);
+  float* dl_s = lse_s + TILE;
+  float* bias = dl_s + TILE;
+  constexpr int S = TILE;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int H = nh * DH;
+  const size_t ld = 3 * (size_t)H;
+  const bf16* base = qkv + (size_t)b * S * ld + h * DH;
+  const bf16* gbase = dctx + (size_t)b * S * H + h * DH;
+
+  // staging: the two halves of the workgroup take different tiles
+  if (tid < 256) {
+    load_tile_rows(Ks, base + H, ld, tid);
+    load_tile_rows(Vs, base + 2 * H, ld, tid);
+    load_tile_transposed(Kt, base + H, ld, tid);
+    load_tile_rows(Gs, gbase, H, tid);
+  } else {
+    load_tile_rows(Qs, base, ld, tid - 256);
+    load_tile_transposed(Qt, base, ld, tid - 256);
+    load_tile_transposed(Gt, gbase, H, tid - 256);
+  }
+  {
+    // delta[q] = sum_d dC[q,d] * C[q,d]: four threads per query, 16 d each
+    const int q = tid >> 2, part = tid & 3;
+    const size_t o = ((size_t)b * S + q) * H + h * DH + 16 * part;
+    float dl = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      bf16x8_t g = *reinterpret_cast<const bf16x8_t*>(dctx + o + 8 * j);
+      bf16x8_t c = *reinterpret_cast<const bf16x8_t*>(ctx + o + 8 * j);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dl += (float)g[i] * (float)c[i];
+    }
+    dl += __shfl_xor(dl, 1, 64);
+    dl += __shfl_xor(dl, 2, 64);
+    if (part == 0) dl_s[q] = dl;
+  }
+  if (tid < TILE) lse_s[tid] = lse[((size_t)b * nh + h) * S + tid];
+  else if (tid < 2 * TILE) bias[tid - TILE] = am[b * S + tid - TILE] ? 0.f : mask_bias;
+  __syncthreads();
+
+  if (wave < 4) {
+    // query side: lane owns query q, registers run over keys
+    const int q = wave * 32 + n;
+    bf16x8_t qf[4], gf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)q * ld + 16 * ks + 8 * half);
+      gf[ks] = *reinterpret_cast<const bf16x8_t*>(gbase + (size_t)q * H + 16 * ks + 8 * half);
+    }
+    const float l = lse_s[q], dl = dl_s[q];
+    f32x16_t dq0 = zero16(), dq1 = zero16();
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      f32x16_t s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s = MFMA(frag_rows(Ks, kb * 32 + n, 2 * ks + half), qf[ks], s);
+        dp = MFMA(frag_rows(Vs, kb * 32 + n, 2 * ks + half), gf[ks], dp);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
+        float bv[4] = {bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float p = __expf(s[4 * g + j] * scale + bv[j] - l);
+          s[4 * g + j] = p * (dp[4 * g + j] - dl);   // dS^T
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        bf16x8_t df = pack_frag(s, c);
+        dq0 = MFMA(frag_transposed(Kt, n, kb, c, half), df, dq0);
+        dq1 = MFMA(frag_transposed(Kt, 32 + n, kb, c, half), df, dq1);
+      }
+    }
+    bf16* out = dqkv + ((size_t)b * S + wave * 32) * ld + h * DH;
+    store_acc_T(out, ld, n, half, dq0, scale);
+    store_acc_T(out + 32, ld, n, half, dq1, scale);
+  } else {
+    // key side: lane owns a key, registers run over queries
+    const int w = wave - 4;
+    const int key = w * 32 + n;
+    bf16x8_t kf[4], vf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8_t*>(base + H + (size_t)key * ld + 16 * ks + 8 * half);
+      vf[ks] = *reinterpret_cast<const bf16x8_t*>(base + 2 * H + (size_t)key * ld + 16 * ks + 8 * half);
+    }
+    const float kbias = bias[key];
+    f32x16_t dk0 = zero16(), dk1 = zero16(), dv0 = zero16(), dv1 = zero16();
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+      f32x16_t s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s = MFMA(frag_rows(Qs, qb * 32 + n, 2 * ks + half), kf[ks], s);
+        dp = MFMA(frag_rows(Gs, qb * 32 + n, 2 * ks + half), vf[ks], dp);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float4 ll = *reinterpret_cast<const float4*>(&lse_s[qb * 32 + 8 * g + 4 * half]);
+        float4 dd = *reinterpret_cast<const float4*>(&dl_s[qb * 32 + 8 * g + 4 * half]);
+        float lv[4] = {ll.x, ll.y, ll.z, ll.w}, dv[4] = {dd.x, dd.y, dd.z, dd.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float p = __expf(s[4 * g + j] * scale + kbias - lv[j]);
+          s[4 * g + j] = p;                                   // P
+          dp[4 * g + j] = p * (dp[4 * g + j] - dv[j]);        // dS
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        bf16x8_t pf = pack_frag(s, c), df = pack_frag(dp, c);
+        dv0 = MFMA(frag_transposed(Gt, n, qb, c, half), pf, dv0);
+        dv1 = MFMA(frag_transposed(Gt, 32 + n, qb, c, half), pf, dv1);
+        dk0 = MFMA(frag_transposed(Qt, n, qb, c, half), df, dk0);
+        dk1 = MFMA(frag_transposed(Qt, 32 + n, qb, c, half), df, dk1);
+      }
+    }
+    bf16* out = dqkv + ((size_t)b * S + w * 32) * ld + h * DH;
+    store_acc_T(out + H, ld, n, half, dk0, scale);
+    store_acc_T(out + H + 32, ld, n, half, dk1, scale);
+    store_acc_T(out + 2 * H, ld, n, half, dv0, 1.0f);
+    store_acc_T(out + 2 * H + 32, ld, n, half, dv1, 1.0f);
+  }
+}
+
 constexpr int KV_LDS_BYTES = (2 * TILE * DH + 2 * DH * TLD) * 2 + 2 * TILE * 4;
 
 bool attention_mfma_supported(int S, int dh) { return dh == DH && S >= TILE && S % TILE == 0; }
@@ -366,6 +517,19 @@ hipError_t attention_bwd_mfma(const AttnBwdDesc& a, hipStream_t s) {
   if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
   dim3 grid(a.S / TILE, a.nh, a.B);
   float scale = 1.0f / sqrtf((float)a.dh);
+  if (a.S == TILE) {
+    static bool one_attr_set = false;
+    if (!one_attr_set) {
+      hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_bwd_one_tile),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, ONE_LDS_BYTES);
+      if (e1 != hipSuccess) return e1;
+      one_attr_set = true;
+    }
+    k_attn_bwd_one_tile<<<dim3(a.nh, a.B), dim3(512), ONE_LDS_BYTES, s>>>(
+        (const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse, (bf16*)a.dqkv, a.attn_mask, a.nh, scale,
+        a.mask_bias);
+    return hipGetLastError();
+  }
   k_attn_bwd_q_mfma<<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse,
                                                a.delta, (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale, a.mask_bias);
   hipError_t e = hipGetLastError();
