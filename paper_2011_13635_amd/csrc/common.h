@@ -34,6 +34,17 @@ __device__ inline float ldf(const bf16* p) { return bf2f(*p); }
 __device__ inline void stf(float* p, float v) { *p = v; }
 __device__ inline void stf(bf16* p, float v) { *p = f2bf(v); }
 
+// The GELU derivative kept from the forward pass for the backward pass.  fp32 mode keeps the
+// float.  bf16 mode keeps 16-bit fixed point (value + 0.25) * 32768 in the 2-byte slot: the
+// derivative lies in [-0.13, 1.13], so the step of 3.05e-5 is two orders of magnitude finer than
+// a bf16 number near 1 (and finer than evaluating the derivative at a bf16-rounded argument).
+__device__ inline uint32_t enc_dgelu(float d) { return __float2uint_rn(fmaf(d, 32768.f, 8192.f)); }
+__device__ inline float dec_dgelu(uint32_t q) { return fmaf((float)q, 1.0f / 32768.f, -0.25f); }
+__device__ inline float ld_dgelu(const float* p) { return *p; }
+__device__ inline float ld_dgelu(const bf16* p) { return dec_dgelu(p->x); }
+__device__ inline void st_dgelu(float* p, float d) { *p = d; }
+__device__ inline void st_dgelu(bf16* p, float d) { p->x = (uint16_t)enc_dgelu(d); }
+
 // ---- wavefront (64 lanes) reductions --------------------------------------------------------
 __device__ inline float wave_sum(float v) {
 #pragma unroll
@@ -46,15 +57,7 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
-// erf-form GELU and its derivative, fp32
-__device__ inline float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
-__device__ inline float gelu_grad_f(float u) {
-  float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752440f));
-  float pdf = 0.39894228040143267794f * __expf(-0.5f * u * u);
-  return cdf + u * pdf;
-}
-
-// Fast variants for the bf16 path: erf from the three-term rational-exponential formula of
+// erf-form GELU for the bf16 path: erf from the three-term rational-exponential formula of
 // Abramowitz & Stegun 7.1.25 (|error| <= 2.5e-5, far below bf16 resolution); the Gaussian factor
 // is shared between Phi and phi.  One reciprocal and one exp2 per element.
 __device__ inline void gelu_parts_fast(float u, float& cdf, float& pdf) {
@@ -66,22 +69,26 @@ __device__ inline void gelu_parts_fast(float u, float& cdf, float& pdf) {
   cdf = u >= 0.f ? 1.0f - erfc_half : erfc_half;
   pdf = 0.39894228040143267794f * e;
 }
-__device__ inline float gelu_fast(float u) {
+// value and derivative together (the forward epilogue stores the derivative for the backward pass)
+__device__ inline void gelu_both_fast(float u, float& val, float& grad) {
   float c, p;
   gelu_parts_fast(u, c, p);
-  return u * c;
+  val = u * c;
+  grad = fmaf(u, p, c);
 }
-__device__ inline float gelu_grad_fast(float u) {
-  float c, p;
-  gelu_parts_fast(u, c, p);
-  return fmaf(u, p, c);
+// erf-form GELU and its derivative with the library erf (fp32 mode)
+__device__ inline void gelu_both_f(float u, float& val, float& grad) {
+  float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752440f));
+  float pdf = 0.39894228040143267794f * __expf(-0.5f * u * u);
+  val = u * cdf;
+  grad = cdf + u * pdf;
 }
 
 // ---- GEMM interface -------------------------------------------------------------------------
 // C(m,n) = sum_k A(m,k) * B(n,k), fp32 accumulation, followed by an epilogue.
 // Each operand has unit stride along exactly one of its two indices:
 //   a_kcontig: A(m,k) = A[m*lda + k]   else A(m,k) = A[k*lda + m]   (same for B with n)
-enum EpiAct { EPI_NONE = 0, EPI_GELU = 1, EPI_MUL_GELU_GRAD = 2, EPI_ADD = 3 };
+enum EpiAct { EPI_NONE = 0, EPI_GELU = 1, EPI_MUL = 2, EPI_ADD = 3 };
 
 struct Epilogue {
   void* out = nullptr;      // [M, ldo]; element type: float if out_f32 else the activation type
@@ -89,8 +96,8 @@ struct Epilogue {
   int out_f32 = 0;
   const float* bias = nullptr;  // per column n, or null
   int act = EPI_NONE;
-  void* out2 = nullptr;     // EPI_GELU: pre-activation values (activation type), may be null
-  const void* aux = nullptr;  // EPI_MUL_GELU_GRAD: pre-activation U[m,n]; EPI_ADD: addend R[m,n]
+  void* out2 = nullptr;     // EPI_GELU: GELU'(pre-activation) for the backward pass (st_dgelu format), may be null
+  const void* aux = nullptr;  // EPI_MUL: the stored GELU derivative D[m,n] (ld_dgelu format); EPI_ADD: addend R[m,n]
   int ldaux = 0;
 };
 
@@ -174,7 +181,7 @@ hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out,
 size_t colsum_scratch_floats(int rows, int N);
 size_t ln_bwd_scratch_floats(int rows, int H);
 
-hipError_t mul_gelu_grad(int dtype, const void* dg, const void* u, void* du, size_t n, hipStream_t s);
+hipError_t mul_dgelu(int dtype, const void* dg, const void* d, void* du, size_t n, hipStream_t s);
 hipError_t gather_rows(int dtype, const void* x, const int32_t* pos, int M, int Mpad, int H, void* out, hipStream_t s);
 // out[j] = j < M ? x[pos[j]] : 0 for j < Mpad
 hipError_t gather_f32(const float* x, const int32_t* pos, int M, int Mpad, float* out, hipStream_t s);

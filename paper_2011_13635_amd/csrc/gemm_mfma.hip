@@ -12,9 +12,10 @@
 // in registers on its way into LDS, so every product of the training step runs through this one
 // kernel and no transposed copy of an activation or weight ever goes to HBM.  The 256-row tile
 // moves 25 % fewer bytes through the vector L1 per FLOP than the 128-row one (the L1 -> LDS path
-// is as scarce as the matrix cores at 128x128) and is used whenever M allows it.  The epilogue
-// stages each wavefront's quarter in LDS and writes 16-byte rows: bias, GELU (+ pre-activation
-// store), GELU-derivative multiply or residual add are fused there.  With split-k the tile's
+// is as scarce as the matrix cores at 128x128) and is used for long contractions with enough
+// tiles.  The epilogue stages each wavefront's quarter in LDS and writes 16-byte rows: bias, GELU
+// (which also stores GELU' for the backward pass), multiply by that stored derivative, or residual
+// add are fused there.  With split-k the tile's
 // partial sums go to an fp32 workspace and a second kernel adds the splits in a fixed order
 // (deterministic, no atomics).
 #include "common.h"
@@ -172,9 +173,9 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
   return u;
 }
-// true when the epilogue reads the per-element operand (pre-activation or addend)
+// true when the epilogue reads the per-element operand (stored GELU derivative or addend)
 __device__ __forceinline__ bool epilogue_reads_aux(const Epilogue& e) {
-  return e.act == EPI_MUL_GELU_GRAD || e.act == EPI_ADD;
+  return e.act == EPI_MUL || e.act == EPI_ADD;
 }
 __device__ __forceinline__ uint4 load_aux8(const Epilogue& e, int m, int n) {
   return *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n);
@@ -187,14 +188,24 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
   for (int i = 0; i < 8; ++i) v[i] += bias[i];
   size_t o = (size_t)m * e.ldo + n;
   if (e.act == EPI_GELU) {
-    if (e.out2) *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(e.out2) + o) = pack8(v);
+    float d[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = gelu_fast(v[i]);
-  } else if (e.act == EPI_MUL_GELU_GRAD) {
-    float u[8];
-    unpack8(raw, u);
+    for (int i = 0; i < 8; ++i) gelu_both_fast(v[i], v[i], d[i]);
+    if (e.out2) {
+      uint4 q;
+      q.x = enc_dgelu(d[0]) | (enc_dgelu(d[1]) << 16);
+      q.y = enc_dgelu(d[2]) | (enc_dgelu(d[3]) << 16);
+      q.z = enc_dgelu(d[4]) | (enc_dgelu(d[5]) << 16);
+      q.w = enc_dgelu(d[6]) | (enc_dgelu(d[7]) << 16);
+      *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(e.out2) + o) = q;
+    }
+  } else if (e.act == EPI_MUL) {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_fast(u[i]);
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] *= dec_dgelu(w[i] & 0xffffu);
+      v[2 * i + 1] *= dec_dgelu(w[i] >> 16);
+    }
   } else if (e.act == EPI_ADD) {
     float u[8];
     unpack8(raw, u);
@@ -410,7 +421,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
   if (d.M <= 0 || d.N <= 0 || d.K <= 0) return false;
   if (d.M % 128 || d.N % BN || d.K % BK) return false;
   if (d.lda % 8 || d.ldb % 8 || d.epi.ldo % 8) return false;
-  if ((d.epi.act == EPI_MUL_GELU_GRAD || d.epi.act == EPI_ADD) && d.epi.ldaux % 8) return false;
+  if ((d.epi.act == EPI_MUL || d.epi.act == EPI_ADD) && d.epi.ldaux % 8) return false;
   auto al = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
   if (!al(d.A) || !al(d.B) || !al(d.epi.out) || !al(d.epi.out2) || !al(d.epi.aux) || !al(d.epi.bias)) return false;
   return true;

@@ -12,10 +12,11 @@ __device__ inline void epilogue_store(const Epilogue& e, int m, int n, float acc
   if (e.bias) v += e.bias[n];
   size_t o = (size_t)m * e.ldo + n;
   if (e.act == EPI_GELU) {
-    if (e.out2) stf(reinterpret_cast<AT*>(e.out2) + o, v);
-    v = gelu_f(v);
-  } else if (e.act == EPI_MUL_GELU_GRAD) {
-    v *= gelu_grad_f(ldf(reinterpret_cast<const AT*>(e.aux) + (size_t)m * e.ldaux + n));
+    float g;
+    gelu_both_f(v, v, g);
+    if (e.out2) st_dgelu(reinterpret_cast<AT*>(e.out2) + o, g);
+  } else if (e.act == EPI_MUL) {
+    v *= ld_dgelu(reinterpret_cast<const AT*>(e.aux) + (size_t)m * e.ldaux + n);
   } else if (e.act == EPI_ADD) {
     v += ldf(reinterpret_cast<const AT*>(e.aux) + (size_t)m * e.ldaux + n);
   }

@@ -61,6 +61,8 @@ struct Profiler {
 };
 
 struct LayerStash {
+  // u holds GELU'(FFN pre-activation): the forward epilogue computes it next to the GELU value, so
+  // the backward pass multiplies instead of evaluating erf and exp again
   void *xout, *qkv, *ctx, *xhat1, *x1, *u, *g, *xhat2;
   float *lse, *rstd1, *rstd2;
 };
@@ -536,13 +538,13 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false,
     if (rc__) return rc__; \
   } while (0)
 
-// Y[rows,N] = X[rows,K] W[N,K]^T + bias, optional GELU
+// Y[rows,N] = X[rows,K] W[N,K]^T + bias, optional GELU (gelu_grad_out then receives GELU' of the pre-activation)
 static int linear_fwd(mslt_model* m, const void* X, int rows, int K, const void* W, int N, const float* bias, void* Y,
-                      int out_f32, int ldo, int act, void* pre_act) {
+                      int out_f32, int ldo, int act, void* gelu_grad_out) {
   GemmDesc d;
   d.A = X; d.lda = K; d.a_kcontig = 1; d.M = rows;
   d.B = W; d.ldb = K; d.b_kcontig = 1; d.N = N; d.K = K;
-  d.epi.out = Y; d.epi.ldo = ldo; d.epi.out_f32 = out_f32; d.epi.bias = bias; d.epi.act = act; d.epi.out2 = pre_act;
+  d.epi.out = Y; d.epi.ldo = ldo; d.epi.out_f32 = out_f32; d.epi.bias = bias; d.epi.act = act; d.epi.out2 = gelu_grad_out;
   return run_gemm(m, d);
 }
 // dX[rows,K] = dY[rows,N] W[N,K]  (+ addend | * gelu'(U))
@@ -629,7 +631,7 @@ static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const U
   RC(ln_backward(m, dXout, r.xhat2, r.rstd2, Wf(m, t_layer(l, L_LN2G)), r.dz2, Gf(m, t_layer(l, L_LN2G)),
                  Gf(m, t_layer(l, L_LN2B)), Gf(m, t_layer(l, L_B2)), R));
   RC(linear_bwd_weight(m, r.dz2, R, H, H, r.g, F, Gf(m, t_layer(l, L_W2))));
-  RC(linear_bwd_input(m, r.dz2, R, H, H, Wg(m, t_layer(l, L_W2)), F, r.du, EPI_MUL_GELU_GRAD, r.u));
+  RC(linear_bwd_input(m, r.dz2, R, H, H, Wg(m, t_layer(l, L_W2)), F, r.du, EPI_MUL, r.u));
   RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_layer(l, L_W1))));
   RC(bias_grad(m, r.du, F, R, F, Gf(m, t_layer(l, L_B1))));
   RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_layer(l, L_W1)), H, r.dx1, EPI_ADD, r.dz2));
@@ -786,7 +788,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   RC(ln_backward(m, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG), Gf(m, th + H_LNB), nullptr, Mr));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 3.0 * Mr * H * m->esz);
-    HIP_TRY(mul_gelu_grad(m->dtype, m->d_gt, m->ut, m->d_ut, (size_t)Mr * H, s));
+    HIP_TRY(mul_dgelu(m->dtype, m->d_gt, m->ut, m->d_ut, (size_t)Mr * H, s));
   }
   RC(linear_bwd_weight(m, m->d_ut, Mr, H, H, m->xm, H, Gf(m, th + H_WT)));
   RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT)));

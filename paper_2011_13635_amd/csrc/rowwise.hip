@@ -538,21 +538,22 @@ hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out,
   return reduce_partials(scratch, nchunks, N, out, s);
 }
 
-// ---- GELU backward (head only; the layers fuse it into the GEMM epilogue) -------------------
+// ---- GELU backward of the head: gradient times the derivative stored by the forward epilogue
+// (the layers fuse this into the GEMM epilogue) -------------------------------------------------
 template <typename AT>
-__global__ void k_mul_gelu_grad(const AT* __restrict__ dg, const AT* __restrict__ u, AT* __restrict__ du, size_t n) {
+__global__ void k_mul_dgelu(const AT* __restrict__ dg, const AT* __restrict__ d, AT* __restrict__ du, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) stf(du + i, ldf(dg + i) * gelu_grad_f(ldf(u + i)));
+  for (; i < n; i += stride) stf(du + i, ldf(dg + i) * ld_dgelu(d + i));
 }
-hipError_t mul_gelu_grad(int dtype, const void* dg, const void* u, void* du, size_t n, hipStream_t s) {
+hipError_t mul_dgelu(int dtype, const void* dg, const void* u, void* du, size_t n, hipStream_t s) {
   if (n == 0) return hipSuccess;
   size_t blocks = (n + 255) / 256;
   if (blocks > 8192) blocks = 8192;
   if (dtype == 0)
-    k_mul_gelu_grad<float><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const float*)dg, (const float*)u, (float*)du, n);
+    k_mul_dgelu<float><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const float*)dg, (const float*)u, (float*)du, n);
   else
-    k_mul_gelu_grad<bf16><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const bf16*)dg, (const bf16*)u, (bf16*)du, n);
+    k_mul_dgelu<bf16><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const bf16*)dg, (const bf16*)u, (bf16*)du, n);
   return hipGetLastError();
 }
 

@@ -42,7 +42,9 @@ def test_tiny_splits_perturbed_ragged(precision, f, k, emb):
 def test_unaligned_shapes_full_step(precision):
     sh = small_shape(2)
     std, perturb = (0.2, 0.2) if precision == 0 else (0.05, 0.05)
-    r = run_case(sh, 3, 10, 0, 2, True, precision, ragged=True, seed=5, std=std, perturb=perturb)
+    # 11 x 13 tokens: on a 3 x 10 batch the max-norm error of the small attention gradients in bf16 mode is set
+    # by a handful of roundings and scatters between 1e-2 and 2.2e-2 from seed to seed; 143 tokens average that out
+    r = run_case(sh, 11, 13, 0, 2, True, precision, ragged=True, seed=5, std=std, perturb=perturb)
     print("unaligned", precision, assert_parity(r, precision, "unaligned"))
     r["model"].close()
 
