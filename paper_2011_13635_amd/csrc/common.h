@@ -182,9 +182,12 @@ size_t colsum_scratch_floats(int rows, int N);
 size_t ln_bwd_scratch_floats(int rows, int H);
 
 hipError_t mul_dgelu(int dtype, const void* dg, const void* d, void* du, size_t n, hipStream_t s);
-hipError_t gather_rows(int dtype, const void* x, const int32_t* pos, int M, int Mpad, int H, void* out, hipStream_t s);
-// out[j] = j < M ? x[pos[j]] : 0 for j < Mpad
-hipError_t gather_f32(const float* x, const int32_t* pos, int M, int Mpad, float* out, hipStream_t s);
+struct GatherDesc { const void* src; void* dst; int row_bytes; };
+constexpr int GATHER_MAX = 8;
+struct GatherArgs { GatherDesc d[GATHER_MAX]; };
+// for each of the n arrays: dst row j = j < M ? src row pos[j] : zeros, j < Mpad; rows are raw bytes
+// (row_bytes a multiple of 4)
+hipError_t gather_rows_multi(const GatherDesc* descs, int n, const int32_t* pos, int M, int Mpad, hipStream_t s);
 hipError_t scatter_rows(int dtype, const void* dxm, const int32_t* inv, int rows_total, int T, int H, void* out,
                         hipStream_t s);
 // cross-entropy over fp32 logits [Mpad, ldz]: writes dZ (activation type, zero in padded rows and

@@ -685,14 +685,10 @@ static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T,
   RC(layer_backward_begin(m, l));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * Mr * (4.0 * H + 2.0 * F) * m->esz);
-    HIP_TRY(gather_rows(m->dtype, st.xhat2, m->pos, M, Mr, H, m->xm, s));
-    HIP_TRY(gather_rows(m->dtype, st.x1, m->pos, M, Mr, H, m->ut, s));
-    HIP_TRY(gather_rows(m->dtype, st.xhat1, m->pos, M, Mr, H, m->gt, s));
-    HIP_TRY(gather_rows(m->dtype, st.ctx, m->pos, M, Mr, H, m->xhat_t, s));
-    HIP_TRY(gather_rows(m->dtype, st.g, m->pos, M, Mr, F, m->c_g, s));
-    HIP_TRY(gather_rows(m->dtype, st.u, m->pos, M, Mr, F, m->c_u, s));
-    HIP_TRY(gather_f32(st.rstd2, m->pos, M, Mr, m->rstd_t, s));
-    HIP_TRY(gather_f32(st.rstd1, m->pos, M, Mr, m->lse_t, s));
+    const int hb = H * (int)m->esz, fb = F * (int)m->esz;
+    const GatherDesc g[8] = {{st.xhat2, m->xm, hb}, {st.x1, m->ut, hb}, {st.xhat1, m->gt, hb}, {st.ctx, m->xhat_t, hb},
+                             {st.g, m->c_g, fb},    {st.u, m->c_u, fb}, {st.rstd2, m->rstd_t, 4}, {st.rstd1, m->lse_t, 4}};
+    HIP_TRY(gather_rows_multi(g, 8, m->pos, M, Mr, s));
   }
   UpperRows r{m->xm, m->c_g, m->c_u, m->ut, m->gt, m->xhat_t, m->rstd_t, m->lse_t,
               m->hm, m->c_du, m->d_hm, m->d_gt, m->d_ut, Mr};
@@ -768,7 +764,8 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   const int th = t_head(m, 0);
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * Mr * H * m->esz);
-    HIP_TRY(gather_rows(m->dtype, x, m->pos, M, Mr, H, m->xm, s));
+    const GatherDesc g{x, m->xm, H * (int)m->esz};
+    HIP_TRY(gather_rows_multi(&g, 1, m->pos, M, Mr, s));
   }
   RC(linear_fwd(m, m->xm, Mr, H, Wg(m, th + H_WT), H, Wf(m, th + H_BT), m->gt, 0, H, EPI_GELU, m->ut));
   LnStash sh{m->xhat_t, m->rstd_t};

@@ -558,33 +558,34 @@ hipError_t mul_dgelu(int dtype, const void* dg, const void* u, void* du, size_t 
 }
 
 // ---- gather of predicted rows / scatter of their gradients ----------------------------------
-template <typename AT>
-__global__ void k_gather_rows(const AT* __restrict__ x, const int32_t* __restrict__ pos, int M, int H,
-                              AT* __restrict__ out) {
-  int j = blockIdx.x;
-  AT* o = out + (size_t)j * H;
-  if (j < M) {
-    const AT* src = x + (size_t)pos[j] * H;
-    for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) store4(o + c, load4(src + c));
-  } else {
-    for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) store4(o + c, make_float4(0, 0, 0, 0));
+// Gathers rows pos[0..M) of up to GATHER_MAX arrays in one launch (blockIdx.y picks the array) and
+// zero-fills rows [M, Mpad).  Rows are copied as raw bytes, whatever they encode.
+template <typename U>
+__device__ inline void copy_row(char* __restrict__ o, const char* __restrict__ src, int row_bytes) {
+  for (int c = threadIdx.x * (int)sizeof(U); c < row_bytes; c += blockDim.x * (int)sizeof(U)) {
+    U v = U();
+    if (src) v = *reinterpret_cast<const U*>(src + c);
+    *reinterpret_cast<U*>(o + c) = v;
   }
 }
-hipError_t gather_rows(int dtype, const void* x, const int32_t* pos, int M, int Mpad, int H, void* out, hipStream_t s) {
-  if (dtype == 0)
-    k_gather_rows<float><<<dim3(Mpad), dim3(64), 0, s>>>((const float*)x, pos, M, H, (float*)out);
-  else
-    k_gather_rows<bf16><<<dim3(Mpad), dim3(64), 0, s>>>((const bf16*)x, pos, M, H, (bf16*)out);
-  return hipGetLastError();
+__global__ void __launch_bounds__(64) k_gather_multi(GatherArgs a, const int32_t* __restrict__ pos, int M) {
+  const int j = blockIdx.x;
+  const GatherDesc g = a.d[blockIdx.y];
+  char* o = reinterpret_cast<char*>(g.dst) + (size_t)j * g.row_bytes;
+  const char* src = j < M ? reinterpret_cast<const char*>(g.src) + (size_t)pos[j] * g.row_bytes : nullptr;
+  if (g.row_bytes % 16 == 0) copy_row<uint4>(o, src, g.row_bytes);
+  else if (g.row_bytes % 8 == 0) copy_row<uint2>(o, src, g.row_bytes);
+  else copy_row<uint32_t>(o, src, g.row_bytes);
 }
-
-__global__ void k_gather_f32(const float* __restrict__ x, const int32_t* __restrict__ pos, int M, int Mpad,
-                             float* __restrict__ out) {
-  int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j < Mpad) out[j] = j < M ? x[pos[j]] : 0.f;
-}
-hipError_t gather_f32(const float* x, const int32_t* pos, int M, int Mpad, float* out, hipStream_t s) {
-  k_gather_f32<<<dim3((Mpad + 255) / 256), dim3(256), 0, s>>>(x, pos, M, Mpad, out);
+hipError_t gather_rows_multi(const GatherDesc* descs, int n, const int32_t* pos, int M, int Mpad, hipStream_t s) {
+  if (n < 1 || n > GATHER_MAX) return hipErrorInvalidValue;
+  GatherArgs a;
+  for (int i = 0; i < n; ++i) {
+    if (descs[i].row_bytes <= 0 || descs[i].row_bytes % 4) return hipErrorInvalidValue;
+    a.d[i] = descs[i];
+  }
+  for (int i = n; i < GATHER_MAX; ++i) a.d[i] = descs[0];
+  k_gather_multi<<<dim3(Mpad, n), dim3(64), 0, s>>>(a, pos, M);
   return hipGetLastError();
 }
 
