@@ -216,7 +216,9 @@ def main():
                      "WRITE_SIZE scaled by a 256 MiB copy)", "algorithmic_bytes_per_launch":
                      round(sum(v["bytes"] for v in gemm) / max(g_launch, 1)), "launches_per_step": round(g_launch, 1),
                      "avg_launch_us": round(g_ms * 1e3 / max(g_launch, 1), 2),
-                     "gemm_ms_per_step": round(g_ms, 4), "gemm_gflop_per_step": round(g_flops / 1e9, 1)},
+                     "gemm_ms_per_step": round(g_ms, 4), "gemm_gflop_per_step": round(g_flops / 1e9, 1),
+                     "timed_with": "HIP events around every launch on the library's stream; the interval also holds "
+                     "the fixed-order split-k summing kernel of a product and the dispatch latency of the launch"},
         "kernel_classes": classes,
         "profiled_ms_per_step": round(sum(v["ms"] for v in prof.values()), 4),
     }

@@ -12,12 +12,16 @@ import hashlib
 import os
 import sys
 
-KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "gemm_mfma.hip")
+CSRC = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+KERNEL_SOURCES = [os.path.join(CSRC, "gemm_mfma.hip"), os.path.join(CSRC, "common.h")]   # kernel + its epilogue helpers
 COPY_BYTES = 256 * 1024 * 1024
 
 
 def kernel_source_hash() -> str:
-    return hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+    h = hashlib.sha256()
+    for path in KERNEL_SOURCES:
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
 
 
 def read_counter(path):
