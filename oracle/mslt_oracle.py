@@ -19,7 +19,9 @@ file.  It imports nothing from the GPU package and shares no code with it.
 Pins (tests/test_oracle_*.py): central finite differences of every tensor;
 triple-loop products; softmax/LayerNorm invariants; loss = ln V closed form;
 uniform-attention and S=1 special cases; stage-step gradients equal the full-step
-gradients of the same tensors; Adam and LAMB one-step closed forms.  The paper
+gradients of the same tensors; Adam and LAMB one-step closed forms; dropout: the
+generator against the published SplitMix64 sequence, keep rate, and finite
+differences with the masks held fixed.  The paper
 prints no worked numerical example, so absolute values have no published pin.
 """
 from __future__ import annotations
@@ -103,19 +105,77 @@ def to_f64(params):
 
 
 # ----------------------------------------------------------------------------------------------
+# dropout ("all other settings are the same as BERT", Section 4.1: probability 0.1 on the embedding
+# output, the attention probabilities, the attention output and the feed-forward output)
+# ----------------------------------------------------------------------------------------------
+# The keep decisions come from a counter-based generator so that any implementation can reproduce
+# them bit for bit: the SplitMix64 output function (Steele, Lea, Flood 2014) applied to
+# key + quad * GOLDEN, where quad = element_index // 4 and the four 16-bit fields of the 64-bit
+# result decide elements 4*quad .. 4*quad+3 (field j = bits 16j..16j+15): keep iff field >= thr,
+# thr = round(p * 65536).  Kept values are scaled by 1 / (1 - p).  The key mixes the user's seed
+# with (step, layer, site); element_index is the C-order index in the tensor the mask applies to.
+GOLDEN = 0x9E3779B97F4A7C15
+_M64 = (1 << 64) - 1
+SITE_EMBEDDING, SITE_ATTN_PROBS, SITE_ATTN_OUT, SITE_FFN_OUT = 0, 1, 2, 3
+
+
+def mix64(z: int) -> int:
+    z &= _M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+    return z ^ (z >> 31)
+
+
+def mix64_array(z):
+    z = np.asarray(z, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+    return z ^ (z >> np.uint64(31))
+
+
+def dropout_key(seed: int, step: int, layer: int, site: int) -> int:
+    stream = (step << 20) | (layer << 4) | site
+    return mix64(seed ^ mix64(stream + GOLDEN))
+
+
+class Dropout:
+    """Dropout settings of one step: probability, seed and step number."""
+
+    def __init__(self, p: float, seed: int, step: int):
+        self.p, self.seed, self.step = float(p), int(seed), int(step)
+        self.thr = int(round(self.p * 65536.0))
+        self.scale = 1.0 / (1.0 - self.p)
+
+    def mask(self, layer: int, site: int, shape):
+        """Array of `shape` holding 0 (dropped) or 1/(1-p) (kept)."""
+        n = int(np.prod(shape))
+        key = dropout_key(self.seed, self.step, layer, site)
+        quads = np.arange((n + 3) // 4, dtype=np.uint64)
+        with np.errstate(over="ignore"):
+            r = mix64_array(np.uint64(key) + quads * np.uint64(GOLDEN))
+        fields = np.stack([(r >> np.uint64(16 * j)) & np.uint64(0xFFFF) for j in range(4)], axis=1).reshape(-1)[:n]
+        return np.where(fields >= np.uint64(self.thr), self.scale, 0.0).reshape(shape)
+
+
+# ----------------------------------------------------------------------------------------------
 # forward
 # ----------------------------------------------------------------------------------------------
-def embed_forward(cfg, P, batch):
+def embed_forward(cfg, P, batch, drop=None):
     ids = np.asarray(batch["input_ids"]).reshape(-1)
     tt = np.asarray(batch["token_type_ids"]).reshape(-1)
     B, S = np.asarray(batch["input_ids"]).shape
     pos = np.tile(np.arange(S), B)
     z = P["emb.word"][ids] + P["emb.pos"][pos] + P["emb.type"][tt]
     x0, ln = layer_norm(z, P["emb.ln_g"], P["emb.ln_b"], cfg.ln_eps)
-    return x0, {"ids": ids, "tt": tt, "pos": pos, "ln": ln}
+    mE = None
+    if drop is not None:
+        mE = drop.mask(0, SITE_EMBEDDING, x0.shape)
+        x0 = x0 * mE
+    return x0, {"ids": ids, "tt": tt, "pos": pos, "ln": ln, "mE": mE}
 
 
-def layer_forward(cfg, P, i, X, key_bias, B, S, ops):
+def layer_forward(cfg, P, i, X, key_bias, B, S, ops, drop=None):
     """One post-LN encoder layer. X is [T, H]; key_bias is [B, S] (0 for tokens, mask_bias for padding)."""
     p = f"layer{i}."
     H, nh = cfg.hidden, cfg.n_heads
@@ -126,6 +186,9 @@ def layer_forward(cfg, P, i, X, key_bias, B, S, ops):
     C = np.empty_like(X)
     Pr = np.empty((B, nh, S, S), dtype=np.float64)
     scale = 1.0 / math.sqrt(dh)
+    mA = drop.mask(i, SITE_ATTN_PROBS, (B, nh, S, S)) if drop is not None else None
+    mO = drop.mask(i, SITE_ATTN_OUT, X.shape) if drop is not None else None
+    mF = drop.mask(i, SITE_FFN_OUT, X.shape) if drop is not None else None
     for b in range(B):
         rows = slice(b * S, (b + 1) * S)
         for h in range(nh):
@@ -133,14 +196,20 @@ def layer_forward(cfg, P, i, X, key_bias, B, S, ops):
             A = ops.mm(Q[rows, cols], K[rows, cols].T) * scale + key_bias[b][None, :]
             Pbh = softmax_rows(A)
             Pr[b, h] = Pbh
-            C[rows, cols] = ops.mm(Pbh, V[rows, cols])
+            Pd = Pbh if mA is None else Pbh * mA[b, h]
+            C[rows, cols] = ops.mm(Pd, V[rows, cols])
     O = ops.mm(C, P[p + "wo"].T) + P[p + "bo"]
+    if mO is not None:
+        O = O * mO
     X1, ln1 = layer_norm(X + O, P[p + "ln1_g"], P[p + "ln1_b"], cfg.ln_eps)
     U = ops.mm(X1, P[p + "w1"].T) + P[p + "b1"]
     G = gelu(U)
     D = ops.mm(G, P[p + "w2"].T) + P[p + "b2"]
+    if mF is not None:
+        D = D * mF
     X2, ln2 = layer_norm(X1 + D, P[p + "ln2_g"], P[p + "ln2_b"], cfg.ln_eps)
-    cache = {"X": X, "Q": Q, "K": K, "V": V, "P": Pr, "C": C, "ln1": ln1, "X1": X1, "U": U, "G": G, "ln2": ln2}
+    cache = {"X": X, "Q": Q, "K": K, "V": V, "P": Pr, "C": C, "ln1": ln1, "X1": X1, "U": U, "G": G, "ln2": ln2,
+             "mA": mA, "mO": mO, "mF": mF}
     return X2, cache
 
 
@@ -165,7 +234,7 @@ def head_forward(cfg, P, XL, pos, Y, ops):
     return loss, {"Xm": Xm, "Ut": Ut, "Gt": Gt, "Hm": Hm, "ln": ln, "Z": Z, "lse": lse, "pos": pos, "Y": Y}
 
 
-def forward(cfg, params, batch, n_layers=None, ops=None, keep_from=0, prefix_at=None):
+def forward(cfg, params, batch, n_layers=None, ops=None, keep_from=0, prefix_at=None, drop=None):
     """Forward through the embedding block, layers 0..n_layers-1 and the masked-LM head.
 
     Layer caches below `keep_from` are dropped (those layers run forward only).
@@ -179,13 +248,13 @@ def forward(cfg, params, batch, n_layers=None, ops=None, keep_from=0, prefix_at=
     ids = np.asarray(batch["input_ids"])
     B, S = ids.shape
     key_bias = (1.0 - np.asarray(batch["attn_mask"], dtype=np.float64)) * cfg.mask_bias
-    X, emb_cache = embed_forward(cfg, P, batch)
+    X, emb_cache = embed_forward(cfg, P, batch, drop)
     layer_caches = [None] * n_layers
     prefix_out = None
     for i in range(n_layers):
         if i == prefix_at:
             prefix_out = X
-        X, c = layer_forward(cfg, P, i, X, key_bias, B, S, ops)
+        X, c = layer_forward(cfg, P, i, X, key_bias, B, S, ops, drop)
         if i >= keep_from:
             layer_caches[i] = c
     pos, Y = masked_rows(batch)
@@ -227,7 +296,7 @@ def layer_backward(cfg, P, i, c, dX2, B, S, ops):
     scale = 1.0 / math.sqrt(dh)
     g = {}
     dZ2, g[p + "ln2_g"], g[p + "ln2_b"] = layer_norm_backward(dX2, P[p + "ln2_g"], c["ln2"])
-    dD = dZ2
+    dD = dZ2 if c.get("mF") is None else dZ2 * c["mF"]
     g[p + "w2"] = ops.mm(dD.T, c["G"])
     g[p + "b2"] = dD.sum(axis=0)
     dG = ops.mm(dD, P[p + "w2"])
@@ -236,7 +305,7 @@ def layer_backward(cfg, P, i, c, dX2, B, S, ops):
     g[p + "b1"] = dU.sum(axis=0)
     dX1 = ops.mm(dU, P[p + "w1"]) + dZ2
     dZ1, g[p + "ln1_g"], g[p + "ln1_b"] = layer_norm_backward(dX1, P[p + "ln1_g"], c["ln1"])
-    dO = dZ1
+    dO = dZ1 if c.get("mO") is None else dZ1 * c["mO"]
     g[p + "wo"] = ops.mm(dO.T, c["C"])
     g[p + "bo"] = dO.sum(axis=0)
     dC = ops.mm(dO, P[p + "wo"])
@@ -249,8 +318,12 @@ def layer_backward(cfg, P, i, c, dX2, B, S, ops):
             cols = slice(h * dh, (h + 1) * dh)
             Pbh = c["P"][b, h]
             dCbh = dC[rows, cols]
-            dV[rows, cols] = ops.mm(Pbh.T, dCbh)
+            mA = None if c.get("mA") is None else c["mA"][b, h]
+            Pd = Pbh if mA is None else Pbh * mA
+            dV[rows, cols] = ops.mm(Pd.T, dCbh)
             dP = ops.mm(dCbh, c["V"][rows, cols].T)
+            if mA is not None:
+                dP = dP * mA
             dA = Pbh * (dP - (dP * Pbh).sum(axis=-1, keepdims=True))
             dQ[rows, cols] = ops.mm(dA, c["K"][rows, cols]) * scale
             dK[rows, cols] = ops.mm(dA.T, c["Q"][rows, cols]) * scale
@@ -264,6 +337,8 @@ def layer_backward(cfg, P, i, c, dX2, B, S, ops):
 
 def embed_backward(cfg, P, ec, dX0):
     g = {}
+    if ec.get("mE") is not None:
+        dX0 = dX0 * ec["mE"]
     dz, g["emb.ln_g"], g["emb.ln_b"] = layer_norm_backward(dX0, P["emb.ln_g"], ec["ln"])
     gw = np.zeros_like(P["emb.word"])
     gp = np.zeros_like(P["emb.pos"])
@@ -301,7 +376,7 @@ def stage_tensor_names(frozen_layers, trainable_layers, train_embeddings):
 
 
 def stage_step(cfg, params, batch, frozen_layers, trainable_layers, train_embeddings=False, ops=None,
-               full_backprop=False):
+               full_backprop=False, drop=None):
     """Loss and gradients of one MSLT stage step (Section 3.2).
 
     Layers [0, frozen) run forward only; layers [frozen, frozen+trainable) and the
@@ -310,6 +385,7 @@ def stage_step(cfg, params, batch, frozen_layers, trainable_layers, train_embedd
     full_backprop the backward runs through every layer and the trainable slice is
     taken afterwards, which is the plain definition; without it the backward stops at
     the lowest trainable layer, which by the chain rule yields the same slice.
+    `drop` (a Dropout, or None) switches dropout on in frozen and trainable layers alike.
     """
     if trainable_layers < 1 or frozen_layers < 0 or frozen_layers + trainable_layers > cfg.n_layers:
         raise ValueError("bad layer split")
@@ -317,7 +393,8 @@ def stage_step(cfg, params, batch, frozen_layers, trainable_layers, train_embedd
         raise ValueError("embeddings train only when nothing is frozen")
     n = frozen_layers + trainable_layers
     keep_from = 0 if full_backprop else frozen_layers
-    loss, cache = forward(cfg, params, batch, n_layers=n, ops=ops, keep_from=keep_from, prefix_at=frozen_layers)
+    loss, cache = forward(cfg, params, batch, n_layers=n, ops=ops, keep_from=keep_from, prefix_at=frozen_layers,
+                          drop=drop)
     if full_backprop:
         g_all = backward(cfg, cache, ops=ops, stop_layer=0, with_embeddings=True)
     else:
