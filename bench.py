@@ -29,9 +29,11 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU, dense
 PEAK_HBM_GBS = 8000.0
 
 
-def run_steps(model, cbatches, f, k, emb, opt, n, stamps=None):
+def run_steps(model, cbatches, f, k, emb, opt, n, stamps=None, dropout=0.0):
     loss = None
     for i in range(n):
+        if dropout > 0.0:
+            model.mslt_set_dropout(dropout, 20201127, i)    # a new step number: new masks
         # one call = stage step + optimizer update (the same work as mslt_stage_step + mslt_apply_update);
         # it returns once the loss is on the host, i.e. after the step's kernels (the update may still run)
         loss = model.mslt_train_step(f, k, emb, cbatches[i % len(cbatches)], opt)
@@ -40,13 +42,15 @@ def run_steps(model, cbatches, f, k, emb, opt, n, stamps=None):
     return loss
 
 
-def time_steps(torch, model, cbatches, f, k, emb, opt, steps, warmup):
-    run_steps(model, cbatches, f, k, emb, opt, warmup)
+def time_steps(torch, model, cbatches, f, k, emb, opt, steps, warmup, dropout=0.0):
+    run_steps(model, cbatches, f, k, emb, opt, warmup, dropout=dropout)
     model.mslt_sync()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     stamps = [t0]
-    loss = run_steps(model, cbatches, f, k, emb, opt, steps, stamps)
+    loss = run_steps(model, cbatches, f, k, emb, opt, steps, stamps, dropout=dropout)
+    if dropout > 0.0:
+        model.mslt_set_dropout(0.0, 0, 0)
     model.mslt_sync()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -237,12 +241,15 @@ def main():
         n_cmp = max(5, min(args.steps, 20))
         sec_stage, _ = time_steps(torch, m12, cb12, 9, 3, False, opt, n_cmp, 3)
         sec_full, _ = time_steps(torch, m12, cb12, 0, 12, True, opt, n_cmp, 3)
+        # the same final-stage step with BERT's dropout (0.1 at the four sites) switched on
+        sec_drop, _ = time_steps(torch, m12, cb12, 9, 3, False, opt, n_cmp, 3, dropout=0.1)
         out["final_stage_vs_full"] = {"workload": "BERT-Base 12 layers, batch 64 x seq 128",
                                       "mslt_9_frozen_3_trainable_ms": round(sec_stage * 1e3, 4),
                                       "full_12_trainable_ms": round(sec_full * 1e3, 4),
                                       "mslt_tokens_per_s": round(tokens / sec_stage, 1),
                                       "full_tokens_per_s": round(tokens / sec_full, 1),
-                                      "speedup": round(sec_full / sec_stage, 3)}
+                                      "speedup": round(sec_full / sec_stage, 3),
+                                      "mslt_with_dropout_0.1_ms": round(sec_drop * 1e3, 4)}
         m12.close()
 
     if not args.no_cpu_baseline:

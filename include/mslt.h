@@ -153,6 +153,19 @@ int mslt_apply_update(mslt_model* m, const mslt_opt* opt);
 int mslt_train_step(mslt_model* m, int frozen_layers, int trainable_layers, int train_embeddings,
                     const mslt_batch* batch, const mslt_opt* opt, float* loss_out);
 
+/* Dropout for the steps that follow ("all other settings are the same as BERT", Section 4.1:
+ * probability 0.1 on the embedding output, the attention probabilities, the attention output and
+ * the feed-forward output, in frozen and trainable layers alike).  p in [0, 1); p = 0 (the state
+ * after mslt_init_model) switches it off.  The keep decisions are counter-based and reproducible:
+ * element e (C-order index in the dropped tensor) of site s (0 embedding [T,H], 1 attention
+ * probabilities [B,heads,S,S], 2 attention output [T,H], 3 feed-forward output [T,H]) of layer l is
+ * kept iff bits 16*(e%4) .. +15 of mix(key + (e/4) * 0x9E3779B97F4A7C15) are >= round(p * 65536),
+ * where mix is the SplitMix64 output function and key = mix(seed ^ mix(((step << 20) | (l << 4) | s)
+ * + 0x9E3779B97F4A7C15)); kept values are scaled by 1 / (1 - p).  The caller advances `step`
+ * (below 2^44) from one training step to the next; the same (seed, step) repeats the same masks.
+ * The hidden size must be a multiple of 4. */
+int mslt_set_dropout(mslt_model* m, float p, uint64_t seed, uint64_t step);
+
 /* Predicted positions (ascending flat index b*seq+s) and their labels as found by the last
  * step, to HOST arrays of at least max_predictions entries; *m_out = their number.  Blocks. */
 int mslt_debug_masked(const mslt_model* m, int32_t* pos_out, int32_t* label_out, int* m_out);

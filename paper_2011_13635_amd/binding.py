@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libmslt.so")
 EXPORTS = [
     "mslt_query_sizes", "mslt_init_model", "mslt_tensor_table", "mslt_load_params", "mslt_get_params",
     "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_train_step",
-    "mslt_debug_masked",
+    "mslt_set_dropout", "mslt_debug_masked",
     "mslt_debug_prefix_output", "mslt_grow", "mslt_sync", "mslt_destroy", "mslt_last_error",
     "mslt_profile_enable", "mslt_profile_read",
 ]
@@ -80,6 +80,7 @@ def load_library():
     lib.mslt_get_grads.argtypes = [vp, vp, sz]
     lib.mslt_apply_update.argtypes = [vp, P(Opt)]
     lib.mslt_train_step.argtypes = [vp, C.c_int, C.c_int, C.c_int, P(Batch), P(Opt), P(C.c_float)]
+    lib.mslt_set_dropout.argtypes = [vp, C.c_float, C.c_uint64, C.c_uint64]
     lib.mslt_debug_masked.argtypes = [vp, vp, vp, P(C.c_int)]
     lib.mslt_debug_prefix_output.argtypes = [vp, vp, sz]
     lib.mslt_grow.argtypes = [vp, C.c_int, C.c_int]
@@ -197,6 +198,9 @@ class Model:
         rc = _check(self.lib.mslt_train_step(self.handle, frozen_layers, trainable_layers, int(train_embeddings),
                                              C.byref(cbatch), C.byref(opt), C.byref(loss)), allow)
         return loss.value if rc == 0 else rc
+
+    def mslt_set_dropout(self, p: float, seed: int, step: int):
+        _check(self.lib.mslt_set_dropout(self.handle, p, seed, step))
 
     def mslt_debug_masked(self):
         cap = self.cfg.max_predictions or self.cfg.max_batch * self.cfg.max_seq

@@ -120,7 +120,7 @@ __device__ __forceinline__ void store_acc_T(bf16* __restrict__ out, size_t ld, i
 // ---- forward --------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
                                                        float* __restrict__ lse, const int32_t* __restrict__ am, int S,
-                                                       int nh, float scale, float mask_bias) {
+                                                       int nh, float scale, float mask_bias, DropSpec drop) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[TILE * DH];
   __shared__ __attribute__((aligned(16))) bf16 Vt[DH * TLD];
   __shared__ __attribute__((aligned(16))) float bias[TILE];
@@ -177,6 +177,17 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ 
       }
     l_run = l_run * alpha + psum;
     m_run = m_new;
+    if (drop.thr) {   // the row sum above is of the undropped probabilities; the product below uses the kept ones
+      const uint64_t rowbase = (((uint64_t)b * nh + h) * S + q) * S + (uint64_t)kt * TILE;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint64_t r = drop_quad(drop, (rowbase + kb * 32 + 8 * g + 4 * half) >> 2);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) s[kb][4 * g + j] *= drop_field(drop, r, j);
+        }
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       o0[r] *= alpha;
@@ -204,7 +215,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
                                                          const bf16* __restrict__ dctx, const float* __restrict__ lse,
                                                          float* __restrict__ delta, bf16* __restrict__ dqkv,
                                                          const int32_t* __restrict__ am, int S, int nh, float scale,
-                                                         float mask_bias) {
+                                                         float mask_bias, DropSpec drop) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[TILE * DH];
   __shared__ __attribute__((aligned(16))) bf16 Vs[TILE * DH];
   __shared__ __attribute__((aligned(16))) bf16 Kt[DH * TLD];
@@ -216,6 +227,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
   const bf16* base = qkv + (size_t)b * S * ld + h * DH;
   const int q = qt * TILE + wave * 32 + n;
   const size_t tok = (size_t)b * S + q;
+  const uint64_t rowbase = (((uint64_t)b * nh + h) * S + q) * S;   // element index of P[b, h, q, 0]
 
   bf16x8_t qf[4], gf[4];
   float dl = 0.f;
@@ -252,10 +264,16 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
       for (int g = 0; g < 4; ++g) {
         float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
         float bv[4] = {bb.x, bb.y, bb.z, bb.w};
+        float kf4[4] = {1.f, 1.f, 1.f, 1.f};
+        if (drop.thr) {
+          const uint64_t r = drop_quad(drop, (rowbase + (uint64_t)kt * TILE + kb * 32 + 8 * g + 4 * half) >> 2);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) kf4[j] = drop_field(drop, r, j);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float p = __expf(s[4 * g + j] * scale + bv[j] - l);
-          s[4 * g + j] = p * (dp[4 * g + j] - dl);   // dS^T
+          s[4 * g + j] = p * (dp[4 * g + j] * kf4[j] - dl);   // dS^T (dP passes through the dropout mask)
         }
       }
 #pragma unroll
@@ -276,7 +294,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict
                                                           const float* __restrict__ lse,
                                                           const float* __restrict__ delta, bf16* __restrict__ dqkv,
                                                           const int32_t* __restrict__ am, int S, int nh, float scale,
-                                                          float mask_bias) {
+                                                          float mask_bias, DropSpec drop) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_kv[];   // KV_LDS_BYTES
   bf16* Qs = reinterpret_cast<bf16*>(smem_kv);
   bf16* Gs = Qs + TILE * DH;
@@ -290,6 +308,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict
   const size_t ld = 3 * (size_t)H;
   const bf16* base = qkv + (size_t)b * S * ld + h * DH;
   const int key = kt * TILE + wave * 32 + n;  // this lane's key
+  const uint64_t headbase = ((uint64_t)b * nh + h) * S;          // row index of P[b, h, 0, :]
 
   bf16x8_t kf[4], vf[4];
 #pragma unroll
@@ -329,8 +348,10 @@ __global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float p = __expf(s[4 * g + j] * scale + kbias - lv[j]);
-          s[4 * g + j] = p;                                   // P
-          dp[4 * g + j] = p * (dp[4 * g + j] - dv[j]);        // dS
+          float kf1 = 1.f;
+          if (drop.thr) kf1 = drop_factor(drop, (headbase + (uint64_t)qt * TILE + qb * 32 + 8 * g + 4 * half + j) * S + key);
+          s[4 * g + j] = p * kf1;                                   // dropped P (for dV)
+          dp[4 * g + j] = p * (dp[4 * g + j] * kf1 - dv[j]);        // dS
         }
       }
 #pragma unroll
@@ -362,7 +383,7 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
                                                            const bf16* __restrict__ dctx,
                                                            const float* __restrict__ lse, bf16* __restrict__ dqkv,
                                                            const int32_t* __restrict__ am, int nh, float scale,
-                                                           float mask_bias) {
+                                                           float mask_bias, DropSpec drop) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_one[];   // ONE_LDS_BYTES
   bf16* Ks = reinterpret_cast<bf16*>(smem_one);
   bf16* Vs = Ks + TILE * DH;
@@ -416,6 +437,7 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
   if (wave < 4) {
     // query side: lane owns query q, registers run over keys
     const int q = wave * 32 + n;
+    const uint64_t rowbase = (((uint64_t)b * nh + h) * S + q) * S;
     bf16x8_t qf[4], gf[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -436,10 +458,16 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
       for (int g = 0; g < 4; ++g) {
         float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
         float bv[4] = {bb.x, bb.y, bb.z, bb.w};
+        float kf4[4] = {1.f, 1.f, 1.f, 1.f};
+        if (drop.thr) {
+          const uint64_t r = drop_quad(drop, (rowbase + kb * 32 + 8 * g + 4 * half) >> 2);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) kf4[j] = drop_field(drop, r, j);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float p = __expf(s[4 * g + j] * scale + bv[j] - l);
-          s[4 * g + j] = p * (dp[4 * g + j] - dl);   // dS^T
+          s[4 * g + j] = p * (dp[4 * g + j] * kf4[j] - dl);   // dS^T (dP passes through the dropout mask)
         }
       }
 #pragma unroll
@@ -456,6 +484,7 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
     // key side: lane owns a key, registers run over queries
     const int w = wave - 4;
     const int key = w * 32 + n;
+    const uint64_t headbase = ((uint64_t)b * nh + h) * S;
     bf16x8_t kf[4], vf[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -480,8 +509,10 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float p = __expf(s[4 * g + j] * scale + kbias - lv[j]);
-          s[4 * g + j] = p;                                   // P
-          dp[4 * g + j] = p * (dp[4 * g + j] - dv[j]);        // dS
+          float kf1 = 1.f;
+          if (drop.thr) kf1 = drop_factor(drop, (headbase + qb * 32 + 8 * g + 4 * half + j) * S + key);
+          s[4 * g + j] = p * kf1;                                   // dropped P (for dV)
+          dp[4 * g + j] = p * (dp[4 * g + j] * kf1 - dv[j]);        // dS
         }
       }
 #pragma unroll
@@ -509,7 +540,7 @@ hipError_t attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
   if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
   dim3 grid(a.S / TILE, a.nh, a.B);
   k_attn_fwd_mfma<<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
-                                             1.0f / sqrtf((float)a.dh), a.mask_bias);
+                                             1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
   return hipGetLastError();
 }
 
@@ -527,11 +558,11 @@ hipError_t attention_bwd_mfma(const AttnBwdDesc& a, hipStream_t s) {
     }
     k_attn_bwd_one_tile<<<dim3(a.nh, a.B), dim3(512), ONE_LDS_BYTES, s>>>(
         (const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse, (bf16*)a.dqkv, a.attn_mask, a.nh, scale,
-        a.mask_bias);
+        a.mask_bias, a.drop);
     return hipGetLastError();
   }
   k_attn_bwd_q_mfma<<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse,
-                                               a.delta, (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale, a.mask_bias);
+                                               a.delta, (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale, a.mask_bias, a.drop);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   static bool attr_set = false;
@@ -542,7 +573,7 @@ hipError_t attention_bwd_mfma(const AttnBwdDesc& a, hipStream_t s) {
     attr_set = true;
   }
   k_attn_bwd_kv_mfma<<<grid, dim3(256), KV_LDS_BYTES, s>>>((const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.delta, (bf16*)a.dqkv,
-                                                a.attn_mask, a.S, a.nh, scale, a.mask_bias);
+                                                a.attn_mask, a.S, a.nh, scale, a.mask_bias, a.drop);
   return hipGetLastError();
 }
 

@@ -10,7 +10,8 @@ namespace mslt {
 template <typename AT>
 __global__ void __launch_bounds__(64) k_attn_fwd_simple(const AT* __restrict__ qkv, AT* __restrict__ ctx,
                                                         float* __restrict__ lse, const int32_t* __restrict__ am, int S,
-                                                        int nh, int dh, float scale, float mask_bias) {
+                                                        int nh, int dh, float scale, float mask_bias,
+                                                        DropSpec drop) {
   extern __shared__ float sm[];  // q[dh] | p[S]
   float* q = sm;
   float* p = sm + dh;
@@ -36,6 +37,10 @@ __global__ void __launch_bounds__(64) k_attn_fwd_simple(const AT* __restrict__ q
     se += e;
   }
   se = wave_sum(se);
+  if (drop.thr) {   // the normaliser is that of the undropped probabilities
+    const uint64_t rowbase = (((uint64_t)b * nh + h) * S + i) * S;
+    for (int j = lane; j < S; j += 64) p[j] *= drop_factor(drop, rowbase + j);
+  }
   __syncthreads();
   float inv = 1.0f / se;
   for (int d = lane; d < dh; d += 64) {
@@ -52,7 +57,7 @@ __global__ void __launch_bounds__(64) k_attn_bwd_q(const AT* __restrict__ qkv, c
                                                    const AT* __restrict__ dctx, const float* __restrict__ lse,
                                                    float* __restrict__ delta, AT* __restrict__ dqkv,
                                                    const int32_t* __restrict__ am, int S, int nh, int dh, float scale,
-                                                   float mask_bias) {
+                                                   float mask_bias, DropSpec drop) {
   extern __shared__ float sm[];  // q[dh] | dc[dh] | da[S]
   float* q = sm;
   float* dc = sm + dh;
@@ -80,6 +85,7 @@ __global__ void __launch_bounds__(64) k_attn_bwd_q(const AT* __restrict__ qkv, c
       dp += dc[d] * ldf(vr + d);
     }
     float pij = __expf(s * scale + (am[b * S + j] ? 0.f : mask_bias) - l);
+    if (drop.thr) dp *= drop_factor(drop, (((uint64_t)b * nh + h) * S + i) * S + j);
     da[j] = pij * (dp - dl);
   }
   __syncthreads();
@@ -96,7 +102,7 @@ template <typename AT>
 __global__ void __launch_bounds__(64) k_attn_bwd_kv(const AT* __restrict__ qkv, const AT* __restrict__ dctx,
                                                     const float* __restrict__ lse, const float* __restrict__ delta,
                                                     AT* __restrict__ dqkv, const int32_t* __restrict__ am, int S, int nh,
-                                                    int dh, float scale, float mask_bias) {
+                                                    int dh, float scale, float mask_bias, DropSpec drop) {
   extern __shared__ float sm[];  // k[dh] | v[dh] | p[S] | da[S]
   float* k = sm;
   float* v = sm + dh;
@@ -121,8 +127,9 @@ __global__ void __launch_bounds__(64) k_attn_bwd_kv(const AT* __restrict__ qkv, 
     }
     size_t li = ((size_t)b * nh + h) * S + i;
     float pij = __expf(s * scale + bias - lse[li]);
-    p[i] = pij;
-    da[i] = pij * (dp - delta[li]);
+    float kf = drop.thr ? drop_factor(drop, (((uint64_t)b * nh + h) * S + i) * S + j) : 1.f;
+    p[i] = pij * kf;                      // dropped probability (for dV)
+    da[i] = pij * (dp * kf - delta[li]);
   }
   __syncthreads();
   size_t row = (size_t)b * S + j;
@@ -142,7 +149,7 @@ static hipError_t fwd_t(const AttnDesc& a, hipStream_t s) {
   dim3 grid(a.S, a.nh, a.B);
   size_t sh = (size_t)(a.dh + a.S) * sizeof(float);
   k_attn_fwd_simple<AT><<<grid, dim3(64), sh, s>>>((const AT*)a.qkv, (AT*)a.ctx, a.lse, a.attn_mask, a.S, a.nh, a.dh,
-                                                   1.0f / sqrtf((float)a.dh), a.mask_bias);
+                                                   1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
   return hipGetLastError();
 }
 hipError_t attention_fwd_simple(int dtype, const AttnDesc& a, hipStream_t s) {
@@ -155,12 +162,12 @@ static hipError_t bwd_t(const AttnBwdDesc& a, hipStream_t s) {
   float scale = 1.0f / sqrtf((float)a.dh);
   k_attn_bwd_q<AT><<<grid, dim3(64), (size_t)(2 * a.dh + a.S) * sizeof(float), s>>>(
       (const AT*)a.qkv, (const AT*)a.ctx, (const AT*)a.dctx, a.lse, a.delta, (AT*)a.dqkv, a.attn_mask, a.S, a.nh, a.dh,
-      scale, a.mask_bias);
+      scale, a.mask_bias, a.drop);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   k_attn_bwd_kv<AT><<<grid, dim3(64), (size_t)(2 * a.dh + 2 * a.S) * sizeof(float), s>>>(
       (const AT*)a.qkv, (const AT*)a.dctx, a.lse, a.delta, (AT*)a.dqkv, a.attn_mask, a.S, a.nh, a.dh, scale,
-      a.mask_bias);
+      a.mask_bias, a.drop);
   return hipGetLastError();
 }
 hipError_t attention_bwd_simple(int dtype, const AttnBwdDesc& a, hipStream_t s) {

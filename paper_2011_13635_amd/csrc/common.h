@@ -45,6 +45,36 @@ __device__ inline float ld_dgelu(const bf16* p) { return dec_dgelu(p->x); }
 __device__ inline void st_dgelu(float* p, float d) { *p = d; }
 __device__ inline void st_dgelu(bf16* p, float d) { p->x = (uint16_t)enc_dgelu(d); }
 
+// ---- dropout keep decisions ------------------------------------------------------------------
+// Counter-based, so that they can be recomputed anywhere (forward, backward, a checker): the
+// SplitMix64 output function (Steele, Lea, Flood 2014) of key + quad * GOLDEN decides the four
+// elements 4*quad .. 4*quad+3 of a tensor (C-order element index) with its four 16-bit fields,
+// lowest field first: an element is kept iff its field >= thr = round(p * 65536), and kept values
+// are scaled by 1 / (1 - p).  The key mixes the caller's seed with (step, layer, site).
+constexpr uint64_t DROP_GOLDEN = 0x9E3779B97F4A7C15ull;
+enum DropSite { SITE_EMBEDDING = 0, SITE_ATTN_PROBS = 1, SITE_ATTN_OUT = 2, SITE_FFN_OUT = 3 };
+struct DropSpec {
+  uint64_t key = 0;
+  uint32_t thr = 0;     // 0: dropout off
+  float scale = 1.f;
+};
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+inline uint64_t drop_key(uint64_t seed, uint64_t step, int layer, int site) {
+  uint64_t stream = (step << 20) | ((uint64_t)layer << 4) | (uint64_t)site;
+  return mix64(seed ^ mix64(stream + DROP_GOLDEN));
+}
+__device__ inline uint64_t drop_quad(const DropSpec& d, uint64_t quad) { return mix64(d.key + quad * DROP_GOLDEN); }
+__device__ inline float drop_field(const DropSpec& d, uint64_t r, int field) {
+  return (uint32_t)((r >> (16 * field)) & 0xffffu) >= d.thr ? d.scale : 0.f;
+}
+__device__ inline float drop_factor(const DropSpec& d, uint64_t elem) {
+  return drop_field(d, drop_quad(d, elem >> 2), (int)(elem & 3));
+}
+
 // ---- wavefront (64 lanes) reductions --------------------------------------------------------
 __device__ inline float wave_sum(float v) {
 #pragma unroll
@@ -99,6 +129,8 @@ struct Epilogue {
   void* out2 = nullptr;     // EPI_GELU: GELU'(pre-activation) for the backward pass (st_dgelu format), may be null
   const void* aux = nullptr;  // EPI_MUL: the stored GELU derivative D[m,n] (ld_dgelu format); EPI_ADD: addend R[m,n]
   int ldaux = 0;
+  DropSpec drop;            // dropout of (acc + bias) before the activation / addend; element index m * drop_ld + n
+  int drop_ld = 0;          // logical row width of the dropped tensor (a multiple of 4)
 };
 
 struct GemmDesc {
@@ -131,6 +163,7 @@ struct AttnDesc {
   const int32_t* attn_mask;  // [B, S]
   int B, S, nh, dh;
   float mask_bias;
+  DropSpec drop;      // dropout of the attention probabilities; element index ((b*nh + h)*S + q)*S + key
 };
 struct AttnBwdDesc {
   const void* qkv;
@@ -142,6 +175,7 @@ struct AttnBwdDesc {
   const int32_t* attn_mask;
   int B, S, nh, dh;
   float mask_bias;
+  DropSpec drop;      // as in AttnDesc
 };
 hipError_t attention_fwd_simple(int dtype, const AttnDesc& d, hipStream_t s);
 hipError_t attention_bwd_simple(int dtype, const AttnBwdDesc& d, hipStream_t s);
@@ -168,14 +202,25 @@ struct LnStash {
 };
 hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S, const float* word, const float* pos,
                         const float* type, const float* g, const float* b, float eps, void* out, LnStash st, int T,
-                        int H, int vocab, int type_vocab, hipStream_t s);
+                        int H, int vocab, int type_vocab, const DropSpec& drop, hipStream_t s);
 // out = LN(a + r) (r may be null)
 hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, const float* b, float eps, void* out,
                       LnStash st, int rows, int H, hipStream_t s);
-// dz from dy, xhat, rstd, gamma; dgamma, dbeta and (if dzsum != null) the column sums of dz via
-// partials in scratch (ln_bwd_scratch_floats(rows, H) floats)
+// Dropout around a LayerNorm in the backward pass.  in: the LayerNorm output was dropped (embedding
+// block), so dy is multiplied by the keep factors first.  out: the LayerNorm input was residual +
+// dropout(y); then dzm receives dz times the keep factors (the gradient of y) next to dz (the
+// gradient of the residual), and the column sums are those of dzm.  rowmap (or null): token row of
+// each of the first n_mapped rows, for the element index of compacted rows.
+struct LnBwdDrop {
+  DropSpec in, out;
+  void* dzm = nullptr;
+  const int32_t* rowmap = nullptr;
+  int n_mapped = 0;
+};
+// dz from dy, xhat, rstd, gamma; dgamma, dbeta and (if dzsum != null) the column sums of dz (of dzm
+// with output dropout) via partials in scratch (ln_bwd_scratch_floats(rows, H) floats)
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
-                  float* db, float* dzsum, float* scratch, int rows, int H, hipStream_t s);
+                  float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s);
 // column sums of Y[rows, N] (leading dimension ld) into out[N]; scratch holds ceil(rows/64)*N floats
 hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s);
 size_t colsum_scratch_floats(int rows, int N);

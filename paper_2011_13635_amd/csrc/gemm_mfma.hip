@@ -186,6 +186,15 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
                                           const uint4& raw) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[i] += bias[i];
+  if (e.drop.thr) {
+    const uint64_t quad = ((uint64_t)m * e.drop_ld + n) >> 2;     // n and drop_ld are multiples of 4
+    const uint64_t r0 = drop_quad(e.drop, quad), r1 = drop_quad(e.drop, quad + 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[i] *= drop_field(e.drop, r0, i);
+      v[4 + i] *= drop_field(e.drop, r1, i);
+    }
+  }
   size_t o = (size_t)m * e.ldo + n;
   if (e.act == EPI_GELU) {
     float d[8];
@@ -422,6 +431,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
   if (d.M % 128 || d.N % BN || d.K % BK) return false;
   if (d.lda % 8 || d.ldb % 8 || d.epi.ldo % 8) return false;
   if ((d.epi.act == EPI_MUL || d.epi.act == EPI_ADD) && d.epi.ldaux % 8) return false;
+  if (d.epi.drop.thr && d.epi.drop_ld % 4) return false;
   auto al = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
   if (!al(d.A) || !al(d.B) || !al(d.epi.out) || !al(d.epi.out2) || !al(d.epi.aux) || !al(d.epi.bias)) return false;
   return true;

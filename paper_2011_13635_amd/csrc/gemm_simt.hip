@@ -10,6 +10,7 @@ template <typename AT>
 __device__ inline void epilogue_store(const Epilogue& e, int m, int n, float acc) {
   float v = acc;
   if (e.bias) v += e.bias[n];
+  if (e.drop.thr) v *= drop_factor(e.drop, (uint64_t)m * e.drop_ld + n);
   size_t o = (size_t)m * e.ldo + n;
   if (e.act == EPI_GELU) {
     float g;

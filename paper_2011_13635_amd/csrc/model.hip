@@ -98,9 +98,15 @@ struct mslt_model {
   hipStream_t side; hipEvent_t ev_fork, ev_join; bool side_forked;
   // the gradient buffers the side stream reads exist twice and alternate by layer, so a layer's
   // side work only has to finish before the layer two below starts
-  struct GradSet { void *d_d, *d_u, *d_z1, *d_qkv; } gset[2];
+  struct GradSet { void *d_d, *d_u, *d_z1, *d_qkv, *d_dm, *d_z1m; } gset[2];   // d_dm, d_z1m: dropout-masked dz2, dz1
   hipEvent_t ev_set[2]; bool set_busy[2];
   hipEvent_t ev_scan;      // batch check done and its verdict copied to the host
+  // dropout (off unless mslt_set_dropout was called with p > 0)
+  uint64_t drop_seed = 0, drop_step = 0;
+  uint32_t drop_thr = 0;
+  float drop_scale = 1.f;
+  void *d_dm, *d_z1m;      // masked dz2 / dz1 of the current layer's set
+  void *c_dz2m, *c_dz1m;   // the same for the compacted top layer
   float *splitk2, *red2;
   int32_t *e_rank, *e_cnt, *e_start, *e_order, *e_blockcnt;
   float* e_partial;                    // [Tp, H] run sums of the embedding backward
@@ -238,8 +244,10 @@ static size_t carve(mslt_model* m, char* base) {
   for (int i = 0; i < 2; ++i) {
     m->gset[i].d_d = b.take<void>(TH); m->gset[i].d_u = b.take<void>(TF);
     m->gset[i].d_z1 = b.take<void>(TH); m->gset[i].d_qkv = b.take<void>(3 * TH);
+    m->gset[i].d_dm = b.take<void>(TH); m->gset[i].d_z1m = b.take<void>(TH);
   }
   m->d_d = m->gset[0].d_d; m->d_u = m->gset[0].d_u; m->d_z1 = m->gset[0].d_z1; m->d_qkv = m->gset[0].d_qkv;
+  m->d_dm = m->gset[0].d_dm; m->d_z1m = m->gset[0].d_z1m;
   m->d_x1 = b.take<void>(TH); m->d_c = b.take<void>(TH);
   m->d_z0 = b.take<void>(TH);
   m->delta = b.take<float>(lse_bytes);
@@ -249,6 +257,7 @@ static size_t carve(mslt_model* m, char* base) {
   m->hm = b.take<void>(MH); m->dz = b.take<void>(Mp * Vp * e); m->d_hm = b.take<void>(MH); m->d_gt = b.take<void>(MH);
   m->d_ut = b.take<void>(MH); m->d_xm = b.take<void>(MH);
   m->c_g = b.take<void>(Mp * F * e); m->c_u = b.take<void>(Mp * F * e); m->c_du = b.take<void>(Mp * F * e);
+  m->c_dz2m = b.take<void>(MH); m->c_dz1m = b.take<void>(MH);
   m->rstd_t = b.take<float>(Mp * 4); m->logits = b.take<float>(Mp * Vp * 4); m->row_loss = b.take<float>(Mp * 4);
   m->lse_t = b.take<float>(Mp * 4); m->loss = b.take<float>(64);
   // reduction scratch: the largest of LayerNorm-backward partials, column-sum partials, token-type partials
@@ -507,6 +516,7 @@ static int layer_backward_begin(mslt_model* m, int l) {
     m->set_busy[p] = false;
   }
   m->d_d = m->gset[p].d_d; m->d_u = m->gset[p].d_u; m->d_z1 = m->gset[p].d_z1; m->d_qkv = m->gset[p].d_qkv;
+  m->d_dm = m->gset[p].d_dm; m->d_z1m = m->gset[p].d_z1m;
   return MSLT_OK;
 }
 static int layer_backward_end(mslt_model* m, int l) {
@@ -538,10 +548,23 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false,
     if (rc__) return rc__; \
   } while (0)
 
-// Y[rows,N] = X[rows,K] W[N,K]^T + bias, optional GELU (gelu_grad_out then receives GELU' of the pre-activation)
+// keep decisions of one dropout site of one layer in the current step (thr 0 = dropout off)
+static DropSpec dspec(const mslt_model* m, int layer, int site) {
+  DropSpec d;
+  if (m->drop_thr) {
+    d.key = drop_key(m->drop_seed, m->drop_step, layer, site);
+    d.thr = m->drop_thr;
+    d.scale = m->drop_scale;
+  }
+  return d;
+}
+
+// Y[rows,N] = X[rows,K] W[N,K]^T + bias, optional GELU (gelu_grad_out then receives GELU' of the pre-activation),
+// optional dropout of the result
 static int linear_fwd(mslt_model* m, const void* X, int rows, int K, const void* W, int N, const float* bias, void* Y,
-                      int out_f32, int ldo, int act, void* gelu_grad_out) {
+                      int out_f32, int ldo, int act, void* gelu_grad_out, const DropSpec& drop = DropSpec()) {
   GemmDesc d;
+  d.epi.drop = drop; d.epi.drop_ld = N;
   d.A = X; d.lda = K; d.a_kcontig = 1; d.M = rows;
   d.B = W; d.ldb = K; d.b_kcontig = 1; d.N = N; d.K = K;
   d.epi.out = Y; d.epi.ldo = ldo; d.epi.out_f32 = out_f32; d.epi.bias = bias; d.epi.act = act; d.epi.out2 = gelu_grad_out;
@@ -583,7 +606,8 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
   void* x1 = st ? st->x1 : m->s_x1;
   void* g = st ? st->g : m->s_g;
   RC(linear_fwd(m, Xin, Tr, H, Wg(m, t_layer(l, L_WQ)), 3 * H, Wf(m, t_layer(l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr));
-  AttnDesc a{qkv, ctx, st ? st->lse : nullptr, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh, m->cfg.mask_bias};
+  AttnDesc a{qkv, ctx, st ? st->lse : nullptr, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh, m->cfg.mask_bias,
+             dspec(m, l, SITE_ATTN_PROBS)};
   {
     const double TS = (double)bt->batch * bt->seq;
     ProfScope ps(m, PC_ATTN_FWD, 4.0 * TS * bt->seq * H, 4.0 * TS * H * m->esz);
@@ -592,12 +616,14 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
     else
       HIP_TRY(attention_fwd_simple(m->dtype, a, m->stream));
   }
-  RC(linear_fwd(m, ctx, Tr, H, Wg(m, t_layer(l, L_WO)), H, Wf(m, t_layer(l, L_BO)), m->s_y, 0, H, EPI_NONE, nullptr));
+  RC(linear_fwd(m, ctx, Tr, H, Wg(m, t_layer(l, L_WO)), H, Wf(m, t_layer(l, L_BO)), m->s_y, 0, H, EPI_NONE, nullptr,
+                dspec(m, l, SITE_ATTN_OUT)));
   LnStash s1, s2;
   if (st) { s1.xhat = st->xhat1; s1.rstd = st->rstd1; s2.xhat = st->xhat2; s2.rstd = st->rstd2; }
   RC(ln_forward(m, m->s_y, Xin, Wf(m, t_layer(l, L_LN1G)), Wf(m, t_layer(l, L_LN1B)), x1, s1, Tr));
   RC(linear_fwd(m, x1, Tr, H, Wg(m, t_layer(l, L_W1)), F, Wf(m, t_layer(l, L_B1)), g, 0, F, EPI_GELU, st ? st->u : nullptr));
-  RC(linear_fwd(m, g, Tr, F, Wg(m, t_layer(l, L_W2)), H, Wf(m, t_layer(l, L_B2)), m->s_y, 0, H, EPI_NONE, nullptr));
+  RC(linear_fwd(m, g, Tr, F, Wg(m, t_layer(l, L_W2)), H, Wf(m, t_layer(l, L_B2)), m->s_y, 0, H, EPI_NONE, nullptr,
+                dspec(m, l, SITE_FFN_OUT)));
   RC(ln_forward(m, m->s_y, x1, Wf(m, t_layer(l, L_LN2G)), Wf(m, t_layer(l, L_LN2B)), Xout, s2, Tr));
   return MSLT_OK;
 }
@@ -611,9 +637,9 @@ static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, flo
 }
 // dzsum (may be null): column sums of dz = bias gradient of the linear layer feeding this LayerNorm
 static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz,
-                       float* dg, float* db, float* dzsum, int rows) {
-  ProfScope ps(m, PC_LN_BWD, 0.0, 3.0 * rows * m->H * m->esz);
-  HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, m->stream));
+                       float* dg, float* db, float* dzsum, int rows, const LnBwdDrop& dd = LnBwdDrop()) {
+  ProfScope ps(m, PC_LN_BWD, 0.0, (dd.out.thr ? 4.0 : 3.0) * rows * m->H * m->esz);
+  HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, dd, m->stream));
   return MSLT_OK;
 }
 
@@ -625,20 +651,30 @@ struct UpperRows {
   const float *rstd2, *rstd1;
   void *dz2, *du, *dx1, *dz1, *dc;               // gradient buffers
   int rows;
+  void *dz2m, *dz1m;                             // dz2, dz1 times the dropout keep factors (used when dropout is on)
+  const int32_t* rowmap;                         // token row of each compacted row, or null
+  int n_mapped;
 };
 static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const UpperRows& r) {
   const int H = m->H, F = m->F, R = r.rows;
+  // With dropout the gradient of a dropped linear output (dy2, dy1) is dz times the keep factors,
+  // while the residual branch takes dz itself; without it they are the same buffer.
+  LnBwdDrop d2, d1;
+  d2.out = dspec(m, l, SITE_FFN_OUT); d2.dzm = r.dz2m; d2.rowmap = r.rowmap; d2.n_mapped = r.n_mapped;
+  d1.out = dspec(m, l, SITE_ATTN_OUT); d1.dzm = r.dz1m; d1.rowmap = r.rowmap; d1.n_mapped = r.n_mapped;
+  const void* dy2 = d2.out.thr ? r.dz2m : r.dz2;
+  const void* dy1 = d1.out.thr ? r.dz1m : r.dz1;
   RC(ln_backward(m, dXout, r.xhat2, r.rstd2, Wf(m, t_layer(l, L_LN2G)), r.dz2, Gf(m, t_layer(l, L_LN2G)),
-                 Gf(m, t_layer(l, L_LN2B)), Gf(m, t_layer(l, L_B2)), R));
-  RC(linear_bwd_weight(m, r.dz2, R, H, H, r.g, F, Gf(m, t_layer(l, L_W2))));
-  RC(linear_bwd_input(m, r.dz2, R, H, H, Wg(m, t_layer(l, L_W2)), F, r.du, EPI_MUL, r.u));
+                 Gf(m, t_layer(l, L_LN2B)), Gf(m, t_layer(l, L_B2)), R, d2));
+  RC(linear_bwd_weight(m, dy2, R, H, H, r.g, F, Gf(m, t_layer(l, L_W2))));
+  RC(linear_bwd_input(m, dy2, R, H, H, Wg(m, t_layer(l, L_W2)), F, r.du, EPI_MUL, r.u));
   RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_layer(l, L_W1))));
   RC(bias_grad(m, r.du, F, R, F, Gf(m, t_layer(l, L_B1))));
   RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_layer(l, L_W1)), H, r.dx1, EPI_ADD, r.dz2));
   RC(ln_backward(m, r.dx1, r.xhat1, r.rstd1, Wf(m, t_layer(l, L_LN1G)), r.dz1, Gf(m, t_layer(l, L_LN1G)),
-                 Gf(m, t_layer(l, L_LN1B)), Gf(m, t_layer(l, L_BO)), R));
-  RC(linear_bwd_weight(m, r.dz1, R, H, H, r.ctx, H, Gf(m, t_layer(l, L_WO))));
-  RC(linear_bwd_input(m, r.dz1, R, H, H, Wg(m, t_layer(l, L_WO)), H, r.dc, EPI_NONE, nullptr));
+                 Gf(m, t_layer(l, L_LN1B)), Gf(m, t_layer(l, L_BO)), R, d1));
+  RC(linear_bwd_weight(m, dy1, R, H, H, r.ctx, H, Gf(m, t_layer(l, L_WO))));
+  RC(linear_bwd_input(m, dy1, R, H, H, Wg(m, t_layer(l, L_WO)), H, r.dc, EPI_NONE, nullptr));
   return MSLT_OK;
 }
 // Attention backward and the QKV projection backward, from dC and dz1 (both [Tr, H], all token rows).
@@ -649,7 +685,7 @@ static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int 
   const LayerStash& st = m->stash[l];
   hipStream_t s = m->stream;
   AttnBwdDesc a{st.qkv, st.ctx, m->d_c, st.lse, m->delta, m->d_qkv, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh,
-                m->cfg.mask_bias};
+                m->cfg.mask_bias, dspec(m, l, SITE_ATTN_PROBS)};
   {
     const double TS = (double)bt->batch * bt->seq;
     ProfScope ps(m, PC_ATTN_BWD, 10.0 * TS * bt->seq * H, 8.0 * TS * H * m->esz);
@@ -670,7 +706,8 @@ static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int
                           void* dXin) {
   const LayerStash& st = m->stash[l];
   RC(layer_backward_begin(m, l));
-  UpperRows r{st.xhat2, st.g, st.u, st.x1, st.xhat1, st.ctx, st.rstd2, st.rstd1, m->d_d, m->d_u, m->d_x1, m->d_z1, m->d_c, Tr};
+  UpperRows r{st.xhat2, st.g, st.u, st.x1, st.xhat1, st.ctx, st.rstd2, st.rstd1, m->d_d, m->d_u, m->d_x1, m->d_z1, m->d_c, Tr,
+              m->d_dm, m->d_z1m, nullptr, 0};
   RC(layer_backward_upper(m, l, dXout, r));
   return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin);
 }
@@ -691,7 +728,7 @@ static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T,
     HIP_TRY(gather_rows_multi(g, 8, m->pos, M, Mr, s));
   }
   UpperRows r{m->xm, m->c_g, m->c_u, m->ut, m->gt, m->xhat_t, m->rstd_t, m->lse_t,
-              m->hm, m->c_du, m->d_hm, m->d_gt, m->d_ut, Mr};
+              m->hm, m->c_du, m->d_hm, m->d_gt, m->d_ut, Mr, m->c_dz2m, m->c_dz1m, m->pos, M};
   RC(layer_backward_upper(m, l, dXm, r));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * ((double)Tr + M) * H * m->esz);
@@ -736,7 +773,8 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   {
     ProfScope ps(m, PC_EMBED, 0.0, (double)T * H * (4.0 + m->esz * (train_emb ? 2.0 : 1.0)));
     HIP_TRY(embed_ln_fwd(m->dtype, bt->input_ids, bt->token_type_ids, S, Wf(m, T_WORD), Wf(m, T_POS), Wf(m, T_TYPE),
-                         Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, m->V, m->cfg.type_vocab, s));
+                         Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, m->V, m->cfg.type_vocab,
+                         dspec(m, 0, SITE_EMBEDDING), s));
   }
   // S2: frozen prefix, forward only, two ping-pong buffers, nothing kept
   const void* x = m->x0;
@@ -807,7 +845,9 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   RC(side_join(m));      // all weight gradients are complete when the step returns
   // S10: embedding backward (first stage / retraining)
   if (train_emb) {
-    RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), nullptr, T));
+    LnBwdDrop de;
+    de.in = dspec(m, 0, SITE_EMBEDDING);
+    RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), nullptr, T, de));
     ProfScope ps(m, PC_EMBED_BWD, 0.0, (double)T * H * (m->esz + 8.0));
     HIP_TRY(embed_bwd(m->dtype, m->d_z0, bt->input_ids, bt->token_type_ids, B, S, H, m->V, m->cfg.type_vocab,
                       Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order, m->e_blockcnt,
@@ -919,6 +959,18 @@ extern "C" int mslt_train_step(mslt_model* m, int f, int k, int train_emb, const
   RC(update_enqueue(m, opt, m->loss));
   m->have_grads = false;
   return stage_step_finish(m, loss_out);
+}
+
+extern "C" int mslt_set_dropout(mslt_model* m, float p, uint64_t seed, uint64_t step) {
+  if (!m) return fail(MSLT_ERR_ARG, "model is null");
+  if (!(p >= 0.f && p < 1.f)) return fail(MSLT_ERR_ARG, "set_dropout: probability %g outside [0, 1)", (double)p);
+  if (step >> 44) return fail(MSLT_ERR_ARG, "set_dropout: step number too large");
+  if (m->H % 4) return fail(MSLT_ERR_ARG, "set_dropout: hidden size must be a multiple of 4");
+  m->drop_thr = (uint32_t)lrintf(p * 65536.0f);
+  m->drop_scale = 1.0f / (1.0f - p);
+  m->drop_seed = seed;
+  m->drop_step = step;
+  return MSLT_OK;
 }
 
 extern "C" int mslt_debug_masked(const mslt_model* m, int32_t* pos_out, int32_t* label_out, int* m_out) {

@@ -24,6 +24,12 @@ __device__ inline float4 load4(const bf16* p) {
 // guarded load-and-wait at a time.
 __device__ inline int ldcol(int c, int H) { return c < H ? c : 0; }
 __device__ inline float4 keep4(bool keep, float4 v) { return keep ? v : make_float4(0.f, 0.f, 0.f, 0.f); }
+// dropout factors of the 4 consecutive elements starting at element index e (a multiple of 4)
+__device__ inline float4 drop4(const DropSpec& d, uint64_t e) {
+  const uint64_t r = drop_quad(d, e >> 2);
+  return make_float4(drop_field(d, r, 0), drop_field(d, r, 1), drop_field(d, r, 2), drop_field(d, r, 3));
+}
+__device__ inline float4 mul4(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
 __device__ inline void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ inline void store4(bf16* p, float4 v) {
   uint2 r;
@@ -157,7 +163,8 @@ hipError_t batch_scan(const int32_t* ids, const int32_t* tt, const int32_t* am, 
 template <typename AT, int NV>
 __device__ inline void ln_row_finish(float4 (&z)[NV], int H, int lane, const float* __restrict__ g,
                                      const float* __restrict__ b, float eps, AT* __restrict__ out,
-                                     AT* __restrict__ xhat, float* __restrict__ rstd_out) {
+                                     AT* __restrict__ xhat, float* __restrict__ rstd_out,
+                                     const DropSpec& drop = DropSpec(), uint64_t drop_base = 0) {
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -190,8 +197,10 @@ __device__ inline void ln_row_finish(float4 (&z)[NV], int H, int lane, const flo
     if (c < H) {
       float4 xh = make_float4(z[i].x * rstd, z[i].y * rstd, z[i].z * rstd, z[i].w * rstd);
       if (xhat != nullptr) store4(xhat + c, xh);
-      store4(out + c, make_float4(xh.x * gg[i].x + bb[i].x, xh.y * gg[i].y + bb[i].y, xh.z * gg[i].z + bb[i].z,
-                                  xh.w * gg[i].w + bb[i].w));
+      float4 y = make_float4(xh.x * gg[i].x + bb[i].x, xh.y * gg[i].y + bb[i].y, xh.z * gg[i].z + bb[i].z,
+                             xh.w * gg[i].w + bb[i].w);
+      if (drop.thr) y = mul4(y, drop4(drop, drop_base + c));     // dropout of the LayerNorm output
+      store4(out + c, y);
     }
   }
 }
@@ -202,7 +211,7 @@ __global__ void __launch_bounds__(256) k_embed_ln(const int32_t* __restrict__ id
                                                   const float* __restrict__ type, const float* __restrict__ g,
                                                   const float* __restrict__ b, float eps, AT* __restrict__ out,
                                                   AT* __restrict__ xhat, float* __restrict__ rstd, int T, int H,
-                                                  int vocab, int type_vocab) {
+                                                  int vocab, int type_vocab, DropSpec drop) {
   int lane = threadIdx.x & 63;
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= T) return;
@@ -219,7 +228,7 @@ __global__ void __launch_bounds__(256) k_embed_ln(const int32_t* __restrict__ id
     z[i] = make_float4(a.x + b2.x + c2.x, a.y + b2.y + c2.y, a.z + b2.z + c2.z, a.w + b2.w + c2.w);
   }
   ln_row_finish<AT, NV>(z, H, lane, g, b, eps, out + (size_t)row * H, xhat ? xhat + (size_t)row * H : nullptr,
-                        rstd ? rstd + row : nullptr);
+                        rstd ? rstd + row : nullptr, drop, (uint64_t)row * H);
 }
 static inline int ln_nv(int H) { return H <= 512 ? 2 : H <= 1024 ? 4 : 8; }
 #define LN_DISPATCH(H, CALL)         \
@@ -230,14 +239,14 @@ static inline int ln_nv(int H) { return H <= 512 ? 2 : H <= 1024 ? 4 : 8; }
   }
 hipError_t embed_ln_fwd(int dtype, const int32_t* ids, const int32_t* tt, int S, const float* word, const float* pos,
                         const float* type, const float* g, const float* b, float eps, void* out, LnStash st, int T,
-                        int H, int vocab, int type_vocab, hipStream_t s) {
+                        int H, int vocab, int type_vocab, const DropSpec& drop, hipStream_t s) {
   dim3 grid((T + 3) / 4), block(256);
   if (dtype == 0) {
     LN_DISPATCH(H, (k_embed_ln<float, NV><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (float*)out,
-                                                                 (float*)st.xhat, st.rstd, T, H, vocab, type_vocab)));
+                                                                 (float*)st.xhat, st.rstd, T, H, vocab, type_vocab, drop)));
   } else {
     LN_DISPATCH(H, (k_embed_ln<bf16, NV><<<grid, block, 0, s>>>(ids, tt, S, word, pos, type, g, b, eps, (bf16*)out,
-                                                                (bf16*)st.xhat, st.rstd, T, H, vocab, type_vocab)));
+                                                                (bf16*)st.xhat, st.rstd, T, H, vocab, type_vocab, drop)));
   }
   return hipGetLastError();
 }
@@ -330,7 +339,7 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
                                                 const float* __restrict__ rstd, const float* __restrict__ g,
                                                 AT* __restrict__ dz, float* __restrict__ part_g,
                                                 float* __restrict__ part_b, float* __restrict__ part_z, int rows,
-                                                int H) {
+                                                int H, LnBwdDrop dd) {
   __shared__ float red[3][256 * NV];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float4 gg[NV], ag[NV], ab[NV], az[NV];
@@ -366,6 +375,8 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
       const bool keep = ok && (i * 64 + lane) * 4 < H;
       d[rr][i] = keep4(keep, d[rr][i]);
       x[rr][i] = keep4(keep, x[rr][i]);
+      // the LayerNorm output went through dropout (embedding block): so does its gradient
+      if (dd.in.thr && keep) d[rr][i] = mul4(d[rr][i], drop4(dd.in, (uint64_t)(row0 + rr) * H + (i * 64 + lane) * 4));
     }
   }
 #pragma unroll
@@ -384,6 +395,10 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
     float m1 = wave_sum(s1) * invH, m2 = wave_sum(s2) * invH;
     int row = row0 + rr;
     if (row < rows) {
+      // the LayerNorm input was residual + dropout(linear output): the linear output's gradient is
+      // dz times the same keep factors (element index by token row: compacted rows go through rowmap)
+      uint64_t tok = (uint64_t)row;
+      if (dd.out.thr && dd.rowmap) tok = row < dd.n_mapped ? (uint64_t)dd.rowmap[row] : 0;
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         int c = (i * 64 + lane) * 4;
@@ -391,8 +406,12 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
           float4 y = d[rr][i], xx = x[rr][i];
           float4 o = make_float4((y.x - m1 - xx.x * m2) * rs[rr], (y.y - m1 - xx.y * m2) * rs[rr],
                                  (y.z - m1 - xx.z * m2) * rs[rr], (y.w - m1 - xx.w * m2) * rs[rr]);
-          az[i].x += o.x; az[i].y += o.y; az[i].z += o.z; az[i].w += o.w;
           store4(dz + (size_t)row * H + c, o);
+          if (dd.out.thr) {
+            o = mul4(o, drop4(dd.out, tok * H + c));
+            store4(reinterpret_cast<AT*>(dd.dzm) + (size_t)row * H + c, o);
+          }
+          az[i].x += o.x; az[i].y += o.y; az[i].z += o.z; az[i].w += o.w;
         }
       }
     }
@@ -427,16 +446,18 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
 }
 template <typename AT>
 static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, const float* g, AT* dz, float* dg, float* db,
-                           float* dzsum, float* scratch, int rows, int H, hipStream_t s) {
+                           float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s) {
+  if (dd.out.thr && dd.dzm == nullptr) return hipErrorInvalidValue;
+  if ((dd.out.thr || dd.in.thr) && H % 4) return hipErrorInvalidValue;
   int R = lnb_rows_per_wave(H);
   int nb = (rows + 4 * R - 1) / (4 * R);
   float* pg = scratch;
   float* pb = pg + (size_t)nb * H;
   float* pz = pb + (size_t)nb * H;
   switch (ln_nv(H)) {
-    case 2: k_ln_bwd<AT, 2, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H); break;
-    case 4: k_ln_bwd<AT, 4, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H); break;
-    default: k_ln_bwd<AT, 8, 2><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H); break;
+    case 2: k_ln_bwd<AT, 2, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd); break;
+    case 4: k_ln_bwd<AT, 4, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd); break;
+    default: k_ln_bwd<AT, 8, 2><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -445,10 +466,10 @@ static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, cons
   return hipGetLastError();
 }
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
-                  float* db, float* dzsum, float* scratch, int rows, int H, hipStream_t s) {
+                  float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s) {
   if (dtype == 0)
-    return ln_bwd_t<float>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, dg, db, dzsum, scratch, rows, H, s);
-  return ln_bwd_t<bf16>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dg, db, dzsum, scratch, rows, H, s);
+    return ln_bwd_t<float>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, dg, db, dzsum, scratch, rows, H, dd, s);
+  return ln_bwd_t<bf16>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dg, db, dzsum, scratch, rows, H, dd, s);
 }
 
 // ---- column sums (bias gradients) -----------------------------------------------------------

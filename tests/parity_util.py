@@ -38,7 +38,7 @@ def rel_errors(g_gpu, g_ref):
 
 
 def run_case(shape, B, S, f, k, emb, precision, ragged=False, seed=0, std=0.02, perturb=0.0, full_backprop=True,
-             model=None, weights=None):
+             model=None, weights=None, dropout=None):
     """Returns dict with loss / grads of both sides for one step on seeded inputs."""
     W = weights if weights is not None else synth.make_weights(shape, seed=seed, std=std, perturb=perturb)
     batch = synth.make_batch(shape, B, S, seed=seed + 1, ragged=ragged)
@@ -47,11 +47,15 @@ def run_case(shape, B, S, f, k, emb, precision, ragged=False, seed=0, std=0.02, 
         model = make_model(shape, B, S, precision)
     model.mslt_load_params(synth.pack_weights(shape, W))
     cb = model.device_batch(batch)
+    drop = None
+    if dropout is not None:            # (p, seed, step): both sides derive the same keep decisions from it
+        model.mslt_set_dropout(*dropout)
+        drop = O.Dropout(*dropout)
     loss = model.mslt_stage_step(f, k, emb, cb)
     g = grads_dict(model, shape, f, k, emb)
     pos, lab = model.mslt_debug_masked()
     prefix = model.mslt_debug_prefix_output(B, S)
-    ref_loss, ref_g, info = O.stage_step(shape, W, batch, f, k, emb, full_backprop=full_backprop)
+    ref_loss, ref_g, info = O.stage_step(shape, W, batch, f, k, emb, full_backprop=full_backprop, drop=drop)
     return {"model": model, "W": W, "batch": batch, "cb": cb, "loss": loss, "grads": g, "pos": pos, "lab": lab,
             "prefix": prefix, "ref_loss": ref_loss, "ref_grads": ref_g, "ref_info": info}
 
