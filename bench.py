@@ -99,6 +99,9 @@ def extra_workloads(torch, binding, synth, steps):
     cases = [
         ("base_final_64x128", synth.bert_base_shape(12), 64, 128, [(9, 3, False)], binding.adam(lr=1e-4)),
         ("base_final_16x512", synth.bert_base_shape(12), 16, 512, [(9, 3, False)], binding.adam(lr=1e-4)),
+        # grouped variant (Section 3.3): 12 layers in 4 groups of 3 that share their parameters
+        ("base_grouped_4x3_final_64x128", synth.ModelShape(n_layers=12, hidden=768, n_heads=12, ffn=3072, vocab=30522,
+                                                           layers_per_group=3), 64, 128, [(9, 3, False)], binding.adam(lr=1e-4)),
         ("large_final_64x128_lamb", synth.bert_large_shape(24), 64, 128, [(18, 6, False)], binding.lamb()),
         ("large_sweep_32x512_lamb", synth.bert_large_shape(24), 32, 512,
          [(0, 6, True), (6, 6, False), (12, 6, False), (18, 6, False)], binding.lamb()),

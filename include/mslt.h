@@ -60,6 +60,11 @@ typedef struct {
   int precision;       /* 0 fp32, 1 bf16 compute with fp32 master */
   float ln_eps;        /* LayerNorm epsilon (1e-12) */
   float mask_bias;     /* added to the scores of padded keys (-10000) */
+  int layers_per_group; /* 0 or 1: every layer has its own parameters (BERT).  n > 1: the grouped ALBERT
+                          variant of Section 3.3 - each run of n consecutive layers shares one parameter set
+                          ("layer g" in the tensor table is the set of group g; there are n_layers_max / n sets),
+                          the gradients of a set are the sums over its n applications, and the layer counts of
+                          mslt_stage_step / mslt_train_step / mslt_grow must be whole groups */
 } mslt_config;
 
 /* One masked-LM batch.  DEVICE pointers to int32 arrays of batch*seq entries, row-major

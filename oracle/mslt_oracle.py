@@ -100,6 +100,15 @@ def softmax_rows(a):
     return e / e.sum(axis=-1, keepdims=True)
 
 
+def layers_per_group(cfg) -> int:
+    return max(1, int(getattr(cfg, "layers_per_group", 1)))
+
+
+def param_prefix(cfg, i: int) -> str:
+    """Name prefix of the parameter set layer i uses: its own (BERT) or its group's (Section 3.3)."""
+    return f"layer{i // layers_per_group(cfg)}."
+
+
 def to_f64(params):
     return {k: np.asarray(v, dtype=np.float64) for k, v in params.items()}
 
@@ -176,8 +185,10 @@ def embed_forward(cfg, P, batch, drop=None):
 
 
 def layer_forward(cfg, P, i, X, key_bias, B, S, ops, drop=None):
-    """One post-LN encoder layer. X is [T, H]; key_bias is [B, S] (0 for tokens, mask_bias for padding)."""
-    p = f"layer{i}."
+    """One post-LN encoder layer. X is [T, H]; key_bias is [B, S] (0 for tokens, mask_bias for padding).
+
+    In the grouped variant of Section 3.3 layer i uses the parameter set of its group, layer{i // g}.*."""
+    p = param_prefix(cfg, i)
     H, nh = cfg.hidden, cfg.n_heads
     dh = H // nh
     Q = ops.mm(X, P[p + "wq"].T) + P[p + "bq"]
@@ -290,7 +301,7 @@ def head_backward(cfg, P, hc, T, ops):
 
 
 def layer_backward(cfg, P, i, c, dX2, B, S, ops):
-    p = f"layer{i}."
+    p = param_prefix(cfg, i)
     H, nh = cfg.hidden, cfg.n_heads
     dh = H // nh
     scale = 1.0 / math.sqrt(dh)
@@ -358,7 +369,8 @@ def backward(cfg, cache, ops=None, stop_layer=0, with_embeddings=True):
     dX, grads, g_word_head, _ = head_backward(cfg, P, cache["head"], T, ops)
     for i in range(cache["n_layers"] - 1, stop_layer - 1, -1):
         dX, g = layer_backward(cfg, P, i, cache["layers"][i], dX, B, S, ops)
-        grads.update(g)
+        for name, val in g.items():      # layers of one group share their tensors: their gradients add up
+            grads[name] = grads[name] + val if name in grads else val
     if with_embeddings:
         assert stop_layer == 0
         ge, gw_in = embed_backward(cfg, P, cache["emb"], dX)
@@ -367,9 +379,9 @@ def backward(cfg, cache, ops=None, stop_layer=0, with_embeddings=True):
     return grads
 
 
-def stage_tensor_names(frozen_layers, trainable_layers, train_embeddings):
+def stage_tensor_names(frozen_layers, trainable_layers, train_embeddings, group=1):
     names = list(EMB_TENSORS) if train_embeddings else []
-    for i in range(frozen_layers, frozen_layers + trainable_layers):
+    for i in range(frozen_layers // group, (frozen_layers + trainable_layers) // group):
         names += [f"layer{i}.{t}" for t in LAYER_TENSORS]
     names += list(HEAD_TENSORS)
     return names
@@ -399,7 +411,10 @@ def stage_step(cfg, params, batch, frozen_layers, trainable_layers, train_embedd
         g_all = backward(cfg, cache, ops=ops, stop_layer=0, with_embeddings=True)
     else:
         g_all = backward(cfg, cache, ops=ops, stop_layer=frozen_layers, with_embeddings=train_embeddings)
-    names = stage_tensor_names(frozen_layers, trainable_layers, train_embeddings)
+    g = layers_per_group(cfg)
+    if frozen_layers % g or trainable_layers % g:
+        raise ValueError("frozen and trainable layers must be whole groups")
+    names = stage_tensor_names(frozen_layers, trainable_layers, train_embeddings, g)
     grads = {k: g_all[k] for k in names}
     info = {"pos": cache["head"]["pos"], "labels": cache["head"]["Y"], "prefix_out": cache["prefix_out"],
             "XL": cache["XL"], "cache": cache}
@@ -460,7 +475,8 @@ def optimizer_update(params, grads, state, kind="adam", lr=1e-4, beta1=0.9, beta
 
 
 def grow(params, n_present, n_new):
-    """Stack growth (Section 3.2): new layer n_present+i is a copy of layer n_present-n_new+i."""
+    """Stack growth (Section 3.2): new layer n_present+i is a copy of layer n_present-n_new+i.
+    With grouped layers (Section 3.3) the counts are in parameter sets (groups)."""
     out = dict(params)
     for i in range(n_new):
         for t in LAYER_TENSORS:

@@ -118,6 +118,7 @@ __device__ __forceinline__ void store_acc_T(bf16* __restrict__ out, size_t ld, i
 }
 
 // ---- forward --------------------------------------------------------------------------------
+template <bool DROP>
 __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
                                                        float* __restrict__ lse, const int32_t* __restrict__ am, int S,
                                                        int nh, float scale, float mask_bias, DropSpec drop) {
@@ -177,7 +178,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ 
       }
     l_run = l_run * alpha + psum;
     m_run = m_new;
-    if (drop.thr) {   // the row sum above is of the undropped probabilities; the product below uses the kept ones
+    if constexpr (DROP) {   // the row sum above is of the undropped probabilities; the product below uses the kept ones
       const uint64_t rowbase = (((uint64_t)b * nh + h) * S + q) * S + (uint64_t)kt * TILE;
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
@@ -211,6 +212,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ 
 }
 
 // ---- backward, query side: delta and dQ -----------------------------------------------------
+template <bool DROP>
 __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
                                                          const bf16* __restrict__ dctx, const float* __restrict__ lse,
                                                          float* __restrict__ delta, bf16* __restrict__ dqkv,
@@ -265,7 +267,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
         float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
         float bv[4] = {bb.x, bb.y, bb.z, bb.w};
         float kf4[4] = {1.f, 1.f, 1.f, 1.f};
-        if (drop.thr) {
+        if constexpr (DROP) {
           const uint64_t r = drop_quad(drop, (rowbase + (uint64_t)kt * TILE + kb * 32 + 8 * g + 4 * half) >> 2);
 #pragma unroll
           for (int j = 0; j < 4; ++j) kf4[j] = drop_field(drop, r, j);
@@ -290,6 +292,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
 }
 
 // ---- backward, key side: dK and dV ----------------------------------------------------------
+template <bool DROP>
 __global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dctx,
                                                           const float* __restrict__ lse,
                                                           const float* __restrict__ delta, bf16* __restrict__ dqkv,
@@ -349,7 +352,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict
         for (int j = 0; j < 4; ++j) {
           float p = __expf(s[4 * g + j] * scale + kbias - lv[j]);
           float kf1 = 1.f;
-          if (drop.thr) kf1 = drop_factor(drop, (headbase + (uint64_t)qt * TILE + qb * 32 + 8 * g + 4 * half + j) * S + key);
+          if constexpr (DROP) kf1 = drop_factor(drop, (headbase + (uint64_t)qt * TILE + qb * 32 + 8 * g + 4 * half + j) * S + key);
           s[4 * g + j] = p * kf1;                                   // dropped P (for dV)
           dp[4 * g + j] = p * (dp[4 * g + j] * kf1 - dv[j]);        // dS
         }
@@ -379,6 +382,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict
 // two kernels above.  Every operand is read from memory once and delta never leaves the chip.
 constexpr int ONE_LDS_BYTES = (4 * TILE * DH + 3 * DH * TLD) * 2 + 3 * TILE * 4;
 
+template <bool DROP>
 __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
                                                            const bf16* __restrict__ dctx,
                                                            const float* __restrict__ lse, bf16* __restrict__ dqkv,
@@ -459,7 +463,7 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
         float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
         float bv[4] = {bb.x, bb.y, bb.z, bb.w};
         float kf4[4] = {1.f, 1.f, 1.f, 1.f};
-        if (drop.thr) {
+        if constexpr (DROP) {
           const uint64_t r = drop_quad(drop, (rowbase + kb * 32 + 8 * g + 4 * half) >> 2);
 #pragma unroll
           for (int j = 0; j < 4; ++j) kf4[j] = drop_field(drop, r, j);
@@ -510,7 +514,7 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
         for (int j = 0; j < 4; ++j) {
           float p = __expf(s[4 * g + j] * scale + kbias - lv[j]);
           float kf1 = 1.f;
-          if (drop.thr) kf1 = drop_factor(drop, (headbase + qb * 32 + 8 * g + 4 * half + j) * S + key);
+          if constexpr (DROP) kf1 = drop_factor(drop, (headbase + qb * 32 + 8 * g + 4 * half + j) * S + key);
           s[4 * g + j] = p * kf1;                                   // dropped P (for dV)
           dp[4 * g + j] = p * (dp[4 * g + j] * kf1 - dv[j]);        // dS
         }
@@ -539,42 +543,54 @@ bool attention_mfma_supported(int S, int dh) { return dh == DH && S >= TILE && S
 hipError_t attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
   if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
   dim3 grid(a.S / TILE, a.nh, a.B);
-  k_attn_fwd_mfma<<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
-                                             1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
+  // dropout is a compile-time variant so that the plain kernels carry none of its registers
+  if (a.drop.thr)
+    k_attn_fwd_mfma<true><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
+                                                     1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
+  else
+    k_attn_fwd_mfma<false><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
+                                                      1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
   return hipGetLastError();
 }
 
-hipError_t attention_bwd_mfma(const AttnBwdDesc& a, hipStream_t s) {
-  if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
+template <bool DROP>
+static hipError_t attention_bwd_mfma_t(const AttnBwdDesc& a, hipStream_t s) {
   dim3 grid(a.S / TILE, a.nh, a.B);
   float scale = 1.0f / sqrtf((float)a.dh);
   if (a.S == TILE) {
-    static bool one_attr_set = false;
+    static bool one_attr_set = false;     // one flag per instantiation
     if (!one_attr_set) {
-      hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_bwd_one_tile),
+      hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_bwd_one_tile<DROP>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, ONE_LDS_BYTES);
       if (e1 != hipSuccess) return e1;
       one_attr_set = true;
     }
-    k_attn_bwd_one_tile<<<dim3(a.nh, a.B), dim3(512), ONE_LDS_BYTES, s>>>(
+    k_attn_bwd_one_tile<DROP><<<dim3(a.nh, a.B), dim3(512), ONE_LDS_BYTES, s>>>(
         (const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse, (bf16*)a.dqkv, a.attn_mask, a.nh, scale,
         a.mask_bias, a.drop);
     return hipGetLastError();
   }
-  k_attn_bwd_q_mfma<<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse,
-                                               a.delta, (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale, a.mask_bias, a.drop);
+  k_attn_bwd_q_mfma<DROP><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse,
+                                                     a.delta, (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale, a.mask_bias,
+                                                     a.drop);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   static bool attr_set = false;
   if (!attr_set) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_bwd_kv_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            KV_LDS_BYTES);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_bwd_kv_mfma<DROP>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, KV_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  k_attn_bwd_kv_mfma<<<grid, dim3(256), KV_LDS_BYTES, s>>>((const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.delta, (bf16*)a.dqkv,
-                                                a.attn_mask, a.S, a.nh, scale, a.mask_bias, a.drop);
+  k_attn_bwd_kv_mfma<DROP><<<grid, dim3(256), KV_LDS_BYTES, s>>>((const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.delta,
+                                                                 (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale,
+                                                                 a.mask_bias, a.drop);
   return hipGetLastError();
+}
+hipError_t attention_bwd_mfma(const AttnBwdDesc& a, hipStream_t s) {
+  if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
+  // dropout is a compile-time variant so that the plain kernels carry none of its registers
+  return a.drop.thr ? attention_bwd_mfma_t<true>(a, s) : attention_bwd_mfma_t<false>(a, s);
 }
 
 }  // namespace mslt

@@ -131,6 +131,7 @@ struct Epilogue {
   int ldaux = 0;
   DropSpec drop;            // dropout of (acc + bias) before the activation / addend; element index m * drop_ld + n
   int drop_ld = 0;          // logical row width of the dropped tensor (a multiple of 4)
+  int accumulate = 0;       // fp32 output only: out += result (gradient of a parameter set shared by several layers)
 };
 
 struct GemmDesc {
@@ -216,13 +217,15 @@ struct LnBwdDrop {
   void* dzm = nullptr;
   const int32_t* rowmap = nullptr;
   int n_mapped = 0;
+  int accumulate = 0;   // dgamma, dbeta and the column sums are added to what the outputs hold
 };
 // dz from dy, xhat, rstd, gamma; dgamma, dbeta and (if dzsum != null) the column sums of dz (of dzm
 // with output dropout) via partials in scratch (ln_bwd_scratch_floats(rows, H) floats)
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
                   float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s);
 // column sums of Y[rows, N] (leading dimension ld) into out[N]; scratch holds ceil(rows/64)*N floats
-hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s);
+hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s,
+                  int accumulate = 0);   // accumulate: out += sums
 size_t colsum_scratch_floats(int rows, int N);
 size_t ln_bwd_scratch_floats(int rows, int H);
 

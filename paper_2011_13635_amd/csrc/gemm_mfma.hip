@@ -223,6 +223,11 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
   }
   if (e.out_f32) {
     float* p = reinterpret_cast<float*>(e.out) + o;
+    if (e.accumulate) {
+      const float4 a0 = *reinterpret_cast<const float4*>(p), a1 = *reinterpret_cast<const float4*>(p + 4);
+      v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w;
+      v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
+    }
     *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
     *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
   } else {
@@ -432,6 +437,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
   if (d.lda % 8 || d.ldb % 8 || d.epi.ldo % 8) return false;
   if ((d.epi.act == EPI_MUL || d.epi.act == EPI_ADD) && d.epi.ldaux % 8) return false;
   if (d.epi.drop.thr && d.epi.drop_ld % 4) return false;
+  if (d.epi.accumulate && !d.epi.out_f32) return false;
   auto al = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
   if (!al(d.A) || !al(d.B) || !al(d.epi.out) || !al(d.epi.out2) || !al(d.epi.aux) || !al(d.epi.bias)) return false;
   return true;

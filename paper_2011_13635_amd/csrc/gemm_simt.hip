@@ -22,7 +22,7 @@ __device__ inline void epilogue_store(const Epilogue& e, int m, int n, float acc
     v += ldf(reinterpret_cast<const AT*>(e.aux) + (size_t)m * e.ldaux + n);
   }
   if (e.out_f32)
-    reinterpret_cast<float*>(e.out)[o] = v;
+    reinterpret_cast<float*>(e.out)[o] = e.accumulate ? reinterpret_cast<float*>(e.out)[o] + v : v;
   else
     stf(reinterpret_cast<AT*>(e.out) + o, v);
 }

@@ -74,6 +74,8 @@ struct mslt_model {
   bool mfma;        // bf16 MFMA GEMMs with padded row counts
   hipStream_t stream;
   int H, F, V, Vp, nh, dh, L, Tp, Mp, cap;
+  int lpg, Lp;      // layers per parameter-sharing group (1: every layer has its own set), number of sets = L / lpg
+  int acc_now;      // the layer whose backward is being queued adds to its set's gradients (not the first of its group)
   std::vector<mslt_tensor_desc> table;
   std::vector<size_t> alloc_count;  // elements reserved per tensor (>= count)
   size_t arena_elems, packed_count;
@@ -149,7 +151,7 @@ static void build_table(mslt_model* m) {
   add_tensor(m, "emb.ln_b", -1, H, 1, 0, 0, true, off);
   static const char* ln[N_LAYER_T] = {"wq", "wk", "wv", "bq", "bk", "bv", "wo", "bo", "ln1_g", "ln1_b",
                                       "w1", "b1", "w2", "b2", "ln2_g", "ln2_b"};
-  for (int l = 0; l < m->L; ++l) {
+  for (int l = 0; l < m->Lp; ++l) {
     char nm[32];
     for (int j = 0; j < N_LAYER_T; ++j) {
       snprintf(nm, sizeof nm, "layer%d.%s", l, ln[j]);
@@ -185,7 +187,9 @@ static void build_table(mslt_model* m) {
 }
 static inline int t_emb(int j) { return j; }
 static inline int t_layer(int l, int j) { return N_EMB + l * N_LAYER_T + j; }
-static inline int t_head(const mslt_model* m, int j) { return N_EMB + m->L * N_LAYER_T + j; }
+static inline int t_head(const mslt_model* m, int j) { return N_EMB + m->Lp * N_LAYER_T + j; }
+// tensor j of the parameter set that applied layer l uses (layers of a group share one set)
+static inline int t_app(const mslt_model* m, int l, int j) { return t_layer(l / m->lpg, j); }
 static inline float* Wf(const mslt_model* m, int t) { return m->param + m->table[t].offset; }
 static inline float* Gf(const mslt_model* m, int t) { return m->grad + m->table[t].offset; }
 // GEMM operand view of a weight matrix: bf16 shadow in bf16 mode, the master itself in fp32 mode
@@ -305,6 +309,8 @@ static int check_config(const mslt_config* c) {
   if ((long long)c->max_batch * c->max_seq > (1 << 22)) return fail(MSLT_ERR_ARG, "config: max_batch*max_seq too large");
   if (c->precision != 0 && c->precision != 1) return fail(MSLT_ERR_ARG, "config: precision must be 0 or 1");
   if (!(c->ln_eps >= 0.f)) return fail(MSLT_ERR_ARG, "config: ln_eps must be >= 0");
+  if (c->layers_per_group < 0 || (c->layers_per_group > 1 && c->n_layers_max % c->layers_per_group))
+    return fail(MSLT_ERR_ARG, "config: n_layers_max must be a multiple of layers_per_group");
   return MSLT_OK;
 }
 
@@ -314,6 +320,8 @@ static void setup_dims(mslt_model* m, const mslt_config* cfg) {
   m->esz = cfg->precision ? 2 : 4;
   m->H = cfg->hidden; m->F = cfg->ffn; m->V = cfg->vocab; m->nh = cfg->n_heads; m->dh = cfg->hidden / cfg->n_heads;
   m->L = cfg->n_layers_max;
+  m->lpg = cfg->layers_per_group > 1 ? cfg->layers_per_group : 1;
+  m->Lp = m->L / m->lpg;
   m->Vp = (int)rup(cfg->vocab, 128);
   int T = cfg->max_batch * cfg->max_seq;
   m->cap = cfg->max_predictions > 0 && cfg->max_predictions < T ? cfg->max_predictions : T;
@@ -511,6 +519,9 @@ static int side_join(mslt_model* m) {
 // last reader of that set, before anything is written there.
 static int layer_backward_begin(mslt_model* m, int l) {
   const int p = l & 1;
+  // the top layer of a group is the first to run backward and writes its set's gradients; the
+  // layers of the group below it add theirs (the two streams keep the order per tensor)
+  m->acc_now = (l % m->lpg) != m->lpg - 1;
   if (m->set_busy[p]) {
     HIP_TRY(hipStreamWaitEvent(m->stream, m->ev_set[p], 0));
     m->set_busy[p] = false;
@@ -520,6 +531,7 @@ static int layer_backward_begin(mslt_model* m, int l) {
   return MSLT_OK;
 }
 static int layer_backward_end(mslt_model* m, int l) {
+  m->acc_now = 0;
   if (!m->side_forked) return MSLT_OK;
   HIP_TRY(hipEventRecord(m->ev_set[l & 1], m->side));
   m->set_busy[l & 1] = true;
@@ -584,7 +596,7 @@ static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int
   GemmDesc d;
   d.A = dY; d.lda = ldy; d.a_kcontig = 0; d.M = N;
   d.B = X; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = rows;
-  d.epi.out = dW; d.epi.ldo = K; d.epi.out_f32 = 1;
+  d.epi.out = dW; d.epi.ldo = K; d.epi.out_f32 = 1; d.epi.accumulate = m->acc_now;
   hipStream_t st; float *partials, *red;
   RC(side_fork(m, &st, &partials, &red));
   return run_gemm(m, d, true, st, partials);
@@ -605,7 +617,7 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
   void* ctx = st ? st->ctx : m->s_ctx;
   void* x1 = st ? st->x1 : m->s_x1;
   void* g = st ? st->g : m->s_g;
-  RC(linear_fwd(m, Xin, Tr, H, Wg(m, t_layer(l, L_WQ)), 3 * H, Wf(m, t_layer(l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr));
+  RC(linear_fwd(m, Xin, Tr, H, Wg(m, t_app(m, l, L_WQ)), 3 * H, Wf(m, t_app(m, l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr));
   AttnDesc a{qkv, ctx, st ? st->lse : nullptr, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh, m->cfg.mask_bias,
              dspec(m, l, SITE_ATTN_PROBS)};
   {
@@ -616,15 +628,15 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
     else
       HIP_TRY(attention_fwd_simple(m->dtype, a, m->stream));
   }
-  RC(linear_fwd(m, ctx, Tr, H, Wg(m, t_layer(l, L_WO)), H, Wf(m, t_layer(l, L_BO)), m->s_y, 0, H, EPI_NONE, nullptr,
+  RC(linear_fwd(m, ctx, Tr, H, Wg(m, t_app(m, l, L_WO)), H, Wf(m, t_app(m, l, L_BO)), m->s_y, 0, H, EPI_NONE, nullptr,
                 dspec(m, l, SITE_ATTN_OUT)));
   LnStash s1, s2;
   if (st) { s1.xhat = st->xhat1; s1.rstd = st->rstd1; s2.xhat = st->xhat2; s2.rstd = st->rstd2; }
-  RC(ln_forward(m, m->s_y, Xin, Wf(m, t_layer(l, L_LN1G)), Wf(m, t_layer(l, L_LN1B)), x1, s1, Tr));
-  RC(linear_fwd(m, x1, Tr, H, Wg(m, t_layer(l, L_W1)), F, Wf(m, t_layer(l, L_B1)), g, 0, F, EPI_GELU, st ? st->u : nullptr));
-  RC(linear_fwd(m, g, Tr, F, Wg(m, t_layer(l, L_W2)), H, Wf(m, t_layer(l, L_B2)), m->s_y, 0, H, EPI_NONE, nullptr,
+  RC(ln_forward(m, m->s_y, Xin, Wf(m, t_app(m, l, L_LN1G)), Wf(m, t_app(m, l, L_LN1B)), x1, s1, Tr));
+  RC(linear_fwd(m, x1, Tr, H, Wg(m, t_app(m, l, L_W1)), F, Wf(m, t_app(m, l, L_B1)), g, 0, F, EPI_GELU, st ? st->u : nullptr));
+  RC(linear_fwd(m, g, Tr, F, Wg(m, t_app(m, l, L_W2)), H, Wf(m, t_app(m, l, L_B2)), m->s_y, 0, H, EPI_NONE, nullptr,
                 dspec(m, l, SITE_FFN_OUT)));
-  RC(ln_forward(m, m->s_y, x1, Wf(m, t_layer(l, L_LN2G)), Wf(m, t_layer(l, L_LN2B)), Xout, s2, Tr));
+  RC(ln_forward(m, m->s_y, x1, Wf(m, t_app(m, l, L_LN2G)), Wf(m, t_app(m, l, L_LN2B)), Xout, s2, Tr));
   return MSLT_OK;
 }
 
@@ -632,13 +644,15 @@ static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, flo
   ProfScope ps(m, PC_COLSUM, (double)rows * N, (double)rows * N * m->esz);
   hipStream_t st; float *partials, *red;
   RC(side_fork(m, &st, &partials, &red));
-  HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, red, st));
+  HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, red, st, m->acc_now));
   return MSLT_OK;
 }
 // dzsum (may be null): column sums of dz = bias gradient of the linear layer feeding this LayerNorm
 static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz,
-                       float* dg, float* db, float* dzsum, int rows, const LnBwdDrop& dd = LnBwdDrop()) {
-  ProfScope ps(m, PC_LN_BWD, 0.0, (dd.out.thr ? 4.0 : 3.0) * rows * m->H * m->esz);
+                       float* dg, float* db, float* dzsum, int rows, const LnBwdDrop& dd_in = LnBwdDrop()) {
+  ProfScope ps(m, PC_LN_BWD, 0.0, (dd_in.out.thr ? 4.0 : 3.0) * rows * m->H * m->esz);
+  LnBwdDrop dd = dd_in;
+  dd.accumulate = m->acc_now;
   HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, dd, m->stream));
   return MSLT_OK;
 }
@@ -664,17 +678,17 @@ static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const U
   d1.out = dspec(m, l, SITE_ATTN_OUT); d1.dzm = r.dz1m; d1.rowmap = r.rowmap; d1.n_mapped = r.n_mapped;
   const void* dy2 = d2.out.thr ? r.dz2m : r.dz2;
   const void* dy1 = d1.out.thr ? r.dz1m : r.dz1;
-  RC(ln_backward(m, dXout, r.xhat2, r.rstd2, Wf(m, t_layer(l, L_LN2G)), r.dz2, Gf(m, t_layer(l, L_LN2G)),
-                 Gf(m, t_layer(l, L_LN2B)), Gf(m, t_layer(l, L_B2)), R, d2));
-  RC(linear_bwd_weight(m, dy2, R, H, H, r.g, F, Gf(m, t_layer(l, L_W2))));
-  RC(linear_bwd_input(m, dy2, R, H, H, Wg(m, t_layer(l, L_W2)), F, r.du, EPI_MUL, r.u));
-  RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_layer(l, L_W1))));
-  RC(bias_grad(m, r.du, F, R, F, Gf(m, t_layer(l, L_B1))));
-  RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_layer(l, L_W1)), H, r.dx1, EPI_ADD, r.dz2));
-  RC(ln_backward(m, r.dx1, r.xhat1, r.rstd1, Wf(m, t_layer(l, L_LN1G)), r.dz1, Gf(m, t_layer(l, L_LN1G)),
-                 Gf(m, t_layer(l, L_LN1B)), Gf(m, t_layer(l, L_BO)), R, d1));
-  RC(linear_bwd_weight(m, dy1, R, H, H, r.ctx, H, Gf(m, t_layer(l, L_WO))));
-  RC(linear_bwd_input(m, dy1, R, H, H, Wg(m, t_layer(l, L_WO)), H, r.dc, EPI_NONE, nullptr));
+  RC(ln_backward(m, dXout, r.xhat2, r.rstd2, Wf(m, t_app(m, l, L_LN2G)), r.dz2, Gf(m, t_app(m, l, L_LN2G)),
+                 Gf(m, t_app(m, l, L_LN2B)), Gf(m, t_app(m, l, L_B2)), R, d2));
+  RC(linear_bwd_weight(m, dy2, R, H, H, r.g, F, Gf(m, t_app(m, l, L_W2))));
+  RC(linear_bwd_input(m, dy2, R, H, H, Wg(m, t_app(m, l, L_W2)), F, r.du, EPI_MUL, r.u));
+  RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_app(m, l, L_W1))));
+  RC(bias_grad(m, r.du, F, R, F, Gf(m, t_app(m, l, L_B1))));
+  RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_app(m, l, L_W1)), H, r.dx1, EPI_ADD, r.dz2));
+  RC(ln_backward(m, r.dx1, r.xhat1, r.rstd1, Wf(m, t_app(m, l, L_LN1G)), r.dz1, Gf(m, t_app(m, l, L_LN1G)),
+                 Gf(m, t_app(m, l, L_LN1B)), Gf(m, t_app(m, l, L_BO)), R, d1));
+  RC(linear_bwd_weight(m, dy1, R, H, H, r.ctx, H, Gf(m, t_app(m, l, L_WO))));
+  RC(linear_bwd_input(m, dy1, R, H, H, Wg(m, t_app(m, l, L_WO)), H, r.dc, EPI_NONE, nullptr));
   return MSLT_OK;
 }
 // Attention backward and the QKV projection backward, from dC and dz1 (both [Tr, H], all token rows).
@@ -696,9 +710,9 @@ static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int 
     if (Tr > T)  // padded token rows must contribute nothing to the weight gradients
       HIP_TRY(fill_zero((char*)m->d_qkv + (size_t)T * 3 * H * m->esz, (size_t)(Tr - T) * 3 * H * m->esz, s));
   }
-  RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_layer(l, L_WQ))));
-  RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_layer(l, L_BQ))));
-  if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_layer(l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
+  RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_app(m, l, L_WQ))));
+  RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_app(m, l, L_BQ))));
+  if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_app(m, l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
   return layer_backward_end(m, l);
 }
 // dXout: gradient w.r.t. the layer output on all token rows.
@@ -746,6 +760,8 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
     return fail(MSLT_ERR_ARG, "stage_step: bad layer split frozen=%d trainable=%d (layers %d)", f, k, m->L);
   if (train_emb != 0 && train_emb != 1) return fail(MSLT_ERR_ARG, "stage_step: train_embeddings must be 0 or 1");
   if (train_emb && f != 0) return fail(MSLT_ERR_ARG, "stage_step: embeddings train only when nothing is frozen");
+  if (f % m->lpg || k % m->lpg)
+    return fail(MSLT_ERR_ARG, "stage_step: frozen and trainable layer counts must be whole groups of %d layers", m->lpg);
   if (!bt->input_ids || !bt->token_type_ids || !bt->attn_mask || !bt->labels)
     return fail(MSLT_ERR_ARG, "stage_step: null batch pointer");
   if (bt->batch < 1 || bt->batch > m->cfg.max_batch || bt->seq < 1 || bt->seq > m->cfg.max_seq)
@@ -755,6 +771,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   hipStream_t s = m->stream;
   const int H = m->H, B = bt->batch, S = bt->seq, T = B * S;
   m->have_grads = false;
+  m->acc_now = 0;
 
   // S0: batch check and compaction of the predicted positions (only index scratch is written)
   HIP_TRY(batch_scan(bt->input_ids, bt->token_type_ids, bt->attn_mask, bt->labels, T, m->V, m->cfg.type_vocab, m->cap,
@@ -875,7 +892,7 @@ extern "C" int mslt_stage_step(mslt_model* m, int f, int k, int train_emb, const
 static int trainable_ranges(const mslt_model* m, int (*r)[2]) {
   int n = 0;
   if (m->last_emb) { r[n][0] = 0; r[n][1] = N_EMB; ++n; }
-  r[n][0] = t_layer(m->last_f, 0); r[n][1] = t_layer(m->last_f + m->last_k, 0); ++n;
+  r[n][0] = t_layer(m->last_f / m->lpg, 0); r[n][1] = t_layer((m->last_f + m->last_k) / m->lpg, 0); ++n;
   r[n][0] = t_head(m, 0); r[n][1] = t_head(m, 0) + N_HEAD; ++n;
   // merge adjacent ranges
   int out = 0;
@@ -1004,6 +1021,10 @@ extern "C" int mslt_grow(mslt_model* m, int n_present, int n_new) {
   if (!m) return fail(MSLT_ERR_ARG, "model is null");
   if (n_new < 1 || n_present < n_new || n_present + n_new > m->L)
     return fail(MSLT_ERR_ARG, "grow: bad layer counts present=%d new=%d (layers %d)", n_present, n_new, m->L);
+  if (n_present % m->lpg || n_new % m->lpg)
+    return fail(MSLT_ERR_ARG, "grow: layer counts must be whole groups of %d layers", m->lpg);
+  n_present /= m->lpg;      // from here on in parameter sets
+  n_new /= m->lpg;
   for (int i = 0; i < n_new; ++i) {
     int src = n_present - n_new + i, dst = n_present + i;
     for (int j = 0; j < N_LAYER_T; ++j) {

@@ -293,6 +293,7 @@ hipError_t add_ln_fwd(int dtype, const void* a, const void* r, const float* g, c
 struct ReduceArgs {
   const float* partial[3];
   float* out[3];
+  int accumulate;     // add to what out holds (gradients of a parameter set shared by several layers)
 };
 __global__ void __launch_bounds__(1024) k_reduce_partials(ReduceArgs a, int n_partials, int N) {
   __shared__ float sh[32][33];
@@ -315,11 +316,12 @@ __global__ void __launch_bounds__(1024) k_reduce_partials(ReduceArgs a, int n_pa
     float v = 0.f;
 #pragma unroll
     for (int j = 0; j < 32; ++j) v += sh[j][cl];
-    a.out[blockIdx.y][c] = v;
+    a.out[blockIdx.y][c] = a.accumulate ? a.out[blockIdx.y][c] + v : v;
   }
 }
-static hipError_t reduce_partials(const float* partial, int n_partials, int N, float* out, hipStream_t s) {
-  ReduceArgs a{{partial, nullptr, nullptr}, {out, nullptr, nullptr}};
+static hipError_t reduce_partials(const float* partial, int n_partials, int N, float* out, hipStream_t s,
+                                  int accumulate = 0) {
+  ReduceArgs a{{partial, nullptr, nullptr}, {out, nullptr, nullptr}, accumulate};
   k_reduce_partials<<<dim3((N + 31) / 32, 1), dim3(1024), 0, s>>>(a, n_partials, N);
   return hipGetLastError();
 }
@@ -461,7 +463,7 @@ static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, cons
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  ReduceArgs a{{pg, pb, pz}, {dg, db, dzsum}};
+  ReduceArgs a{{pg, pb, pz}, {dg, db, dzsum}, dd.accumulate};
   k_reduce_partials<<<dim3((H + 31) / 32, dzsum ? 3 : 2), dim3(1024), 0, s>>>(a, nb, H);
   return hipGetLastError();
 }
@@ -536,7 +538,8 @@ __global__ void __launch_bounds__(256) k_colsum_partial(const AT* __restrict__ y
   for (int r = r0; r < r1; ++r) acc += ldf(y + (size_t)r * ld + c);
   partial[(size_t)blockIdx.y * N + c] = acc;
 }
-hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s) {
+hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s,
+                  int accumulate) {
   bool vec = (N % 8 == 0) && (ld % 8 == 0) && ((reinterpret_cast<uintptr_t>(y) & 31) == 0);
   int nchunks;
   if (vec) {
@@ -556,7 +559,7 @@ hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out,
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return reduce_partials(scratch, nchunks, N, out, s);
+  return reduce_partials(scratch, nchunks, N, out, s, accumulate);
 }
 
 // ---- GELU backward of the head: gradient times the derivative stored by the forward epilogue

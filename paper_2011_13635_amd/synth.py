@@ -36,6 +36,13 @@ class ModelShape:
     type_vocab: int = 2
     ln_eps: float = 1e-12
     mask_bias: float = -10000.0
+    # grouped ALBERT variant (Section 3.3): runs of this many consecutive layers share one parameter set,
+    # named layer{g}.* for group g; 1 = every layer has its own set (BERT)
+    layers_per_group: int = 1
+
+    @property
+    def n_param_sets(self):
+        return self.n_layers // self.layers_per_group
 
     def as_dict(self):
         return asdict(self)
@@ -72,7 +79,7 @@ def tensor_specs(shape: ModelShape):
         ("emb.ln_g", (H,), "gamma"),
         ("emb.ln_b", (H,), "beta"),
     ]
-    for i in range(shape.n_layers):
+    for i in range(shape.n_param_sets):
         p = f"layer{i}."
         specs += [
             (p + "wq", (H, H), "matrix"), (p + "wk", (H, H), "matrix"), (p + "wv", (H, H), "matrix"),
@@ -187,7 +194,8 @@ def trainable_names(shape: ModelShape, frozen_layers: int, trainable_layers: int
     names = []
     if train_embeddings:
         names += ["emb.word", "emb.pos", "emb.type", "emb.ln_g", "emb.ln_b"]
-    for i in range(frozen_layers, frozen_layers + trainable_layers):
+    g = shape.layers_per_group
+    for i in range(frozen_layers // g, (frozen_layers + trainable_layers) // g):
         names += [f"layer{i}.{t}" for t in LAYER_TENSORS]
     names += ["head.wt", "head.bt", "head.ln_g", "head.ln_b", "head.b_out"]
     return names
