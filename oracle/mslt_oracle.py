@@ -33,6 +33,7 @@ LAYER_TENSORS = ("wq", "wk", "wv", "bq", "bk", "bv", "wo", "bo", "ln1_g", "ln1_b
                  "w1", "b1", "w2", "b2", "ln2_g", "ln2_b")
 EMB_TENSORS = ("emb.word", "emb.pos", "emb.type", "emb.ln_g", "emb.ln_b")
 HEAD_TENSORS = ("head.wt", "head.bt", "head.ln_g", "head.ln_b", "head.b_out")
+NSP_TENSORS = ("pooler.w", "pooler.b", "nsp.w", "nsp.b")
 IGNORE_LABEL = -100
 
 
@@ -245,6 +246,31 @@ def head_forward(cfg, P, XL, pos, Y, ops):
     return loss, {"Xm": Xm, "Ut": Ut, "Gt": Gt, "Hm": Hm, "ln": ln, "Z": Z, "lse": lse, "pos": pos, "Y": Y}
 
 
+def nsp_forward(cfg, P, XL, B, S, Ynsp, ops):
+    """Next-sentence head (Section 4.1 keeps BERT's second objective): pooler = tanh(dense) of every
+    sequence's first token, a two-way classifier on it, mean cross-entropy over the batch."""
+    cls = np.arange(B) * S
+    Xc = XL[cls]
+    Pl = np.tanh(ops.mm(Xc, P["pooler.w"].T) + P["pooler.b"])
+    Z = ops.mm(Pl, P["nsp.w"].T) + P["nsp.b"]
+    zmax = Z.max(axis=-1, keepdims=True)
+    lse = (zmax + np.log(np.exp(Z - zmax).sum(axis=-1, keepdims=True)))[:, 0]
+    loss = (lse - Z[np.arange(B), Ynsp]).sum() / B
+    return loss, {"cls": cls, "Xc": Xc, "Pl": Pl, "Z": Z, "lse": lse, "Y": Ynsp}
+
+
+def nsp_backward(cfg, P, nc, ops):
+    B = len(nc["cls"])
+    dZ = np.exp(nc["Z"] - nc["lse"][:, None])
+    dZ[np.arange(B), nc["Y"]] -= 1.0
+    dZ /= B
+    g = {"nsp.w": ops.mm(dZ.T, nc["Pl"]), "nsp.b": dZ.sum(axis=0)}
+    dU = ops.mm(dZ, P["nsp.w"]) * (1.0 - nc["Pl"] ** 2)
+    g["pooler.w"] = ops.mm(dU.T, nc["Xc"])
+    g["pooler.b"] = dU.sum(axis=0)
+    return ops.mm(dU, P["pooler.w"]), g          # gradient of the first-token rows of the last layer's output
+
+
 def forward(cfg, params, batch, n_layers=None, ops=None, keep_from=0, prefix_at=None, drop=None):
     """Forward through the embedding block, layers 0..n_layers-1 and the masked-LM head.
 
@@ -272,8 +298,12 @@ def forward(cfg, params, batch, n_layers=None, ops=None, keep_from=0, prefix_at=
     if len(pos) == 0:
         raise ValueError("batch has no predicted position")
     loss, head_cache = head_forward(cfg, P, X, pos, Y, ops)
+    nsp_cache = None
+    if getattr(cfg, "nsp", False):              # the two objectives are added
+        nsp_loss, nsp_cache = nsp_forward(cfg, P, X, B, S, np.asarray(batch["nsp_labels"], dtype=np.int64), ops)
+        loss = loss + nsp_loss
     cache = {"P64": P, "B": B, "S": S, "T": B * S, "n_layers": n_layers, "emb": emb_cache, "layers": layer_caches,
-             "head": head_cache, "XL": X, "prefix_out": prefix_out, "keep_from": keep_from}
+             "head": head_cache, "nsp": nsp_cache, "XL": X, "prefix_out": prefix_out, "keep_from": keep_from}
     return loss, cache
 
 
@@ -367,6 +397,10 @@ def backward(cfg, cache, ops=None, stop_layer=0, with_embeddings=True):
     P = cache["P64"]
     B, S, T = cache["B"], cache["S"], cache["T"]
     dX, grads, g_word_head, _ = head_backward(cfg, P, cache["head"], T, ops)
+    if cache.get("nsp") is not None:
+        dXc, g = nsp_backward(cfg, P, cache["nsp"], ops)
+        dX[cache["nsp"]["cls"]] += dXc
+        grads.update(g)
     for i in range(cache["n_layers"] - 1, stop_layer - 1, -1):
         dX, g = layer_backward(cfg, P, i, cache["layers"][i], dX, B, S, ops)
         for name, val in g.items():      # layers of one group share their tensors: their gradients add up
@@ -415,6 +449,8 @@ def stage_step(cfg, params, batch, frozen_layers, trainable_layers, train_embedd
     if frozen_layers % g or trainable_layers % g:
         raise ValueError("frozen and trainable layers must be whole groups")
     names = stage_tensor_names(frozen_layers, trainable_layers, train_embeddings, g)
+    if getattr(cfg, "nsp", False):
+        names += list(NSP_TENSORS)
     grads = {k: g_all[k] for k in names}
     info = {"pos": cache["head"]["pos"], "labels": cache["head"]["Y"], "prefix_out": cache["prefix_out"],
             "XL": cache["XL"], "cache": cache}
@@ -427,7 +463,7 @@ def stage_step(cfg, params, batch, frozen_layers, trainable_layers, train_embedd
 def decays(name: str) -> bool:
     """Weight decay applies to matrices and embedding tables, not to biases or LayerNorm parameters."""
     leaf = name.split(".")[-1]
-    return leaf in ("word", "pos", "type", "wq", "wk", "wv", "wo", "w1", "w2", "wt")
+    return leaf in ("word", "pos", "type", "wq", "wk", "wv", "wo", "w1", "w2", "wt", "w")
 
 
 def new_opt_state(params):

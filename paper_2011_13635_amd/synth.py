@@ -22,6 +22,7 @@ IGNORE_LABEL = -100
 # stream identifiers of the counter-based generator
 _STREAM_WEIGHTS, _STREAM_TOKENS, _STREAM_LENGTHS, _STREAM_MASKPOS, _STREAM_MASKKIND, _STREAM_MASKRAND = (
     11, 12, 13, 14, 15, 16)
+_STREAM_NSP = 17
 
 
 @dataclass(frozen=True)
@@ -39,6 +40,9 @@ class ModelShape:
     # grouped ALBERT variant (Section 3.3): runs of this many consecutive layers share one parameter set,
     # named layer{g}.* for group g; 1 = every layer has its own set (BERT)
     layers_per_group: int = 1
+    # next-sentence head (Section 4.1 keeps BERT's second objective): pooler (dense + tanh on the first
+    # token) and a two-way classifier, tensors pooler.w, pooler.b, nsp.w, nsp.b after the masked-LM head
+    nsp: bool = False
 
     @property
     def n_param_sets(self):
@@ -95,6 +99,9 @@ def tensor_specs(shape: ModelShape):
         ("head.ln_g", (H,), "gamma"), ("head.ln_b", (H,), "beta"),
         ("head.b_out", (V,), "bias"),
     ]
+    if shape.nsp:
+        specs += [("pooler.w", (H, H), "matrix"), ("pooler.b", (H,), "bias"),
+                  ("nsp.w", (2, H), "matrix"), ("nsp.b", (2,), "bias")]
     return specs
 
 
@@ -198,6 +205,8 @@ def trainable_names(shape: ModelShape, frozen_layers: int, trainable_layers: int
     for i in range(frozen_layers // g, (frozen_layers + trainable_layers) // g):
         names += [f"layer{i}.{t}" for t in LAYER_TENSORS]
     names += ["head.wt", "head.bt", "head.ln_g", "head.ln_b", "head.b_out"]
+    if shape.nsp:
+        names += ["pooler.w", "pooler.b", "nsp.w", "nsp.b"]
     return names
 
 
@@ -283,4 +292,6 @@ def make_batch(shape: ModelShape, batch: int, seq: int, seed: int = 1, ragged: b
         "labels": labels.astype(np.int32),
         "masked_positions": flat_pos,
         "lengths": lengths.astype(np.int32),
+        # next-sentence label of each sequence (1 = the second segment is a random one), a seeded coin
+        "nsp_labels": (rand_uniform(seed, _STREAM_NSP, np.arange(batch, dtype=np.uint64)) < 0.5).astype(np.int32),
     }
