@@ -98,6 +98,9 @@ def extra_workloads(torch, binding, synth, steps):
     res = {}
     cases = [
         ("base_final_64x128", synth.bert_base_shape(12), 64, 128, [(9, 3, False)], binding.adam(lr=1e-4)),
+        # the paper's own training settings (Section 4.1): both objectives of BERT and its dropout of 0.1
+        ("base_final_64x128_nsp_dropout", synth.ModelShape(n_layers=12, hidden=768, n_heads=12, ffn=3072, vocab=30522,
+                                                           nsp=True), 64, 128, [(9, 3, False)], binding.adam(lr=1e-4), 0.1),
         ("base_final_16x512", synth.bert_base_shape(12), 16, 512, [(9, 3, False)], binding.adam(lr=1e-4)),
         # grouped variant (Section 3.3): 12 layers in 4 groups of 3 that share their parameters
         ("base_grouped_4x3_final_64x128", synth.ModelShape(n_layers=12, hidden=768, n_heads=12, ffn=3072, vocab=30522,
@@ -106,7 +109,8 @@ def extra_workloads(torch, binding, synth, steps):
         ("large_sweep_32x512_lamb", synth.bert_large_shape(24), 32, 512,
          [(0, 6, True), (6, 6, False), (12, 6, False), (18, 6, False)], binding.lamb()),
     ]
-    for name, shape, B, S, stages, opt in cases:
+    for name, shape, B, S, stages, opt, *rest in cases:
+        dropout = rest[0] if rest else 0.0
         W = synth.make_weights(shape, seed=0)
         batches = [synth.make_batch(shape, B, S, seed=1 + i) for i in range(2)]
         n_pred = max(len(b["masked_positions"]) for b in batches)
@@ -117,11 +121,11 @@ def extra_workloads(torch, binding, synth, steps):
         tokens = B * S
         entry = {"tokens_per_step": tokens, "stages": []}
         for f, k, emb in stages:
-            sec, loss = time_steps(torch, m, cb, f, k, emb, opt, steps, 2)
+            sec, loss = time_steps(torch, m, cb, f, k, emb, opt, steps, 2, dropout=dropout)
             prof = profile_steps(m, cb, f, k, emb, opt, min(steps, 4))
             entry["stages"].append({"frozen": f, "trainable": k, "train_embeddings": emb, "ms_per_step": round(sec * 1e3, 4),
                                     "tokens_per_s": round(tokens / sec, 1), **gemm_roofline(prof)})
-        sec_full, _ = time_steps(torch, m, cb, 0, shape.n_layers, True, opt, steps, 2)
+        sec_full, _ = time_steps(torch, m, cb, 0, shape.n_layers, True, opt, steps, 2, dropout=dropout)
         entry["full_step_ms"] = round(sec_full * 1e3, 4)
         entry["full_tokens_per_s"] = round(tokens / sec_full, 1)
         entry["speedup_last_stage_vs_full"] = round(sec_full / (entry["stages"][-1]["ms_per_step"] * 1e-3), 3)

@@ -65,6 +65,11 @@ typedef struct {
                           ("layer g" in the tensor table is the set of group g; there are n_layers_max / n sets),
                           the gradients of a set are the sums over its n applications, and the layer counts of
                           mslt_stage_step / mslt_train_step / mslt_grow must be whole groups */
+  int with_nsp;         /* 1: the model also has BERT's next-sentence head (Section 4.1 keeps both objectives):
+                          pooler.w [H,H], pooler.b [H] (dense + tanh on the first token of every sequence) and
+                          nsp.w [2,H], nsp.b [2] after the masked-LM head in the tensor table; they train in every
+                          stage, the step's loss is the sum of the two mean cross-entropies, and every step's batch
+                          must bring nsp_labels */
 } mslt_config;
 
 /* One masked-LM batch.  DEVICE pointers to int32 arrays of batch*seq entries, row-major
@@ -77,6 +82,7 @@ typedef struct {
   const int32_t* labels;
   int batch;
   int seq;
+  const int32_t* nsp_labels; /* DEVICE, [batch], 0 or 1; read only by a model with with_nsp = 1, else may be null */
 } mslt_batch;
 
 /* Optimizer of the update (Section 4.1: LAMB, lr 0.00088; Section 5 also names Adam).

@@ -34,12 +34,13 @@ class Config(C.Structure):
     _fields_ = [("n_layers_max", C.c_int), ("hidden", C.c_int), ("n_heads", C.c_int), ("ffn", C.c_int),
                 ("vocab", C.c_int), ("max_pos", C.c_int), ("type_vocab", C.c_int), ("max_batch", C.c_int),
                 ("max_seq", C.c_int), ("max_predictions", C.c_int), ("precision", C.c_int),
-                ("ln_eps", C.c_float), ("mask_bias", C.c_float), ("layers_per_group", C.c_int)]
+                ("ln_eps", C.c_float), ("mask_bias", C.c_float), ("layers_per_group", C.c_int),
+                ("with_nsp", C.c_int)]
 
 
 class Batch(C.Structure):
     _fields_ = [("input_ids", C.c_void_p), ("token_type_ids", C.c_void_p), ("attn_mask", C.c_void_p),
-                ("labels", C.c_void_p), ("batch", C.c_int), ("seq", C.c_int)]
+                ("labels", C.c_void_p), ("batch", C.c_int), ("seq", C.c_int), ("nsp_labels", C.c_void_p)]
 
 
 class Opt(C.Structure):
@@ -107,7 +108,7 @@ def make_config(shape, max_batch, max_seq, precision, max_predictions=0) -> Conf
     """Config from a synth.ModelShape-like object (n_layers, hidden, n_heads, ffn, vocab, ...)."""
     return Config(shape.n_layers, shape.hidden, shape.n_heads, shape.ffn, shape.vocab, shape.max_pos,
                   shape.type_vocab, max_batch, max_seq, max_predictions, precision, shape.ln_eps, shape.mask_bias,
-                  getattr(shape, "layers_per_group", 1))
+                  getattr(shape, "layers_per_group", 1), int(getattr(shape, "nsp", False)))
 
 
 def mslt_query_sizes(cfg: Config):
@@ -169,8 +170,12 @@ class Model:
         B, S = batch["input_ids"].shape
         keep = [torch.as_tensor(np.ascontiguousarray(batch[k], dtype=np.int32)).to(self.device)
                 for k in ("input_ids", "token_type_ids", "attn_mask", "labels")]
+        nsp = None
+        if "nsp_labels" in batch:
+            nsp = torch.as_tensor(np.ascontiguousarray(batch["nsp_labels"], dtype=np.int32)).to(self.device)
         torch.cuda.synchronize(self.device)
-        cb = Batch(*[C.c_void_p(t.data_ptr()) for t in keep], B, S)
+        cb = Batch(*[C.c_void_p(t.data_ptr()) for t in keep], B, S, C.c_void_p(nsp.data_ptr()) if nsp is not None else None)
+        keep.append(nsp)
         cb._keep = keep   # keep the tensors alive as long as the struct
         return cb
 

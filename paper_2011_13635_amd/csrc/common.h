@@ -195,7 +195,7 @@ hipError_t widen_to_f32(int dtype, const void* src, float* dst, size_t n, hipStr
 // pos/lab hold at most `cap` entries; counters[0] still reports the true count.
 hipError_t batch_scan(const int32_t* ids, const int32_t* tt, const int32_t* am, const int32_t* labels, int T, int vocab,
                       int type_vocab, int cap, int32_t* pos, int32_t* lab, int32_t* inv, int32_t* counters,
-                      hipStream_t s);
+                      int cls_every, const int32_t* nsp_labels, int n_seq, hipStream_t s);
 
 struct LnStash {
   void* xhat = nullptr;   // [rows, H] activation type, or null
@@ -240,8 +240,16 @@ hipError_t scatter_rows(int dtype, const void* dxm, const int32_t* inv, int rows
                         hipStream_t s);
 // cross-entropy over fp32 logits [Mpad, ldz]: writes dZ (activation type, zero in padded rows and
 // columns), per-row loss and lse; loss_out = mean over M rows in fixed order.
-hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mpad, int V, void* dz,
-                      float* row_loss, float* lse, float* loss_out, hipStream_t s);
+// (rows whose label is negative are only there for the next-sentence head: zero dZ, no loss; Mn = rows with a label)
+hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mn, int Mpad, int V,
+                      void* dz, float* row_loss, float* lse, float* loss_out, hipStream_t s);
+// next-sentence head: small row-wise pieces around its three products
+hipError_t gather_first_tokens(int dtype, const void* x, int S, int H, int n_seq, void* out, hipStream_t s);
+hipError_t tanh_inplace(int dtype, void* u, size_t n, hipStream_t s);
+hipError_t tanh_bwd(int dtype, const void* dp, const void* p, void* du, size_t n, hipStream_t s);
+hipError_t nsp_ce(int dtype, const float* z, const int32_t* y, int n_seq, void* dz, float* loss, hipStream_t s);
+hipError_t add_first_token_rows(int dtype, const void* dxc, const int32_t* inv, int S, int H, int n_seq, void* dxm,
+                                hipStream_t s);
 
 // embedding backward (first stage / retraining only): adds the gather contribution into gword,
 // writes gpos (all gpos_rows rows) and gtype.  rank/order hold T ints, cnt/start round_up(vocab,4)

@@ -36,6 +36,8 @@ static inline size_t rup(size_t x, size_t a) { return (x + a - 1) / a * a; }
 enum { T_WORD = 0, T_POS, T_TYPE, T_ELN_G, T_ELN_B, N_EMB };
 enum { L_WQ = 0, L_WK, L_WV, L_BQ, L_BK, L_BV, L_WO, L_BO, L_LN1G, L_LN1B, L_W1, L_B1, L_W2, L_B2, L_LN2G, L_LN2B, N_LAYER_T };
 enum { H_WT = 0, H_BT, H_LNG, H_LNB, H_BOUT, N_HEAD };
+// next-sentence head, after the masked-LM head when the model has one
+enum { P_W = N_HEAD, P_B, C_W, C_B, N_HEAD_NSP };
 
 // Optional per-kernel-class timing with HIP events on the model's stream (off by default).
 enum ProfClass { PC_GEMM_NT = 0, PC_GEMM_NN, PC_GEMM_TN, PC_GEMM_SIMT, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD, PC_LN_BWD,
@@ -74,6 +76,9 @@ struct mslt_model {
   bool mfma;        // bf16 MFMA GEMMs with padded row counts
   hipStream_t stream;
   int H, F, V, Vp, nh, dh, L, Tp, Mp, cap;
+  int nsp;          // next-sentence head present (pooler + two-way classifier)
+  void *n_xc, *n_p, *n_dz, *n_dp, *n_du, *n_dx;   // its batch-many rows: first tokens, pooled, and gradients
+  float* n_z;       // its logits [max_batch, 2]
   int lpg, Lp;      // layers per parameter-sharing group (1: every layer has its own set), number of sets = L / lpg
   int acc_now;      // the layer whose backward is being queued adds to its set's gradients (not the first of its group)
   std::vector<mslt_tensor_desc> table;
@@ -173,6 +178,12 @@ static void build_table(mslt_model* m) {
   add_tensor(m, "head.ln_g", -2, H, 1, 0, 0, true, off);
   add_tensor(m, "head.ln_b", -2, H, 1, 0, 0, true, off);
   add_tensor(m, "head.b_out", -2, V, 1, 0, (size_t)Vp, true, off);
+  if (m->nsp) {
+    add_tensor(m, "pooler.w", -2, H, H, 1, 0, true, off);
+    add_tensor(m, "pooler.b", -2, H, 1, 0, 0, true, off);
+    add_tensor(m, "nsp.w", -2, 2, H, 1, 0, true, off);
+    add_tensor(m, "nsp.b", -2, 2, 1, 0, 0, true, off);
+  }
   m->arena_elems = rup(off, 64);
   m->packed_count = 0;
   for (auto& d : m->table) m->packed_count += d.count;
@@ -264,6 +275,13 @@ static size_t carve(mslt_model* m, char* base) {
   m->c_dz2m = b.take<void>(MH); m->c_dz1m = b.take<void>(MH);
   m->rstd_t = b.take<float>(Mp * 4); m->logits = b.take<float>(Mp * Vp * 4); m->row_loss = b.take<float>(Mp * 4);
   m->lse_t = b.take<float>(Mp * 4); m->loss = b.take<float>(64);
+  {
+    const size_t BH = rup((size_t)m->cfg.max_batch, 128) * H * e;
+    m->n_xc = b.take<void>(BH); m->n_p = b.take<void>(BH); m->n_dp = b.take<void>(BH); m->n_du = b.take<void>(BH);
+    m->n_dx = b.take<void>(BH);
+    m->n_dz = b.take<void>(rup((size_t)m->cfg.max_batch, 128) * 2 * e);
+    m->n_z = b.take<float>(rup((size_t)m->cfg.max_batch, 128) * 2 * 4);
+  }
   // reduction scratch: the largest of LayerNorm-backward partials, column-sum partials, token-type partials
   size_t rows = Tp > Mp ? Tp : Mp;
   size_t maxN = 3 * H > F ? 3 * H : F;
@@ -320,6 +338,7 @@ static void setup_dims(mslt_model* m, const mslt_config* cfg) {
   m->esz = cfg->precision ? 2 : 4;
   m->H = cfg->hidden; m->F = cfg->ffn; m->V = cfg->vocab; m->nh = cfg->n_heads; m->dh = cfg->hidden / cfg->n_heads;
   m->L = cfg->n_layers_max;
+  m->nsp = cfg->with_nsp != 0;
   m->lpg = cfg->layers_per_group > 1 ? cfg->layers_per_group : 1;
   m->Lp = m->L / m->lpg;
   m->Vp = (int)rup(cfg->vocab, 128);
@@ -764,6 +783,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
     return fail(MSLT_ERR_ARG, "stage_step: frozen and trainable layer counts must be whole groups of %d layers", m->lpg);
   if (!bt->input_ids || !bt->token_type_ids || !bt->attn_mask || !bt->labels)
     return fail(MSLT_ERR_ARG, "stage_step: null batch pointer");
+  if (m->nsp && !bt->nsp_labels) return fail(MSLT_ERR_ARG, "stage_step: the model has a next-sentence head but nsp_labels is null");
   if (bt->batch < 1 || bt->batch > m->cfg.max_batch || bt->seq < 1 || bt->seq > m->cfg.max_seq)
     return fail(MSLT_ERR_ARG, "stage_step: batch %dx%d outside 1..%dx1..%d", bt->batch, bt->seq, m->cfg.max_batch,
                 m->cfg.max_seq);
@@ -775,8 +795,8 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
 
   // S0: batch check and compaction of the predicted positions (only index scratch is written)
   HIP_TRY(batch_scan(bt->input_ids, bt->token_type_ids, bt->attn_mask, bt->labels, T, m->V, m->cfg.type_vocab, m->cap,
-                     m->pos, m->lab, m->inv, m->counters, s));
-  HIP_TRY(hipMemcpyAsync(m->h_counters, m->counters, 8, hipMemcpyDeviceToHost, s));
+                     m->pos, m->lab, m->inv, m->counters, m->nsp ? S : 0, m->nsp ? bt->nsp_labels : nullptr, B, s));
+  HIP_TRY(hipMemcpyAsync(m->h_counters, m->counters, 12, hipMemcpyDeviceToHost, s));
   HIP_TRY(hipEventRecord(m->ev_scan, s));
   const int Tr = m->mfma ? (int)rup(T, 128) : T;
   const int Vr = m->mfma ? m->Vp : m->V;
@@ -807,11 +827,14 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
     x = m->stash[l].xout;
   }
   HIP_TRY(hipEventSynchronize(m->ev_scan));
-  const int M = m->h_counters[0], bad = m->h_counters[1];
-  if (bad || M < 1 || M > m->cap) {
+  // M: compacted rows (predicted positions, plus every first token when there is a next-sentence head);
+  // Mn: those of them that carry a masked-LM label
+  const int M = m->h_counters[0], bad = m->h_counters[1], Mn = m->h_counters[2];
+  if (bad || Mn < 1 || M > m->cap) {
     HIP_TRY(hipStreamSynchronize(s));   // let the queued forward drain before reporting
-    if (bad) return fail(MSLT_ERR_DATA, "stage_step: batch content out of range (bits %d: 1 id, 2 type, 4 label, 8 mask)", bad);
-    if (M < 1) return fail(MSLT_ERR_DATA, "stage_step: no predicted position in the batch");
+    if (bad)
+      return fail(MSLT_ERR_DATA, "stage_step: batch content out of range (bits %d: 1 id, 2 type, 4 label, 8 mask, 16 nsp label)", bad);
+    if (Mn < 1) return fail(MSLT_ERR_DATA, "stage_step: no predicted position in the batch");
     return fail(MSLT_ERR_DATA, "stage_step: %d predicted positions exceed max_predictions %d", M, m->cap);
   }
   const int Mr = m->mfma ? (int)rup(M, 128) : M;
@@ -828,7 +851,16 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   RC(linear_fwd(m, m->hm, Mr, H, Wg(m, T_WORD), Vr, Wf(m, th + H_BOUT), m->logits, 1, m->Vp, EPI_NONE, nullptr));
   {
     ProfScope ps(m, PC_CE, 0.0, (double)M * m->V * 4.0 + (double)Mr * m->Vp * m->esz);
-    HIP_TRY(ce_fwd_bwd(m->dtype, m->logits, m->Vp, m->lab, M, Mr, m->V, m->dz, m->row_loss, m->lse_t, m->loss, s));
+    HIP_TRY(ce_fwd_bwd(m->dtype, m->logits, m->Vp, m->lab, M, Mn, Mr, m->V, m->dz, m->row_loss, m->lse_t, m->loss, s));
+  }
+  if (m->nsp) {
+    // next-sentence head (the second objective is added to the loss): pooled = tanh(X_first Wp^T + bp),
+    // logits = pooled Wc^T + bc, mean two-way cross-entropy over the batch
+    HIP_TRY(gather_first_tokens(m->dtype, x, S, H, B, m->n_xc, s));
+    RC(linear_fwd(m, m->n_xc, B, H, Wg(m, th + P_W), H, Wf(m, th + P_B), m->n_p, 0, H, EPI_NONE, nullptr));
+    HIP_TRY(tanh_inplace(m->dtype, m->n_p, (size_t)B * H, s));
+    RC(linear_fwd(m, m->n_p, B, H, Wg(m, th + C_W), 2, Wf(m, th + C_B), m->n_z, 1, 2, EPI_NONE, nullptr));
+    HIP_TRY(nsp_ce(m->dtype, m->n_z, bt->nsp_labels, B, m->n_dz, m->loss, s));
   }
   HIP_TRY(hipMemcpyAsync(m->h_loss, m->loss, 4, hipMemcpyDeviceToHost, s));
   // S7: head backward
@@ -845,6 +877,17 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   RC(linear_bwd_weight(m, m->d_ut, Mr, H, H, m->xm, H, Gf(m, th + H_WT)));
   RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT)));
   RC(linear_bwd_input(m, m->d_ut, Mr, H, H, Wg(m, th + H_WT), H, m->d_xm, EPI_NONE, nullptr));
+  if (m->nsp) {
+    // backward of the next-sentence head; its input gradient joins the compacted rows of the first tokens
+    RC(linear_bwd_weight(m, m->n_dz, B, 2, 2, m->n_p, H, Gf(m, th + C_W)));
+    RC(bias_grad(m, m->n_dz, 2, B, 2, Gf(m, th + C_B)));
+    RC(linear_bwd_input(m, m->n_dz, B, 2, 2, Wg(m, th + C_W), H, m->n_dp, EPI_NONE, nullptr, false));
+    HIP_TRY(tanh_bwd(m->dtype, m->n_dp, m->n_p, m->n_du, (size_t)B * H, s));
+    RC(linear_bwd_weight(m, m->n_du, B, H, H, m->n_xc, H, Gf(m, th + P_W)));
+    RC(bias_grad(m, m->n_du, H, B, H, Gf(m, th + P_B)));
+    RC(linear_bwd_input(m, m->n_du, B, H, H, Wg(m, th + P_W), H, m->n_dx, EPI_NONE, nullptr, false));
+    HIP_TRY(add_first_token_rows(m->dtype, m->n_dx, m->inv, S, H, B, m->d_xm, s));
+  }
   RC(side_join(m));      // the top layer's backward reuses the head buffers
   // S8/S9: trainable layers backward, top down.  The top layer works on the compacted predicted rows
   // and scatters inside; the layers below get dense gradients.
@@ -893,7 +936,7 @@ static int trainable_ranges(const mslt_model* m, int (*r)[2]) {
   int n = 0;
   if (m->last_emb) { r[n][0] = 0; r[n][1] = N_EMB; ++n; }
   r[n][0] = t_layer(m->last_f / m->lpg, 0); r[n][1] = t_layer((m->last_f + m->last_k) / m->lpg, 0); ++n;
-  r[n][0] = t_head(m, 0); r[n][1] = t_head(m, 0) + N_HEAD; ++n;
+  r[n][0] = t_head(m, 0); r[n][1] = t_head(m, 0) + (m->nsp ? N_HEAD_NSP : N_HEAD); ++n;
   // merge adjacent ranges
   int out = 0;
   for (int i = 0; i < n; ++i) {
@@ -996,7 +1039,10 @@ extern "C" int mslt_debug_masked(const mslt_model* m, int32_t* pos_out, int32_t*
   HIP_TRY(hipMemcpyAsync(pos_out, m->pos, (size_t)m->last_M * 4, hipMemcpyDeviceToHost, m->stream));
   HIP_TRY(hipMemcpyAsync(label_out, m->lab, (size_t)m->last_M * 4, hipMemcpyDeviceToHost, m->stream));
   HIP_TRY(hipStreamSynchronize(m->stream));
-  *m_out = m->last_M;
+  int n = 0;               // rows that are only there for the next-sentence head carry no label: leave them out
+  for (int i = 0; i < m->last_M; ++i)
+    if (label_out[i] >= 0) { pos_out[n] = pos_out[i]; label_out[n] = label_out[i]; ++n; }
+  *m_out = n;
   return MSLT_OK;
 }
 

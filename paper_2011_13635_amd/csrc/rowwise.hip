@@ -96,7 +96,11 @@ hipError_t widen_to_f32(int dtype, const void* src, float* dst, size_t n, hipStr
 __global__ void __launch_bounds__(1024) k_batch_scan(const int32_t* __restrict__ ids, const int32_t* __restrict__ tt,
                                                      const int32_t* __restrict__ am, const int32_t* __restrict__ labels,
                                                      int T, int vocab, int type_vocab, int cap, int32_t* pos,
-                                                     int32_t* lab, int32_t* inv, int32_t* counters) {
+                                                     int32_t* lab, int32_t* inv, int32_t* counters, int cls_every,
+                                                     const int32_t* __restrict__ nsp_labels, int n_seq) {
+  // cls_every > 0 (next-sentence head on): the first token of every sequence (t % cls_every == 0)
+  // joins the compacted rows even without a label, because the classifier sends a gradient there;
+  // its entry in lab stays -100.  counters: [0] rows, [1] error bits, [2] rows with a label.
   // One workgroup walks the tokens in chunks of 1024 (coalesced); inside a chunk the rank of a
   // predicted position is a wavefront ballot prefix plus the totals of the wavefronts before it.
   __shared__ int wtot[16];
@@ -104,7 +108,12 @@ __global__ void __launch_bounds__(1024) k_batch_scan(const int32_t* __restrict__
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   if (tid == 0) bad_all = 0;
   __syncthreads();
-  int base = 0, bad = 0;
+  int base = 0, bad = 0, labelled = 0;
+  if (nsp_labels != nullptr)
+    for (int i = tid; i < n_seq; i += 1024) {
+      int y = nsp_labels[i];
+      if (y != 0 && y != 1) bad |= 16;
+    }
   for (int c0 = 0; c0 < T; c0 += 1024) {
     const int t = c0 + tid;
     const bool in = t < T;
@@ -118,8 +127,10 @@ __global__ void __launch_bounds__(1024) k_batch_scan(const int32_t* __restrict__
       if (a != 0 && a != 1) bad |= 8;
       l = labels[t];
     }
-    const bool v = in && l != -100;
-    if (v && (l < 0 || l >= vocab)) bad |= 4;
+    const bool has_label = in && l != -100;
+    if (has_label && (l < 0 || l >= vocab)) bad |= 4;
+    const bool v = has_label || (in && cls_every > 0 && t % cls_every == 0);
+    labelled += __popcll(__ballot(has_label));       // the same count in every lane of the wavefront
     const unsigned long long mask = __ballot(v);
     const int within = __popcll(mask & ((1ull << lane) - 1ull));
     if (lane == 0) wtot[w] = __popcll(mask);
@@ -145,16 +156,21 @@ __global__ void __launch_bounds__(1024) k_batch_scan(const int32_t* __restrict__
     __syncthreads();
   }
   if (bad) atomicOr(&bad_all, bad);
+  if (lane == 0) wtot[w] = labelled;
   __syncthreads();
   if (tid == 0) {
+    int n = 0;
+    for (int j = 0; j < 16; ++j) n += wtot[j];
     counters[0] = base;
     counters[1] = bad_all;
+    counters[2] = n;
   }
 }
 hipError_t batch_scan(const int32_t* ids, const int32_t* tt, const int32_t* am, const int32_t* labels, int T, int vocab,
                       int type_vocab, int cap, int32_t* pos, int32_t* lab, int32_t* inv, int32_t* counters,
-                      hipStream_t s) {
-  k_batch_scan<<<dim3(1), dim3(1024), 0, s>>>(ids, tt, am, labels, T, vocab, type_vocab, cap, pos, lab, inv, counters);
+                      int cls_every, const int32_t* nsp_labels, int n_seq, hipStream_t s) {
+  k_batch_scan<<<dim3(1), dim3(1024), 0, s>>>(ids, tt, am, labels, T, vocab, type_vocab, cap, pos, lab, inv, counters,
+                                              cls_every, nsp_labels, n_seq);
   return hipGetLastError();
 }
 
@@ -655,13 +671,14 @@ __device__ inline float block_reduce_max_256(float v, float* sh) {
 
 template <typename AT>
 __global__ void __launch_bounds__(256) k_ce(const float* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
-                                            int M, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
+                                            int M, int Mn, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
                                             float* __restrict__ lse_out) {
   __shared__ float sh[4];
   int j = blockIdx.x;
   AT* d = dz + (size_t)j * ldz;
-  if (j >= M) {
+  if (j >= M || lab[j] < 0) {      // padding row, or a row that is only there for the next-sentence head
     for (int c = threadIdx.x; c < ldz; c += 256) stf(d + c, 0.f);
+    if (j < M && threadIdx.x == 0) { row_loss[j] = 0.f; lse_out[j] = 0.f; }
     return;
   }
   const float* z = logits + (size_t)j * ldz;
@@ -673,7 +690,7 @@ __global__ void __launch_bounds__(256) k_ce(const float* __restrict__ logits, in
   se = block_reduce_sum_256(se, sh);
   float lse = mx + __logf(se);
   int y = lab[j];
-  float invM = 1.0f / (float)M;
+  float invM = 1.0f / (float)Mn;
   for (int c = threadIdx.x; c < ldz; c += 256) {
     float v = 0.f;
     if (c < V) v = (__expf(z[c] - lse) - (c == y ? 1.0f : 0.0f)) * invM;
@@ -688,14 +705,15 @@ __global__ void __launch_bounds__(256) k_ce(const float* __restrict__ logits, in
 // logits and one write of dZ per row, 1024 threads per row.
 template <typename AT>
 __global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
-                                                 int M, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
+                                                 int M, int Mn, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
                                                  float* __restrict__ lse_out) {
   extern __shared__ __attribute__((aligned(16))) float row[];
   __shared__ float sh[16];
   const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   AT* d = dz + (size_t)j * ldz;
-  if (j >= M) {
+  if (j >= M || lab[j] < 0) {      // padding row, or a row that is only there for the next-sentence head
     for (int c = tid * 4; c < ldz; c += 4096) store4(d + c, make_float4(0, 0, 0, 0));
+    if (j < M && tid == 0) { row_loss[j] = 0.f; lse_out[j] = 0.f; }
     return;
   }
   const float* z = logits + (size_t)j * ldz;
@@ -728,7 +746,7 @@ __global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logit
   for (int w = 0; w < 16; ++w) se += sh[w];
   const float lse = mx + __logf(se);
   const int y = lab[j];
-  const float invM = 1.0f / (float)M;
+  const float invM = 1.0f / (float)Mn;
   for (int c = tid * 4; c < ldz; c += 4096) {
     float o[4];
 #pragma unroll
@@ -743,7 +761,7 @@ __global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logit
     lse_out[j] = lse;
   }
 }
-__global__ void __launch_bounds__(256) k_mean_rows(const float* __restrict__ v, int M, float* __restrict__ out) {
+__global__ void __launch_bounds__(256) k_mean_rows(const float* __restrict__ v, int M, int Mn, float* __restrict__ out) {
   __shared__ float sh[256];
   float acc = 0.f;
   for (int i = threadIdx.x; i < M; i += 256) acc += v[i];
@@ -753,10 +771,10 @@ __global__ void __launch_bounds__(256) k_mean_rows(const float* __restrict__ v, 
     if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
     __syncthreads();
   }
-  if (threadIdx.x == 0) *out = sh[0] / (float)M;
+  if (threadIdx.x == 0) *out = sh[0] / (float)Mn;     // mean over the rows that carry a label
 }
-hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mpad, int V, void* dz,
-                      float* row_loss, float* lse, float* loss_out, hipStream_t s) {
+hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mn, int Mpad, int V,
+                      void* dz, float* row_loss, float* lse, float* loss_out, hipStream_t s) {
   const size_t row_bytes = (size_t)V * 4;
   hipError_t e;
   if (row_bytes <= 150 * 1024 && ldz % 4 == 0) {
@@ -769,17 +787,17 @@ hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* la
       attr_set = true;
     }
     if (dtype == 0)
-      k_ce_lds<float><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, V, (float*)dz, row_loss, lse);
+      k_ce_lds<float><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, Mn, V, (float*)dz, row_loss, lse);
     else
-      k_ce_lds<bf16><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, V, (bf16*)dz, row_loss, lse);
+      k_ce_lds<bf16><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, Mn, V, (bf16*)dz, row_loss, lse);
   } else if (dtype == 0) {
-    k_ce<float><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, V, (float*)dz, row_loss, lse);
+    k_ce<float><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, Mn, V, (float*)dz, row_loss, lse);
   } else {
-    k_ce<bf16><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, V, (bf16*)dz, row_loss, lse);
+    k_ce<bf16><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, Mn, V, (bf16*)dz, row_loss, lse);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  k_mean_rows<<<dim3(1), dim3(256), 0, s>>>(row_loss, M, loss_out);
+  k_mean_rows<<<dim3(1), dim3(256), 0, s>>>(row_loss, M, Mn, loss_out);
   return hipGetLastError();
 }
 
@@ -1094,5 +1112,93 @@ hipError_t optimizer_step(const OptHyper& h, const OptTensor* tensors, const int
   k_lamb_pass2<<<dim3(n_chunks), dim3(256), 0, s>>>(h, tensors, tsteps, chunk_tensor, chunk0, w, m, v, shadow, ratio);
   return hipGetLastError();
 }
+
+// ---- next-sentence head (pooler + two-way classifier on the first token of every sequence) ----
+// These work on batch-many rows: a few thousand elements, small launches.
+template <typename AT>
+__global__ void k_gather_first_tokens(const AT* __restrict__ x, int S, int H, AT* __restrict__ out) {
+  int b = blockIdx.x;
+  for (int c = threadIdx.x; c < H; c += blockDim.x) out[(size_t)b * H + c] = x[(size_t)b * S * H + c];
+}
+template <typename AT>
+__global__ void k_tanh_inplace(AT* __restrict__ u, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) stf(u + i, tanhf(ldf(u + i)));
+}
+// du = dp * (1 - p^2)
+template <typename AT>
+__global__ void k_tanh_bwd(const AT* __restrict__ dp, const AT* __restrict__ p, AT* __restrict__ du, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    float t = ldf(p + i);
+    stf(du + i, ldf(dp + i) * (1.0f - t * t));
+  }
+}
+// two-way cross-entropy: dz = (softmax(z) - onehot) / n_seq, *loss += mean loss (one workgroup)
+template <typename AT>
+__global__ void __launch_bounds__(256) k_nsp_ce(const float* __restrict__ z, const int32_t* __restrict__ y, int n_seq,
+                                                AT* __restrict__ dz, float* __restrict__ loss) {
+  __shared__ float sh[256];
+  float acc = 0.f;
+  const float inv = 1.0f / (float)n_seq;
+  for (int b = threadIdx.x; b < n_seq; b += 256) {
+    float z0 = z[2 * b], z1 = z[2 * b + 1];
+    float mx = fmaxf(z0, z1);
+    float lse = mx + __logf(__expf(z0 - mx) + __expf(z1 - mx));
+    int yy = y[b] != 0;
+    acc += lse - (yy ? z1 : z0);
+    stf(dz + 2 * b, (__expf(z0 - lse) - (yy ? 0.f : 1.f)) * inv);
+    stf(dz + 2 * b + 1, (__expf(z1 - lse) - (yy ? 1.f : 0.f)) * inv);
+  }
+  sh[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss += sh[0] * inv;
+}
+// dxm[inv[b*S], :] += dxc[b, :]: the classifier's gradient joins the compacted rows of the last layer's output
+template <typename AT>
+__global__ void k_add_first_token_rows(const AT* __restrict__ dxc, const int32_t* __restrict__ inv, int S, int H,
+                                       AT* __restrict__ dxm) {
+  int b = blockIdx.x;
+  int j = inv[(size_t)b * S];
+  if (j < 0) return;
+  for (int c = threadIdx.x; c < H; c += blockDim.x) {
+    AT* d = dxm + (size_t)j * H + c;
+    stf(d, ldf(d) + ldf(dxc + (size_t)b * H + c));
+  }
+}
+#define MSLT_BY_DTYPE(CALL_F, CALL_B) do { if (dtype == 0) { CALL_F; } else { CALL_B; } } while (0)
+hipError_t gather_first_tokens(int dtype, const void* x, int S, int H, int n_seq, void* out, hipStream_t s) {
+  MSLT_BY_DTYPE((k_gather_first_tokens<float><<<dim3(n_seq), dim3(256), 0, s>>>((const float*)x, S, H, (float*)out)),
+                (k_gather_first_tokens<bf16><<<dim3(n_seq), dim3(256), 0, s>>>((const bf16*)x, S, H, (bf16*)out)));
+  return hipGetLastError();
+}
+hipError_t tanh_inplace(int dtype, void* u, size_t n, hipStream_t s) {
+  dim3 grid((unsigned)((n + 255) / 256));
+  MSLT_BY_DTYPE((k_tanh_inplace<float><<<grid, dim3(256), 0, s>>>((float*)u, n)),
+                (k_tanh_inplace<bf16><<<grid, dim3(256), 0, s>>>((bf16*)u, n)));
+  return hipGetLastError();
+}
+hipError_t tanh_bwd(int dtype, const void* dp, const void* p, void* du, size_t n, hipStream_t s) {
+  dim3 grid((unsigned)((n + 255) / 256));
+  MSLT_BY_DTYPE((k_tanh_bwd<float><<<grid, dim3(256), 0, s>>>((const float*)dp, (const float*)p, (float*)du, n)),
+                (k_tanh_bwd<bf16><<<grid, dim3(256), 0, s>>>((const bf16*)dp, (const bf16*)p, (bf16*)du, n)));
+  return hipGetLastError();
+}
+hipError_t nsp_ce(int dtype, const float* z, const int32_t* y, int n_seq, void* dz, float* loss, hipStream_t s) {
+  MSLT_BY_DTYPE((k_nsp_ce<float><<<dim3(1), dim3(256), 0, s>>>(z, y, n_seq, (float*)dz, loss)),
+                (k_nsp_ce<bf16><<<dim3(1), dim3(256), 0, s>>>(z, y, n_seq, (bf16*)dz, loss)));
+  return hipGetLastError();
+}
+hipError_t add_first_token_rows(int dtype, const void* dxc, const int32_t* inv, int S, int H, int n_seq, void* dxm,
+                                hipStream_t s) {
+  MSLT_BY_DTYPE((k_add_first_token_rows<float><<<dim3(n_seq), dim3(256), 0, s>>>((const float*)dxc, inv, S, H, (float*)dxm)),
+                (k_add_first_token_rows<bf16><<<dim3(n_seq), dim3(256), 0, s>>>((const bf16*)dxc, inv, S, H, (bf16*)dxm)));
+  return hipGetLastError();
+}
+#undef MSLT_BY_DTYPE
 
 }  // namespace mslt
