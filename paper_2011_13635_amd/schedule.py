@@ -11,7 +11,9 @@ learning rate; every step runs in the library (mslt_train_step, mslt_grow).
 """
 from __future__ import annotations
 
-from dataclasses import dataclass
+import inspect
+import math
+from dataclasses import dataclass, replace
 from typing import Callable, List, Optional
 
 from . import binding
@@ -27,6 +29,7 @@ class Stage:
     steps: int
     lr: float
     grow_first: int = 0     # layers to add (by copying the top ones) before the stage starts
+    seq_len: int = 0        # sequence length of this entry's batches; 0 = the run's ordinary length
 
 
 def mslt_schedule(n_layers: int, k: int, steps_per_stage: int, retrain_steps: int, lr: float,
@@ -47,6 +50,26 @@ def mslt_schedule(n_layers: int, k: int, steps_per_stage: int, retrain_steps: in
     return stages
 
 
+def long_sequence_tail(stages: List[Stage], fraction: float, seq_len: int) -> List[Stage]:
+    """The last `fraction` of all steps on sequences of length `seq_len` (Section 4.2: the last 10 % of the
+    steps use sequences of 512 so that the position embeddings beyond the ordinary length get trained).
+    Entries that straddle the boundary are split in two; a split-off second half does not grow again."""
+    total = sum(st.steps for st in stages)
+    tail = int(math.ceil(fraction * total))
+    out: List[Stage] = []
+    for st in reversed(stages):
+        if tail <= 0:
+            out.append(st)
+        elif st.steps <= tail:
+            out.append(replace(st, seq_len=seq_len))
+            tail -= st.steps
+        else:
+            out.append(replace(st, name=st.name + "-long", steps=tail, seq_len=seq_len, grow_first=0))
+            out.append(replace(st, steps=st.steps - tail))
+            tail = 0
+    return list(reversed(out))
+
+
 def warmup_factor(global_step: int, warmup_steps: int) -> float:
     """Linear warm-up over the first warmup_steps steps of the run (Section 4.2), 1 afterwards."""
     if warmup_steps <= 0 or global_step >= warmup_steps:
@@ -59,9 +82,11 @@ def run_schedule(model: "binding.Model", stages: List[Stage], next_batch: Callab
                  on_step: Optional[Callable[[Stage, int, float], None]] = None) -> List[List[float]]:
     """Runs the stages in order on `model`; returns the losses per stage.
 
-    next_batch(global_step) hands out a device batch (binding.Model.device_batch);
+    next_batch(global_step) or next_batch(global_step, stage) hands out a device batch
+    (binding.Model.device_batch), of length stage.seq_len where that is set;
     make_opt(lr) builds the optimizer settings for one step (binding.adam / binding.lamb).
     """
+    wants_stage = len(inspect.signature(next_batch).parameters) >= 2
     losses: List[List[float]] = []
     present = 0
     step = 0
@@ -72,7 +97,8 @@ def run_schedule(model: "binding.Model", stages: List[Stage], next_batch: Callab
         out = []
         for i in range(st.steps):
             lr = st.lr * warmup_factor(step, warmup_steps)
-            loss = model.mslt_train_step(st.frozen, st.trainable, st.train_embeddings, next_batch(step), make_opt(lr))
+            batch = next_batch(step, st) if wants_stage else next_batch(step)
+            loss = model.mslt_train_step(st.frozen, st.trainable, st.train_embeddings, batch, make_opt(lr))
             out.append(loss)
             if on_step is not None:
                 on_step(st, i, loss)

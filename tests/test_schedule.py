@@ -51,3 +51,20 @@ def test_harness_call_order():
         ("step", 0, 4, True, 4, 0.001),
     ]
     assert [len(x) for x in losses] == [2, 2, 1]
+
+
+def test_last_tenth_of_the_steps_on_long_sequences():
+    # Section 4.2: the last 10 % of the steps use sequences of 512
+    st = S.mslt_schedule(12, 4, 200_000, 200_000, 0.00088, 0.0001)
+    out = S.long_sequence_tail(st, 0.10, 512)
+    assert sum(s.steps for s in out) == 1_000_000
+    assert [(s.name, s.steps, s.seq_len) for s in out[-2:]] == [("retrain", 100_000, 0), ("retrain-long", 100_000, 512)]
+    assert [s.seq_len for s in out[:-1]] == [0] * 5 and out[-1].grow_first == 0
+    # a tail that swallows whole entries and splits an earlier one; growth happens once, before the first half
+    out = S.long_sequence_tail(S.mslt_schedule(4, 2, 10, 4, 0.01), 0.5, 64)
+    assert [(s.name, s.steps, s.seq_len, s.grow_first) for s in out] == [
+        ("stage1", 10, 0, 0), ("stage2", 2, 0, 2), ("stage2-long", 8, 64, 0), ("retrain", 4, 64, 0)]
+    rec = Recorder()
+    S.run_schedule(rec, out, next_batch=lambda g, stage: (g, stage.seq_len), make_opt=lambda lr: lr)
+    assert rec.calls[10] == ("grow", 2, 2)
+    assert [c[4] for c in rec.calls if c[0] == "step"][11:14] == [(11, 0), (12, 64), (13, 64)]
