@@ -117,11 +117,32 @@ __device__ __forceinline__ void store_acc_T(bf16* __restrict__ out, size_t ld, i
   }
 }
 
+__device__ __forceinline__ void store_acc_T_f32(float* __restrict__ out, size_t ld, int n, int half, const f32x16_t& a,
+                                                float scale) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
+    *reinterpret_cast<float4*>(out + (size_t)n * ld + 8 * g + 4 * half) =
+        make_float4(a[4 * g] * scale, a[4 * g + 1] * scale, a[4 * g + 2] * scale, a[4 * g + 3] * scale);
+}
+// 8 consecutive values of the context row for delta: from the fp32 copy when there is one
+__device__ __forceinline__ void load_ctx8(const bf16* __restrict__ ctx, const float* __restrict__ ctx32, size_t o,
+                                          float (&c)[8]) {
+  if (ctx32 != nullptr) {
+    float4 a = *reinterpret_cast<const float4*>(ctx32 + o), b = *reinterpret_cast<const float4*>(ctx32 + o + 4);
+    c[0] = a.x; c[1] = a.y; c[2] = a.z; c[3] = a.w; c[4] = b.x; c[5] = b.y; c[6] = b.z; c[7] = b.w;
+  } else {
+    bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(ctx + o);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = (float)v[i];
+  }
+}
+
 // ---- forward --------------------------------------------------------------------------------
 template <bool DROP>
 __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
                                                        float* __restrict__ lse, const int32_t* __restrict__ am, int S,
-                                                       int nh, float scale, float mask_bias, DropSpec drop) {
+                                                       int nh, float scale, float mask_bias, DropSpec drop,
+                                                       float* __restrict__ ctx32) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[TILE * DH];
   __shared__ __attribute__((aligned(16))) bf16 Vt[DH * TLD];
   __shared__ __attribute__((aligned(16))) float bias[TILE];
@@ -208,6 +229,11 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ 
   bf16* out = ctx + ((size_t)b * S + qt * TILE + wave * 32) * H + h * DH;
   store_acc_T(out, H, n, half, o0, inv);
   store_acc_T(out + 32, H, n, half, o1, inv);
+  if (ctx32 != nullptr) {
+    float* out32 = ctx32 + ((size_t)b * S + qt * TILE + wave * 32) * H + h * DH;
+    store_acc_T_f32(out32, H, n, half, o0, inv);
+    store_acc_T_f32(out32 + 32, H, n, half, o1, inv);
+  }
   if (lse != nullptr && half == 0) lse[((size_t)b * nh + h) * S + q] = m_run + __logf(l_tot);
 }
 
@@ -217,7 +243,8 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
                                                          const bf16* __restrict__ dctx, const float* __restrict__ lse,
                                                          float* __restrict__ delta, bf16* __restrict__ dqkv,
                                                          const int32_t* __restrict__ am, int S, int nh, float scale,
-                                                         float mask_bias, DropSpec drop) {
+                                                         float mask_bias, DropSpec drop,
+                                                         const float* __restrict__ ctx32) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[TILE * DH];
   __shared__ __attribute__((aligned(16))) bf16 Vs[TILE * DH];
   __shared__ __attribute__((aligned(16))) bf16 Kt[DH * TLD];
@@ -237,9 +264,10 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
   for (int ks = 0; ks < 4; ++ks) {
     qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)q * ld + 16 * ks + 8 * half);
     gf[ks] = *reinterpret_cast<const bf16x8_t*>(dctx + tok * H + h * DH + 16 * ks + 8 * half);
-    bf16x8_t cf = *reinterpret_cast<const bf16x8_t*>(ctx + tok * H + h * DH + 16 * ks + 8 * half);
+    float cf[8];
+    load_ctx8(ctx, ctx32, tok * H + h * DH + 16 * ks + 8 * half, cf);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) dl += (float)gf[ks][i] * (float)cf[i];
+    for (int i = 0; i < 8; ++i) dl += (float)gf[ks][i] * cf[i];
   }
   dl += __shfl_xor(dl, 32, 64);
   const float l = lse[((size_t)b * nh + h) * S + q];
@@ -387,7 +415,8 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
                                                            const bf16* __restrict__ dctx,
                                                            const float* __restrict__ lse, bf16* __restrict__ dqkv,
                                                            const int32_t* __restrict__ am, int nh, float scale,
-                                                           float mask_bias, DropSpec drop) {
+                                                           float mask_bias, DropSpec drop,
+                                                           const float* __restrict__ ctx32) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_one[];   // ONE_LDS_BYTES
   bf16* Ks = reinterpret_cast<bf16*>(smem_one);
   bf16* Vs = Ks + TILE * DH;
@@ -426,9 +455,10 @@ __global__ void __launch_bounds__(512) k_attn_bwd_one_tile(const bf16* __restric
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       bf16x8_t g = *reinterpret_cast<const bf16x8_t*>(dctx + o + 8 * j);
-      bf16x8_t c = *reinterpret_cast<const bf16x8_t*>(ctx + o + 8 * j);
+      float c[8];
+      load_ctx8(ctx, ctx32, o + 8 * j, c);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) dl += (float)g[i] * (float)c[i];
+      for (int i = 0; i < 8; ++i) dl += (float)g[i] * c[i];
     }
     dl += __shfl_xor(dl, 1, 64);
     dl += __shfl_xor(dl, 2, 64);
@@ -546,10 +576,10 @@ hipError_t attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
   // dropout is a compile-time variant so that the plain kernels carry none of its registers
   if (a.drop.thr)
     k_attn_fwd_mfma<true><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
-                                                     1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
+                                                     1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop, a.ctx_f32);
   else
     k_attn_fwd_mfma<false><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
-                                                      1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
+                                                      1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop, a.ctx_f32);
   return hipGetLastError();
 }
 
@@ -567,12 +597,12 @@ static hipError_t attention_bwd_mfma_t(const AttnBwdDesc& a, hipStream_t s) {
     }
     k_attn_bwd_one_tile<DROP><<<dim3(a.nh, a.B), dim3(512), ONE_LDS_BYTES, s>>>(
         (const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse, (bf16*)a.dqkv, a.attn_mask, a.nh, scale,
-        a.mask_bias, a.drop);
+        a.mask_bias, a.drop, a.ctx_f32);
     return hipGetLastError();
   }
   k_attn_bwd_q_mfma<DROP><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (const bf16*)a.ctx, (const bf16*)a.dctx, a.lse,
                                                      a.delta, (bf16*)a.dqkv, a.attn_mask, a.S, a.nh, scale, a.mask_bias,
-                                                     a.drop);
+                                                     a.drop, a.ctx_f32);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   static bool attr_set = false;

@@ -11,7 +11,7 @@ template <typename AT>
 __global__ void __launch_bounds__(64) k_attn_fwd_simple(const AT* __restrict__ qkv, AT* __restrict__ ctx,
                                                         float* __restrict__ lse, const int32_t* __restrict__ am, int S,
                                                         int nh, int dh, float scale, float mask_bias,
-                                                        DropSpec drop) {
+                                                        DropSpec drop, float* __restrict__ ctx32) {
   extern __shared__ float sm[];  // q[dh] | p[S]
   float* q = sm;
   float* p = sm + dh;
@@ -47,6 +47,7 @@ __global__ void __launch_bounds__(64) k_attn_fwd_simple(const AT* __restrict__ q
     float acc = 0.f;
     for (int j = 0; j < S; ++j) acc += p[j] * ldf(base + (size_t)j * ld + 2 * H + h * dh + d);
     stf(ctx + ((size_t)b * S + i) * H + h * dh + d, acc * inv);
+    if (ctx32 != nullptr) ctx32[((size_t)b * S + i) * H + h * dh + d] = acc * inv;
   }
   if (lse != nullptr && lane == 0) lse[((size_t)b * nh + h) * S + i] = mx + __logf(se);
 }
@@ -57,7 +58,7 @@ __global__ void __launch_bounds__(64) k_attn_bwd_q(const AT* __restrict__ qkv, c
                                                    const AT* __restrict__ dctx, const float* __restrict__ lse,
                                                    float* __restrict__ delta, AT* __restrict__ dqkv,
                                                    const int32_t* __restrict__ am, int S, int nh, int dh, float scale,
-                                                   float mask_bias, DropSpec drop) {
+                                                   float mask_bias, DropSpec drop, const float* __restrict__ ctx32) {
   extern __shared__ float sm[];  // q[dh] | dc[dh] | da[S]
   float* q = sm;
   float* dc = sm + dh;
@@ -71,7 +72,7 @@ __global__ void __launch_bounds__(64) k_attn_bwd_q(const AT* __restrict__ qkv, c
     q[d] = ldf(base + (size_t)i * ld + h * dh + d);
     float g = ldf(dctx + row * H + h * dh + d);
     dc[d] = g;
-    dl += g * ldf(ctx + row * H + h * dh + d);
+    dl += g * (ctx32 != nullptr ? ctx32[row * H + h * dh + d] : ldf(ctx + row * H + h * dh + d));
   }
   dl = wave_sum(dl);
   __syncthreads();
@@ -149,7 +150,7 @@ static hipError_t fwd_t(const AttnDesc& a, hipStream_t s) {
   dim3 grid(a.S, a.nh, a.B);
   size_t sh = (size_t)(a.dh + a.S) * sizeof(float);
   k_attn_fwd_simple<AT><<<grid, dim3(64), sh, s>>>((const AT*)a.qkv, (AT*)a.ctx, a.lse, a.attn_mask, a.S, a.nh, a.dh,
-                                                   1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop);
+                                                   1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop, a.ctx_f32);
   return hipGetLastError();
 }
 hipError_t attention_fwd_simple(int dtype, const AttnDesc& a, hipStream_t s) {
@@ -162,7 +163,7 @@ static hipError_t bwd_t(const AttnBwdDesc& a, hipStream_t s) {
   float scale = 1.0f / sqrtf((float)a.dh);
   k_attn_bwd_q<AT><<<grid, dim3(64), (size_t)(2 * a.dh + a.S) * sizeof(float), s>>>(
       (const AT*)a.qkv, (const AT*)a.ctx, (const AT*)a.dctx, a.lse, a.delta, (AT*)a.dqkv, a.attn_mask, a.S, a.nh, a.dh,
-      scale, a.mask_bias, a.drop);
+      scale, a.mask_bias, a.drop, a.ctx_f32);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   k_attn_bwd_kv<AT><<<grid, dim3(64), (size_t)(2 * a.dh + 2 * a.S) * sizeof(float), s>>>(

@@ -165,6 +165,7 @@ struct AttnDesc {
   int B, S, nh, dh;
   float mask_bias;
   DropSpec drop;      // dropout of the attention probabilities; element index ((b*nh + h)*S + q)*S + key
+  float* ctx_f32 = nullptr;   // optional second copy of ctx in fp32, unrounded, for the backward pass (see AttnBwdDesc)
 };
 struct AttnBwdDesc {
   const void* qkv;
@@ -177,6 +178,11 @@ struct AttnBwdDesc {
   int B, S, nh, dh;
   float mask_bias;
   DropSpec drop;      // as in AttnDesc
+  // The backward needs delta = rowsum(dC * C) to equal sum_key P * dP of the probabilities it
+  // recomputes; with C rounded to bf16 the two differ by 2^-9 |C||dC|, the rows of dS no longer sum
+  // to zero, and that residual times the (large) common part of the keys ends up in dQ.  So when the
+  // forward kept an unrounded fp32 copy of C, delta is taken from that.
+  const float* ctx_f32 = nullptr;
 };
 hipError_t attention_fwd_simple(int dtype, const AttnDesc& d, hipStream_t s);
 hipError_t attention_bwd_simple(int dtype, const AttnBwdDesc& d, hipStream_t s);

@@ -63,10 +63,11 @@ struct Profiler {
 };
 
 struct LayerStash {
+  // ctx32: unrounded fp32 copy of the attention context (bf16 mode only), from which the backward takes delta
   // u holds GELU'(FFN pre-activation): the forward epilogue computes it next to the GELU value, so
   // the backward pass multiplies instead of evaluating erf and exp again
   void *xout, *qkv, *ctx, *xhat1, *x1, *u, *g, *xhat2;
-  float *lse, *rstd1, *rstd2;
+  float *lse, *rstd1, *rstd2, *ctx32;
 };
 
 struct mslt_model {
@@ -254,6 +255,7 @@ static size_t carve(mslt_model* m, char* base) {
     s.xhat1 = b.take<void>(TH); s.x1 = b.take<void>(TH); s.u = b.take<void>(TF); s.g = b.take<void>(TF);
     s.xhat2 = b.take<void>(TH);
     s.lse = b.take<float>(lse_bytes); s.rstd1 = b.take<float>(Tp * 4); s.rstd2 = b.take<float>(Tp * 4);
+    s.ctx32 = m->dtype ? b.take<float>(Tp * H * 4) : nullptr;
   }
   m->dxa = b.take<void>(TH); m->dxb = b.take<void>(TH);
   for (int i = 0; i < 2; ++i) {
@@ -638,7 +640,7 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
   void* g = st ? st->g : m->s_g;
   RC(linear_fwd(m, Xin, Tr, H, Wg(m, t_app(m, l, L_WQ)), 3 * H, Wf(m, t_app(m, l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr));
   AttnDesc a{qkv, ctx, st ? st->lse : nullptr, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh, m->cfg.mask_bias,
-             dspec(m, l, SITE_ATTN_PROBS)};
+             dspec(m, l, SITE_ATTN_PROBS), st ? st->ctx32 : nullptr};
   {
     const double TS = (double)bt->batch * bt->seq;
     ProfScope ps(m, PC_ATTN_FWD, 4.0 * TS * bt->seq * H, 4.0 * TS * H * m->esz);
@@ -718,7 +720,7 @@ static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int 
   const LayerStash& st = m->stash[l];
   hipStream_t s = m->stream;
   AttnBwdDesc a{st.qkv, st.ctx, m->d_c, st.lse, m->delta, m->d_qkv, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh,
-                m->cfg.mask_bias, dspec(m, l, SITE_ATTN_PROBS)};
+                m->cfg.mask_bias, dspec(m, l, SITE_ATTN_PROBS), st.ctx32};
   {
     const double TS = (double)bt->batch * bt->seq;
     ProfScope ps(m, PC_ATTN_BWD, 10.0 * TS * bt->seq * H, 8.0 * TS * H * m->esz);

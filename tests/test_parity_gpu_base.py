@@ -90,3 +90,13 @@ def test_base_final_stage_full_size():
     r = run_case(sh, 64, 128, 9, 3, False, 1, full_backprop=False)
     print("base 9/3 64x128", assert_parity(r, 1, "base-final"))
     r["model"].close()
+
+
+@pytest.mark.gpu
+def test_large_final_stage_full_size():
+    # final stage of the BERT-Large schedule at full size: 24 layers, bottom 18 frozen, top 6 trainable,
+    # batch 64 x seq 128 (the oracle needs about a minute and 10 GB for this one)
+    sh = synth.bert_large_shape(24)
+    r = run_case(sh, 64, 128, 18, 6, False, 1, full_backprop=False)
+    print("large 18/6 64x128", assert_parity(r, 1, "large-final"))
+    r["model"].close()
