@@ -67,3 +67,36 @@ def test_model_needs_a_gpu():
         pytest.skip("GPU present")
     with pytest.raises(RuntimeError):
         binding.Model(binding.make_config(synth.tiny_shape(), 4, 64, 0))
+
+
+def test_ctypes_structs_match_the_header_layout(tmp_path, repo_root):
+    """sizeof and every field offset of the C structs, as gcc lays them out from include/mslt.h, against the
+    ctypes mirrors of the binding (a reordered or missing field would silently corrupt every call)."""
+    import ctypes
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    structs = {"mslt_config": binding.Config, "mslt_batch": binding.Batch, "mslt_opt": binding.Opt,
+               "mslt_tensor_desc": binding.TensorDesc, "mslt_profile_entry": binding.ProfileEntry}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mslt.h"', 'int main(void) {']
+    for cname, cls in structs.items():
+        lines.append(f'  printf("{cname} size %zu\\n", sizeof({cname}));')
+        for fname, _ in cls._fields_:
+            lines.append(f'  printf("{cname} {fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(repo_root, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen = 0
+    for line in out:
+        if not line:
+            continue
+        cname, fname, value = line.split()
+        cls = structs[cname]
+        want = ctypes.sizeof(cls) if fname == "size" else getattr(cls, fname).offset
+        assert int(value) == want, (cname, fname, value, want)
+        seen += 1
+    assert seen == sum(len(c._fields_) + 1 for c in structs.values())
