@@ -19,6 +19,7 @@
 // partial sums go to an fp32 workspace and a second kernel adds the splits in a fixed order
 // (deterministic, no atomics).
 #include "common.h"
+#include <type_traits>
 
 namespace mslt {
 
@@ -182,11 +183,14 @@ __device__ __forceinline__ uint4 load_aux8(const Epilogue& e, int m, int n) {
 }
 // raw: the 8 per-element operand values of this position (only read when the epilogue uses them);
 // callers load it well ahead so its latency is not paid here
+// EXTRAS: the rarely used parts (dropout of the result, accumulation into the output) are compiled
+// into a second copy of the epilogue, so that the common one carries none of their code.
+template <bool EXTRAS>
 __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float (&v)[8], const float (&bias)[8],
                                           const uint4& raw) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[i] += bias[i];
-  if (e.drop.thr) {
+  if (EXTRAS && e.drop.thr) {
     const uint64_t quad = ((uint64_t)m * e.drop_ld + n) >> 2;     // n and drop_ld are multiples of 4
     const uint64_t r0 = drop_quad(e.drop, quad), r1 = drop_quad(e.drop, quad + 1);
 #pragma unroll
@@ -223,7 +227,7 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
   }
   if (e.out_f32) {
     float* p = reinterpret_cast<float*>(e.out) + o;
-    if (e.accumulate) {
+    if (EXTRAS && e.accumulate) {
       const float4 a0 = *reinterpret_cast<const float4*>(p), a1 = *reinterpret_cast<const float4*>(p + 4);
       v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w;
       v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
@@ -398,14 +402,18 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
       }
   __syncthreads();
 
+  auto finish = [&](auto extras) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    int row = 8 * i + (lane >> 3);
-    float4 x0 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc);
-    float4 x1 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc + 4);
-    float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-    epilogue8(e, mrow + 8 * i, n, v, bias, raw[i]);
-  }
+    for (int i = 0; i < 8; ++i) {
+      int row = 8 * i + (lane >> 3);
+      float4 x0 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc);
+      float4 x1 = *reinterpret_cast<const float4*>(stage + row * EPI_LD + cc + 4);
+      float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+      epilogue8<decltype(extras)::value>(e, mrow + 8 * i, n, v, bias, raw[i]);
+    }
+  };
+  if (e.drop.thr || e.accumulate) finish(std::true_type());
+  else finish(std::false_type());
 }
 
 // sums the split-k partials in split order and applies the epilogue; 8 columns per thread
@@ -428,7 +436,8 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float* __restrict__
 #pragma unroll
     for (int i = 0; i < 8; ++i) bias[i] = e.bias[n + i];
   }
-  epilogue8(e, m, n, v, bias, raw);
+  if (e.drop.thr || e.accumulate) epilogue8<true>(e, m, n, v, bias, raw);
+  else epilogue8<false>(e, m, n, v, bias, raw);
 }
 
 bool gemm_mfma_supported(const GemmDesc& d) {

@@ -352,7 +352,8 @@ size_t ln_bwd_scratch_floats(int rows, int H) {
   return (size_t)3 * ((rows + rpb - 1) / rpb) * H;
 }
 
-template <typename AT, int NV, int R>
+// DROP: the dropout variants are a second compiled copy, so that the plain kernel carries none of their code
+template <typename AT, int NV, int R, bool DROP>
 __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const AT* __restrict__ xhat,
                                                 const float* __restrict__ rstd, const float* __restrict__ g,
                                                 AT* __restrict__ dz, float* __restrict__ part_g,
@@ -394,7 +395,7 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
       d[rr][i] = keep4(keep, d[rr][i]);
       x[rr][i] = keep4(keep, x[rr][i]);
       // the LayerNorm output went through dropout (embedding block): so does its gradient
-      if (dd.in.thr && keep) d[rr][i] = mul4(d[rr][i], drop4(dd.in, (uint64_t)(row0 + rr) * H + (i * 64 + lane) * 4));
+      if (DROP && dd.in.thr && keep) d[rr][i] = mul4(d[rr][i], drop4(dd.in, (uint64_t)(row0 + rr) * H + (i * 64 + lane) * 4));
     }
   }
 #pragma unroll
@@ -416,7 +417,7 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
       // the LayerNorm input was residual + dropout(linear output): the linear output's gradient is
       // dz times the same keep factors (element index by token row: compacted rows go through rowmap)
       uint64_t tok = (uint64_t)row;
-      if (dd.out.thr && dd.rowmap) tok = row < dd.n_mapped ? (uint64_t)dd.rowmap[row] : 0;
+      if (DROP && dd.out.thr && dd.rowmap) tok = row < dd.n_mapped ? (uint64_t)dd.rowmap[row] : 0;
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         int c = (i * 64 + lane) * 4;
@@ -425,7 +426,7 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
           float4 o = make_float4((y.x - m1 - xx.x * m2) * rs[rr], (y.y - m1 - xx.y * m2) * rs[rr],
                                  (y.z - m1 - xx.z * m2) * rs[rr], (y.w - m1 - xx.w * m2) * rs[rr]);
           store4(dz + (size_t)row * H + c, o);
-          if (dd.out.thr) {
+          if (DROP && dd.out.thr) {
             o = mul4(o, drop4(dd.out, tok * H + c));
             store4(reinterpret_cast<AT*>(dd.dzm) + (size_t)row * H + c, o);
           }
@@ -472,11 +473,18 @@ static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, cons
   float* pg = scratch;
   float* pb = pg + (size_t)nb * H;
   float* pz = pb + (size_t)nb * H;
+  const bool drop = dd.in.thr || dd.out.thr;
+#define MSLT_LNB(NV, R)                                                                                         \
+  do {                                                                                                          \
+    if (drop) k_ln_bwd<AT, NV, R, true><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd);  \
+    else k_ln_bwd<AT, NV, R, false><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd);      \
+  } while (0)
   switch (ln_nv(H)) {
-    case 2: k_ln_bwd<AT, 2, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd); break;
-    case 4: k_ln_bwd<AT, 4, 4><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd); break;
-    default: k_ln_bwd<AT, 8, 2><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd); break;
+    case 2: MSLT_LNB(2, 4); break;
+    case 4: MSLT_LNB(4, 4); break;
+    default: MSLT_LNB(8, 2); break;
   }
+#undef MSLT_LNB
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ReduceArgs a{{pg, pb, pz}, {dg, db, dzsum}, dd.accumulate};
