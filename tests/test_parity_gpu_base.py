@@ -100,3 +100,39 @@ def test_large_final_stage_full_size():
     r = run_case(sh, 64, 128, 18, 6, False, 1, full_backprop=False)
     print("large 18/6 64x128", assert_parity(r, 1, "large-final"))
     r["model"].close()
+
+
+def test_base_final_stage_full_size_long_sequences():
+    # final stage of the BERT-Base schedule on the long sequences of the last tenth of training (Section 4.2):
+    # 12 layers, bottom 9 frozen, top 3 trainable, batch 16 x seq 512; every gradient element against the oracle
+    sh = synth.bert_base_shape(12)
+    r = run_case(sh, 16, 512, 9, 3, False, 1, seed=5, full_backprop=False)
+    print("base 9/3 16x512", assert_parity(r, 1, "base-final-long"))
+    r["model"].close()
+
+
+def test_large_sweep_size_top_layer_against_oracle_and_stage_equals_slice_of_full_step():
+    # BERT-Large, 24 layers, batch 32 x seq 512 (the size of the schedule sweep).  The oracle needs minutes for
+    # a six-layer backward at this size, so it checks the step that trains the top layer alone (all 24 layers
+    # forward, one backward), and the six-layer stage is checked through the property that defines the method
+    # (Section 3.2): its gradients are the same tensors' gradients of the step that trains all 24 layers.
+    from parity_util import grads_dict, make_model
+    sh = synth.bert_large_shape(24)
+    r = run_case(sh, 32, 512, 23, 1, False, 1, seed=6, full_backprop=False)
+    print("large 23/1 32x512", assert_parity(r, 1, "large-sweep-top"))
+    m, cb = r["model"], r["cb"]
+    ls = m.mslt_stage_step(18, 6, False, cb)
+    gs = grads_dict(m, sh, 18, 6, False)
+    ps = m.mslt_debug_prefix_output(32, 512)
+    lf = m.mslt_stage_step(0, 24, False, cb)
+    gf = grads_dict(m, sh, 0, 24, False)
+    assert ls == lf, (ls, lf)
+    assert abs(ls - r["ref_loss"]) < 1e-3 * abs(r["ref_loss"])       # the forward pass is that of the checked step
+    worst = 0.0
+    for name, g in gs.items():
+        d = np.abs(g - gf[name]).max() / max(np.abs(gf[name]).max(), 1e-30)
+        worst = max(worst, d)
+        assert d <= 1e-6, (name, d)
+    print("large 18/6 vs 0/24 32x512: worst relative difference", worst)
+    assert np.isfinite(ps).all()
+    m.close()
