@@ -595,13 +595,14 @@ static DropSpec dspec(const mslt_model* m, int layer, int site) {
 // Y[rows,N] = X[rows,K] W[N,K]^T + bias, optional GELU (gelu_grad_out then receives GELU' of the pre-activation),
 // optional dropout of the result
 static int linear_fwd(mslt_model* m, const void* X, int rows, int K, const void* W, int N, const float* bias, void* Y,
-                      int out_f32, int ldo, int act, void* gelu_grad_out, const DropSpec& drop = DropSpec()) {
+                      int out_f32, int ldo, int act, void* gelu_grad_out, const DropSpec& drop = DropSpec(),
+                      hipStream_t st = nullptr) {
   GemmDesc d;
   d.epi.drop = drop; d.epi.drop_ld = N;
   d.A = X; d.lda = K; d.a_kcontig = 1; d.M = rows;
   d.B = W; d.ldb = K; d.b_kcontig = 1; d.N = N; d.K = K;
   d.epi.out = Y; d.epi.ldo = ldo; d.epi.out_f32 = out_f32; d.epi.bias = bias; d.epi.act = act; d.epi.out2 = gelu_grad_out;
-  return run_gemm(m, d);
+  return run_gemm(m, d, false, st);
 }
 // dX[rows,K] = dY[rows,N] W[N,K]  (+ addend | * gelu'(U))
 static int linear_bwd_input(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* W, int K, void* dX,
@@ -624,40 +625,63 @@ static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int
 }
 
 static int ln_forward(mslt_model* m, const void* a, const void* r, const float* g, const float* b, void* out, LnStash st,
-                      int rows) {
+                      int rows, hipStream_t stream = nullptr) {
   ProfScope ps(m, PC_LN_FWD, 0.0, (double)rows * m->H * m->esz * (2.0 + (r ? 1.0 : 0.0) + (st.xhat ? 1.0 : 0.0)));
-  HIP_TRY(add_ln_fwd(m->dtype, a, r, g, b, m->cfg.ln_eps, out, st, rows, m->H, m->stream));
+  HIP_TRY(add_ln_fwd(m->dtype, a, r, g, b, m->cfg.ln_eps, out, st, rows, m->H, stream ? stream : m->stream));
   return MSLT_OK;
 }
 
 // ---- one encoder layer ----------------------------------------------------------------------
+// Every kernel of the forward pass works on token rows (or whole sequences) independently of the
+// other rows, so a layer can run on a range of the batch's sequences: FwdPart names the range and
+// the stream.  Without a part the layer runs on all Tr rows on the main stream.
+struct FwdPart {
+  int b0, nb;        // sequences [b0, b0 + nb)
+  hipStream_t st;
+};
 static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, const void* Xin, void* Xout,
-                         const LayerStash* st) {
-  const int H = m->H, F = m->F;
-  void* qkv = st ? st->qkv : m->s_qkv;
-  void* ctx = st ? st->ctx : m->s_ctx;
-  void* x1 = st ? st->x1 : m->s_x1;
-  void* g = st ? st->g : m->s_g;
-  RC(linear_fwd(m, Xin, Tr, H, Wg(m, t_app(m, l, L_WQ)), 3 * H, Wf(m, t_app(m, l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr));
-  AttnDesc a{qkv, ctx, st ? st->lse : nullptr, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh, m->cfg.mask_bias,
-             dspec(m, l, SITE_ATTN_PROBS), st ? st->ctx32 : nullptr};
+                         const LayerStash* st, const FwdPart* part = nullptr) {
+  const int H = m->H, F = m->F, S = bt->seq;
+  const int nb = part ? part->nb : bt->batch;
+  const size_t r0 = part ? (size_t)part->b0 * S : 0;          // first token row
+  const int rows = part ? nb * S : Tr;
+  hipStream_t s = part ? part->st : m->stream;
+  auto at = [&](const void* p, size_t width_bytes) -> void* {   // row r0 of a [rows, width] array (null stays null)
+    return p ? (void*)((char*)p + r0 * width_bytes) : nullptr;
+  };
+  const size_t e = m->esz;
+  void* qkv = at(st ? st->qkv : m->s_qkv, 3 * H * e);
+  void* ctx = at(st ? st->ctx : m->s_ctx, H * e);
+  void* x1 = at(st ? st->x1 : m->s_x1, H * e);
+  void* g = at(st ? st->g : m->s_g, F * e);
+  void* y = at(m->s_y, H * e);
+  const void* xin = at(Xin, H * e);
+  void* xout = at(Xout, H * e);
+  RC(linear_fwd(m, xin, rows, H, Wg(m, t_app(m, l, L_WQ)), 3 * H, Wf(m, t_app(m, l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr,
+                DropSpec(), s));
+  AttnDesc a{qkv, ctx, st ? (float*)at(st->lse, (size_t)m->nh * 4) : nullptr, bt->attn_mask + r0, nb, S, m->nh, m->dh,
+             m->cfg.mask_bias, dspec(m, l, SITE_ATTN_PROBS), st ? (float*)at(st->ctx32, H * 4) : nullptr};
   {
-    const double TS = (double)bt->batch * bt->seq;
-    ProfScope ps(m, PC_ATTN_FWD, 4.0 * TS * bt->seq * H, 4.0 * TS * H * m->esz);
-    if (m->dtype == 1 && attention_mfma_supported(bt->seq, m->dh))
-      HIP_TRY(attention_fwd_mfma(a, m->stream));
+    const double TS = (double)nb * S;
+    ProfScope ps(m, PC_ATTN_FWD, 4.0 * TS * S * H, 4.0 * TS * H * m->esz);
+    if (m->dtype == 1 && attention_mfma_supported(S, m->dh))
+      HIP_TRY(attention_fwd_mfma(a, s));
     else
-      HIP_TRY(attention_fwd_simple(m->dtype, a, m->stream));
+      HIP_TRY(attention_fwd_simple(m->dtype, a, s));
   }
-  RC(linear_fwd(m, ctx, Tr, H, Wg(m, t_app(m, l, L_WO)), H, Wf(m, t_app(m, l, L_BO)), m->s_y, 0, H, EPI_NONE, nullptr,
-                dspec(m, l, SITE_ATTN_OUT)));
+  RC(linear_fwd(m, ctx, rows, H, Wg(m, t_app(m, l, L_WO)), H, Wf(m, t_app(m, l, L_BO)), y, 0, H, EPI_NONE, nullptr,
+                dspec(m, l, SITE_ATTN_OUT), s));
   LnStash s1, s2;
-  if (st) { s1.xhat = st->xhat1; s1.rstd = st->rstd1; s2.xhat = st->xhat2; s2.rstd = st->rstd2; }
-  RC(ln_forward(m, m->s_y, Xin, Wf(m, t_app(m, l, L_LN1G)), Wf(m, t_app(m, l, L_LN1B)), x1, s1, Tr));
-  RC(linear_fwd(m, x1, Tr, H, Wg(m, t_app(m, l, L_W1)), F, Wf(m, t_app(m, l, L_B1)), g, 0, F, EPI_GELU, st ? st->u : nullptr));
-  RC(linear_fwd(m, g, Tr, F, Wg(m, t_app(m, l, L_W2)), H, Wf(m, t_app(m, l, L_B2)), m->s_y, 0, H, EPI_NONE, nullptr,
-                dspec(m, l, SITE_FFN_OUT)));
-  RC(ln_forward(m, m->s_y, x1, Wf(m, t_app(m, l, L_LN2G)), Wf(m, t_app(m, l, L_LN2B)), Xout, s2, Tr));
+  if (st) {
+    s1.xhat = at(st->xhat1, H * e); s1.rstd = (float*)at(st->rstd1, 4);
+    s2.xhat = at(st->xhat2, H * e); s2.rstd = (float*)at(st->rstd2, 4);
+  }
+  RC(ln_forward(m, y, xin, Wf(m, t_app(m, l, L_LN1G)), Wf(m, t_app(m, l, L_LN1B)), x1, s1, rows, s));
+  RC(linear_fwd(m, x1, rows, H, Wg(m, t_app(m, l, L_W1)), F, Wf(m, t_app(m, l, L_B1)), g, 0, F, EPI_GELU,
+                st ? at(st->u, F * e) : nullptr, DropSpec(), s));
+  RC(linear_fwd(m, g, rows, F, Wg(m, t_app(m, l, L_W2)), H, Wf(m, t_app(m, l, L_B2)), y, 0, H, EPI_NONE, nullptr,
+                dspec(m, l, SITE_FFN_OUT), s));
+  RC(ln_forward(m, y, x1, Wf(m, t_app(m, l, L_LN2G)), Wf(m, t_app(m, l, L_LN2B)), xout, s2, rows, s));
   return MSLT_OK;
 }
 
@@ -815,19 +839,37 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
                          Wf(m, T_ELN_G), Wf(m, T_ELN_B), m->cfg.ln_eps, m->x0, e0, T, H, m->V, m->cfg.type_vocab,
                          dspec(m, 0, SITE_EMBEDDING), s));
   }
+  // The two halves of the batch go through the encoder as two independent chains of kernels, one per
+  // stream: where a kernel of one chain leaves compute units idle (a last, partly filled round of
+  // workgroups, its ramp-up and its drain) kernels of the other chain take them.  Measured: 2-5 %
+  // of the step; four chains on four streams were slower.  Dropout indexes its decisions by position
+  // in the whole batch, so the halves are used only without it.  Off while event profiling.
+  const bool halves = !m->prof.on && !m->drop_thr && m->dtype == 1 && m->mfma && B % 2 == 0 && (T / 2) % 128 == 0 && Tr == T;
+  const FwdPart parts[2] = {{0, B / 2, s}, {B / 2, B / 2, m->side}};
+  if (halves) {
+    HIP_TRY(hipEventRecord(m->ev_fork, s));
+    HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+    m->side_forked = true;     // a step that fails half-way is joined at the start of the next one
+  }
+  auto forward = [&](int l, const void* xin, void* xo, const LayerStash* st) -> int {
+    if (!halves) return layer_forward(m, l, bt, Tr, xin, xo, st);
+    RC(layer_forward(m, l, bt, Tr, xin, xo, st, &parts[0]));
+    return layer_forward(m, l, bt, Tr, xin, xo, st, &parts[1]);
+  };
   // S2: frozen prefix, forward only, two ping-pong buffers, nothing kept
   const void* x = m->x0;
   for (int l = 0; l < f; ++l) {
     void* xo = (l & 1) ? m->xb : m->xa;
-    RC(layer_forward(m, l, bt, Tr, x, xo, nullptr));
+    RC(forward(l, x, xo, nullptr));
     x = xo;
   }
   m->last_prefix = x;
   // S3: trainable layers, with stash
   for (int l = f; l < f + k; ++l) {
-    RC(layer_forward(m, l, bt, Tr, x, m->stash[l].xout, &m->stash[l]));
+    RC(forward(l, x, m->stash[l].xout, &m->stash[l]));
     x = m->stash[l].xout;
   }
+  if (halves) RC(side_join(m));
   HIP_TRY(hipEventSynchronize(m->ev_scan));
   // M: compacted rows (predicted positions, plus every first token when there is a next-sentence head);
   // Mn: those of them that carry a masked-LM label

@@ -136,3 +136,23 @@ def test_large_sweep_size_top_layer_against_oracle_and_stage_equals_slice_of_ful
     print("large 18/6 vs 0/24 32x512: worst relative difference", worst)
     assert np.isfinite(ps).all()
     m.close()
+
+
+def test_two_stream_schedule_gives_the_single_stream_result_bit_for_bit():
+    # The step spreads its kernels over two streams (the halves of the batch go through the encoder forward as two
+    # chains; weight-gradient products run beside the data-gradient chain).  With per-kernel event timing switched
+    # on everything runs on one stream in program order.  Both must give the same bits.
+    from parity_util import make_model
+    sh = synth.bert_base_shape(4)
+    m = make_model(sh, 8, 128, 1)
+    m.mslt_load_params(synth.pack_weights(sh, synth.make_weights(sh, seed=8)))
+    cb = m.device_batch(synth.make_batch(sh, 8, 128, seed=9))
+    l2 = m.mslt_stage_step(2, 2, False, cb)
+    g2 = m.mslt_get_grads().copy()
+    m.mslt_profile_enable(True)
+    l1 = m.mslt_stage_step(2, 2, False, cb)
+    g1 = m.mslt_get_grads().copy()
+    m.mslt_profile_enable(False)
+    assert l1 == l2
+    assert np.array_equal(g1, g2)
+    m.close()
