@@ -582,10 +582,12 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false,
   } while (0)
 
 // keep decisions of one dropout site of one layer in the current step (thr 0 = dropout off)
-static DropSpec dspec(const mslt_model* m, int layer, int site) {
+// first_elem: index, in the whole tensor, of the element the kernel will call element 0 (a multiple
+// of 4).  The decision of quad q comes from mix64(key + q * DROP_GOLDEN), so an offset folds into the key.
+static DropSpec dspec(const mslt_model* m, int layer, int site, uint64_t first_elem = 0) {
   DropSpec d;
   if (m->drop_thr) {
-    d.key = drop_key(m->drop_seed, m->drop_step, layer, site);
+    d.key = drop_key(m->drop_seed, m->drop_step, layer, site) + (first_elem >> 2) * DROP_GOLDEN;
     d.thr = m->drop_thr;
     d.scale = m->drop_scale;
   }
@@ -660,7 +662,7 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
   RC(linear_fwd(m, xin, rows, H, Wg(m, t_app(m, l, L_WQ)), 3 * H, Wf(m, t_app(m, l, L_BQ)), qkv, 0, 3 * H, EPI_NONE, nullptr,
                 DropSpec(), s));
   AttnDesc a{qkv, ctx, st ? (float*)at(st->lse, (size_t)m->nh * 4) : nullptr, bt->attn_mask + r0, nb, S, m->nh, m->dh,
-             m->cfg.mask_bias, dspec(m, l, SITE_ATTN_PROBS), st ? (float*)at(st->ctx32, H * 4) : nullptr};
+             m->cfg.mask_bias, dspec(m, l, SITE_ATTN_PROBS, r0 * m->nh * S), st ? (float*)at(st->ctx32, H * 4) : nullptr};
   {
     const double TS = (double)nb * S;
     ProfScope ps(m, PC_ATTN_FWD, 4.0 * TS * S * H, 4.0 * TS * H * m->esz);
@@ -670,7 +672,7 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
       HIP_TRY(attention_fwd_simple(m->dtype, a, s));
   }
   RC(linear_fwd(m, ctx, rows, H, Wg(m, t_app(m, l, L_WO)), H, Wf(m, t_app(m, l, L_BO)), y, 0, H, EPI_NONE, nullptr,
-                dspec(m, l, SITE_ATTN_OUT), s));
+                dspec(m, l, SITE_ATTN_OUT, r0 * H), s));
   LnStash s1, s2;
   if (st) {
     s1.xhat = at(st->xhat1, H * e); s1.rstd = (float*)at(st->rstd1, 4);
@@ -680,7 +682,7 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
   RC(linear_fwd(m, x1, rows, H, Wg(m, t_app(m, l, L_W1)), F, Wf(m, t_app(m, l, L_B1)), g, 0, F, EPI_GELU,
                 st ? at(st->u, F * e) : nullptr, DropSpec(), s));
   RC(linear_fwd(m, g, rows, F, Wg(m, t_app(m, l, L_W2)), H, Wf(m, t_app(m, l, L_B2)), y, 0, H, EPI_NONE, nullptr,
-                dspec(m, l, SITE_FFN_OUT), s));
+                dspec(m, l, SITE_FFN_OUT, r0 * H), s));
   RC(ln_forward(m, y, x1, Wf(m, t_app(m, l, L_LN2G)), Wf(m, t_app(m, l, L_LN2B)), xout, s2, rows, s));
   return MSLT_OK;
 }
@@ -843,8 +845,9 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   // stream: where a kernel of one chain leaves compute units idle (a last, partly filled round of
   // workgroups, its ramp-up and its drain) kernels of the other chain take them.  Measured: 2-5 %
   // of the step; four chains on four streams were slower.  Dropout indexes its decisions by position
-  // in the whole batch, so the halves are used only without it.  Off while event profiling.
-  const bool halves = !m->prof.on && !m->drop_thr && m->dtype == 1 && m->mfma && B % 2 == 0 && (T / 2) % 128 == 0 && Tr == T;
+  // in the whole batch: the second half's kernels get keys that carry its offset (S even keeps the
+  // offset of the attention probabilities a multiple of 4).  Off while event profiling.
+  const bool halves = !m->prof.on && m->dtype == 1 && m->mfma && B % 2 == 0 && (T / 2) % 128 == 0 && Tr == T && S % 2 == 0;
   const FwdPart parts[2] = {{0, B / 2, s}, {B / 2, B / 2, m->side}};
   if (halves) {
     HIP_TRY(hipEventRecord(m->ev_fork, s));

@@ -147,12 +147,14 @@ def test_two_stream_schedule_gives_the_single_stream_result_bit_for_bit():
     m = make_model(sh, 8, 128, 1)
     m.mslt_load_params(synth.pack_weights(sh, synth.make_weights(sh, seed=8)))
     cb = m.device_batch(synth.make_batch(sh, 8, 128, seed=9))
-    l2 = m.mslt_stage_step(2, 2, False, cb)
-    g2 = m.mslt_get_grads().copy()
-    m.mslt_profile_enable(True)
-    l1 = m.mslt_stage_step(2, 2, False, cb)
-    g1 = m.mslt_get_grads().copy()
-    m.mslt_profile_enable(False)
-    assert l1 == l2
-    assert np.array_equal(g1, g2)
+    for p in (0.0, 0.1):       # with dropout the second half's kernels must take the decisions of their own positions
+        m.mslt_set_dropout(p, 77, 3)
+        l2 = m.mslt_stage_step(2, 2, False, cb)
+        g2 = m.mslt_get_grads().copy()
+        m.mslt_profile_enable(True)
+        l1 = m.mslt_stage_step(2, 2, False, cb)
+        g1 = m.mslt_get_grads().copy()
+        m.mslt_profile_enable(False)
+        assert l1 == l2, p
+        assert np.array_equal(g1, g2), p
     m.close()
