@@ -158,3 +158,31 @@ def test_two_stream_schedule_gives_the_single_stream_result_bit_for_bit():
         assert l1 == l2, p
         assert np.array_equal(g1, g2), p
     m.close()
+
+
+def test_a_run_of_training_steps_on_two_streams_gives_the_single_stream_result_bit_for_bit():
+    # A run of steps (layer split changing in between, growth, then a step that trains everything) must leave the
+    # same parameters whether the kernels are spread over the two streams or all run on one in program order.
+    from paper_2011_13635_amd import binding
+    from parity_util import make_model
+    sh = synth.bert_base_shape(4)
+    W = synth.pack_weights(sh, synth.make_weights(sh, seed=11))
+    batches = [synth.make_batch(sh, 8, 128, seed=20 + i) for i in range(6)]
+    results = []
+    for serial in (False, True):
+        m = make_model(sh, 8, 128, 1)
+        m.mslt_load_params(W)
+        m.mslt_profile_enable(serial)
+        cbs = [m.device_batch(b) for b in batches]
+        losses = []
+        losses.append(m.mslt_train_step(0, 2, True, cbs[0], binding.lamb(lr=1e-3)))
+        losses.append(m.mslt_train_step(0, 2, True, cbs[1], binding.lamb(lr=1e-3)))
+        m.mslt_grow(2, 2)
+        losses.append(m.mslt_train_step(2, 2, False, cbs[2], binding.lamb(lr=1e-3)))
+        losses.append(m.mslt_train_step(2, 2, False, cbs[3], binding.adam(lr=1e-4)))
+        losses.append(m.mslt_train_step(3, 1, False, cbs[4], binding.adam(lr=1e-4)))   # layer 2 was just updated
+        losses.append(m.mslt_train_step(0, 4, True, cbs[5], binding.adam(lr=1e-4)))
+        results.append((losses, m.mslt_get_params().copy()))
+        m.close()
+    assert results[0][0] == results[1][0]
+    assert np.array_equal(results[0][1], results[1][1])
