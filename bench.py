@@ -182,8 +182,13 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+        # the counters are read per launch: keep every step of this run in the form the per-launch timing below
+        # uses (one stream, one launch per product) so that the launches of the two runs correspond
+        model.mslt_profile_enable(True)
 
     sec, loss = time_steps(torch, model, cb, f, k, False, opt, args.steps, args.warmup)
+    if args.copy_calibration:
+        model.mslt_profile_read()
     tokens = B * S
     ps = time_steps.per_step_ms     # host time between consecutive step returns
     step_quantiles = [round(ps[len(ps) // 2], 4), round(ps[len(ps) // 10], 4), round(ps[(len(ps) * 9) // 10], 4)]
