@@ -115,6 +115,8 @@ struct mslt_model {
   float drop_scale = 1.f;
   void *d_dm, *d_z1m;      // masked dz2 / dz1 of the current layer's set
   void *c_dz2m, *c_dz1m;   // the same for the compacted top layer
+  void *c_xhat2, *c_dz2, *c_dc;   // compacted top layer: rows of xhat2, dz2 and dC (buffers of their own: the side
+                                  // stream may still be reading the head's when the top layer starts)
   float *splitk2, *red2;
   int32_t *e_rank, *e_cnt, *e_start, *e_order, *e_blockcnt;
   float* e_partial;                    // [Tp, H] run sums of the embedding backward
@@ -275,6 +277,7 @@ static size_t carve(mslt_model* m, char* base) {
   m->d_ut = b.take<void>(MH); m->d_xm = b.take<void>(MH);
   m->c_g = b.take<void>(Mp * F * e); m->c_u = b.take<void>(Mp * F * e); m->c_du = b.take<void>(Mp * F * e);
   m->c_dz2m = b.take<void>(MH); m->c_dz1m = b.take<void>(MH);
+  m->c_xhat2 = b.take<void>(MH); m->c_dz2 = b.take<void>(MH); m->c_dc = b.take<void>(MH);
   m->rstd_t = b.take<float>(Mp * 4); m->logits = b.take<float>(Mp * Vp * 4); m->row_loss = b.take<float>(Mp * 4);
   m->lse_t = b.take<float>(Mp * 4); m->loss = b.take<float>(64);
   {
@@ -519,11 +522,15 @@ static int pick_splitk(int M, int N, int K) {
 // data-gradient chain (which is what the layer below waits for).  side_fork makes the side stream
 // see the main stream's work so far; side_join makes the main stream wait for the side stream and
 // is called before any buffer the side work reads is overwritten.  Off while event profiling.
-static int side_fork(mslt_model* m, hipStream_t* st, float** partials, float** red) {
+// again: nothing the side work reads was produced on the main stream since the previous fork, so
+// that fork's event still covers it (recording an event costs the recording stream about 6 us).
+static int side_fork(mslt_model* m, hipStream_t* st, float** partials, float** red, bool again = false) {
   *st = m->stream; *partials = m->splitk; *red = m->red_scratch;
   if (m->prof.on) return MSLT_OK;
-  HIP_TRY(hipEventRecord(m->ev_fork, m->stream));
-  HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+  if (!(again && m->side_forked)) {
+    HIP_TRY(hipEventRecord(m->ev_fork, m->stream));
+    HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+  }
   m->side_forked = true;
   *st = m->side; *partials = m->splitk2; *red = m->red2;
   return MSLT_OK;
@@ -616,13 +623,14 @@ static int linear_bwd_input(mslt_model* m, const void* dY, int rows, int N, int 
   return run_gemm(m, d, allow_splitk);
 }
 // dW[N,K] = dY[rows,N]^T X[rows,K]   (fp32 out, contraction over rows)
-static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* X, int K, float* dW) {
+static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* X, int K, float* dW,
+                             bool again = false) {
   GemmDesc d;
   d.A = dY; d.lda = ldy; d.a_kcontig = 0; d.M = N;
   d.B = X; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = rows;
   d.epi.out = dW; d.epi.ldo = K; d.epi.out_f32 = 1; d.epi.accumulate = m->acc_now;
   hipStream_t st; float *partials, *red;
-  RC(side_fork(m, &st, &partials, &red));
+  RC(side_fork(m, &st, &partials, &red, again));
   return run_gemm(m, d, true, st, partials);
 }
 
@@ -687,10 +695,10 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
   return MSLT_OK;
 }
 
-static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, float* out) {
+static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, float* out, bool again = false) {
   ProfScope ps(m, PC_COLSUM, (double)rows * N, (double)rows * N * m->esz);
   hipStream_t st; float *partials, *red;
-  RC(side_fork(m, &st, &partials, &red));
+  RC(side_fork(m, &st, &partials, &red, again));
   HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, red, st, m->acc_now));
   return MSLT_OK;
 }
@@ -727,10 +735,12 @@ static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const U
   const void* dy1 = d1.out.thr ? r.dz1m : r.dz1;
   RC(ln_backward(m, dXout, r.xhat2, r.rstd2, Wf(m, t_app(m, l, L_LN2G)), r.dz2, Gf(m, t_app(m, l, L_LN2G)),
                  Gf(m, t_app(m, l, L_LN2B)), Gf(m, t_app(m, l, L_B2)), R, d2));
-  RC(linear_bwd_weight(m, dy2, R, H, H, r.g, F, Gf(m, t_app(m, l, L_W2))));
+  // one fork for the three side products of the feed-forward part (W2's waits for the data gradient
+  // of the second linear layer: the side stream has a backlog anyway, and every fork stalls this stream)
   RC(linear_bwd_input(m, dy2, R, H, H, Wg(m, t_app(m, l, L_W2)), F, r.du, EPI_MUL, r.u));
-  RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_app(m, l, L_W1))));
-  RC(bias_grad(m, r.du, F, R, F, Gf(m, t_app(m, l, L_B1))));
+  RC(linear_bwd_weight(m, dy2, R, H, H, r.g, F, Gf(m, t_app(m, l, L_W2))));
+  RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_app(m, l, L_W1)), true));
+  RC(bias_grad(m, r.du, F, R, F, Gf(m, t_app(m, l, L_B1)), true));
   RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_app(m, l, L_W1)), H, r.dx1, EPI_ADD, r.dz2));
   RC(ln_backward(m, r.dx1, r.xhat1, r.rstd1, Wf(m, t_app(m, l, L_LN1G)), r.dz1, Gf(m, t_app(m, l, L_LN1G)),
                  Gf(m, t_app(m, l, L_LN1B)), Gf(m, t_app(m, l, L_BO)), R, d1));
@@ -758,7 +768,7 @@ static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int 
       HIP_TRY(fill_zero((char*)m->d_qkv + (size_t)T * 3 * H * m->esz, (size_t)(Tr - T) * 3 * H * m->esz, s));
   }
   RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_app(m, l, L_WQ))));
-  RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_app(m, l, L_BQ))));
+  RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_app(m, l, L_BQ)), true));
   if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_app(m, l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
   return layer_backward_end(m, l);
 }
@@ -784,16 +794,16 @@ static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T,
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * Mr * (4.0 * H + 2.0 * F) * m->esz);
     const int hb = H * (int)m->esz, fb = F * (int)m->esz;
-    const GatherDesc g[8] = {{st.xhat2, m->xm, hb}, {st.x1, m->ut, hb}, {st.xhat1, m->gt, hb}, {st.ctx, m->xhat_t, hb},
+    const GatherDesc g[8] = {{st.xhat2, m->c_xhat2, hb}, {st.x1, m->ut, hb}, {st.xhat1, m->gt, hb}, {st.ctx, m->xhat_t, hb},
                              {st.g, m->c_g, fb},    {st.u, m->c_u, fb}, {st.rstd2, m->rstd_t, 4}, {st.rstd1, m->lse_t, 4}};
     HIP_TRY(gather_rows_multi(g, 8, m->pos, M, Mr, s));
   }
-  UpperRows r{m->xm, m->c_g, m->c_u, m->ut, m->gt, m->xhat_t, m->rstd_t, m->lse_t,
-              m->hm, m->c_du, m->d_hm, m->d_gt, m->d_ut, Mr, m->c_dz2m, m->c_dz1m, m->pos, M};
+  UpperRows r{m->c_xhat2, m->c_g, m->c_u, m->ut, m->gt, m->xhat_t, m->rstd_t, m->lse_t,
+              m->c_dz2, m->c_du, m->d_hm, m->d_gt, m->c_dc, Mr, m->c_dz2m, m->c_dz1m, m->pos, M};
   RC(layer_backward_upper(m, l, dXm, r));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * ((double)Tr + M) * H * m->esz);
-    HIP_TRY(scatter_rows(m->dtype, m->d_ut, m->inv, Tr, T, H, m->d_c, s));
+    HIP_TRY(scatter_rows(m->dtype, m->c_dc, m->inv, Tr, T, H, m->d_c, s));
     HIP_TRY(scatter_rows(m->dtype, m->d_gt, m->inv, Tr, T, H, m->d_z1, s));
   }
   return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin);
@@ -913,7 +923,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   // S7: head backward
   // over the padded vocabulary (the padded columns of dZ are zero and the output bias reserves them)
   RC(bias_grad(m, m->dz, m->Vp, Mr, m->Vp, Gf(m, th + H_BOUT)));
-  if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD)));
+  if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD), true));
   // few output tiles, contraction over the whole vocabulary: split it
   RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr, true));
   RC(ln_backward(m, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG), Gf(m, th + H_LNB), nullptr, Mr));
@@ -922,20 +932,21 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
     HIP_TRY(mul_dgelu(m->dtype, m->d_gt, m->ut, m->d_ut, (size_t)Mr * H, s));
   }
   RC(linear_bwd_weight(m, m->d_ut, Mr, H, H, m->xm, H, Gf(m, th + H_WT)));
-  RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT)));
+  RC(bias_grad(m, m->d_ut, H, Mr, H, Gf(m, th + H_BT), true));
   RC(linear_bwd_input(m, m->d_ut, Mr, H, H, Wg(m, th + H_WT), H, m->d_xm, EPI_NONE, nullptr));
   if (m->nsp) {
     // backward of the next-sentence head; its input gradient joins the compacted rows of the first tokens
     RC(linear_bwd_weight(m, m->n_dz, B, 2, 2, m->n_p, H, Gf(m, th + C_W)));
-    RC(bias_grad(m, m->n_dz, 2, B, 2, Gf(m, th + C_B)));
+    RC(bias_grad(m, m->n_dz, 2, B, 2, Gf(m, th + C_B), true));
     RC(linear_bwd_input(m, m->n_dz, B, 2, 2, Wg(m, th + C_W), H, m->n_dp, EPI_NONE, nullptr, false));
     HIP_TRY(tanh_bwd(m->dtype, m->n_dp, m->n_p, m->n_du, (size_t)B * H, s));
     RC(linear_bwd_weight(m, m->n_du, B, H, H, m->n_xc, H, Gf(m, th + P_W)));
-    RC(bias_grad(m, m->n_du, H, B, H, Gf(m, th + P_B)));
+    RC(bias_grad(m, m->n_du, H, B, H, Gf(m, th + P_B), true));
     RC(linear_bwd_input(m, m->n_du, B, H, H, Wg(m, th + P_W), H, m->n_dx, EPI_NONE, nullptr, false));
     HIP_TRY(add_first_token_rows(m->dtype, m->n_dx, m->inv, S, H, B, m->d_xm, s));
   }
-  RC(side_join(m));      // the top layer's backward reuses the head buffers
+  // (no join here: the top layer's compacted rows have buffers of their own, so the side stream may still be
+  //  working on the head's weight gradients while the main stream goes on)
   // S8/S9: trainable layers backward, top down.  The top layer works on the compacted predicted rows
   // and scatters inside; the layers below get dense gradients.
   void* dx = m->dxa;
