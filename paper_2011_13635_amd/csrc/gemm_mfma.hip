@@ -452,11 +452,20 @@ bool gemm_mfma_supported(const GemmDesc& d) {
   return true;
 }
 
-// The tall tile pays off only for long contractions with at least one full wave of tall tiles
-// (measured: 8192^3 runs at 1054 vs 852 TFLOP/s; at K = 768..3072 two resident 128-row workgroups
-// per CU overlap their prologues and epilogues better than one 256-row workgroup).
+// The tall tile pays off for long contractions with at least one full wave of tall tiles (measured:
+// 8192^3 runs at 1054 vs 852 TFLOP/s), and, inside the training step, for the products with a narrow
+// output (N <= 1024: output projection, second feed-forward layer and the data gradients that end in
+// the hidden size): there a 128-row tiling leaves the last round of workgroups partly empty, and with
+// a second kernel chain running beside it fewer, larger workgroups finish sooner.  Measured in the
+// step (same box, alternating): NT products 0.4 % (hidden 768) and 2.1 % (hidden 1024) of the step; NN
+// products gain only at hidden 1024 (0.4 %) and lose 1 % at 768, where two resident 128-row
+// workgroups per CU overlap their prologues and epilogues better.  Wide outputs stay at 128 rows
+// (the tall tile costs 3.5 % of the step there).
 int gemm_mfma_tile_m(const GemmDesc& d) {
-  return (d.M % 256 == 0 && d.K >= 4096 && (d.M / 256) * (d.N / BN) >= 256) ? 256 : 128;
+  if (d.M % 256) return 128;
+  if (d.K >= 4096 && (d.M / 256) * (d.N / BN) >= 256) return 256;
+  if (d.a_kcontig && d.M >= 2048 && d.N <= 1024 && (d.b_kcontig || d.N == 1024)) return 256;
+  return 128;
 }
 
 template <int BM, int AMODE, int BMODE>
