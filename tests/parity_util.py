@@ -5,7 +5,7 @@ import numpy as np
 from oracle import mslt_oracle as O
 from paper_2011_13635_amd import binding, synth
 
-# spec tolerances: loss and gradients relative 1e-4 in fp32 mode, relative 2e-2 (max-norm) in bf16 mode
+# tolerances: loss and gradients relative 1e-4 in fp32 mode, relative 2e-2 (max-norm) in bf16 mode
 TOL = {0: 1e-4, 1: 2e-2}
 
 
