@@ -69,6 +69,46 @@ def profile_steps(model, cbatches, f, k, emb, opt, steps):
     return prof
 
 
+def clocks_under_load(model, cbatches, f, k, emb, opt):
+    """Clock and power state while the step runs: rocm-smi is queried from a second thread during a burst of about a
+    second and a half of steps (the library calls release the interpreter lock).  None if the tool is not there."""
+    import re
+    import shutil
+    import subprocess
+    import threading
+    if shutil.which("rocm-smi") is None:
+        return None
+    got = {}
+
+    def query():
+        time.sleep(0.4)
+        try:
+            got["text"] = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel", "--showpower", "--showmaxpower"],
+                                         capture_output=True, text=True, timeout=20).stdout
+        except (OSError, subprocess.SubprocessError):
+            pass
+
+    th = threading.Thread(target=query)
+    th.start()
+    t_end = time.perf_counter() + 1.5
+    while time.perf_counter() < t_end or th.is_alive():
+        run_steps(model, cbatches, f, k, emb, opt, 10)
+    th.join()
+    model.mslt_sync()
+    text = got.get("text")
+    if not text:
+        return None
+
+    def find(pattern, cast=float):
+        m = re.search(pattern, text)
+        return cast(m.group(1)) if m else None
+
+    return {"sclk_mhz": find(r"sclk clock level: \d+: \((\d+)Mhz\)"), "mclk_mhz": find(r"mclk clock level: \d+: \((\d+)Mhz\)"),
+            "perf_level": find(r"Performance Level: (\w+)", str), "power_w": find(r"(?:Average|Current Socket) Graphics Package Power \(W\): ([\d.]+)"),
+            "power_cap_w": find(r"Max Graphics Package Power \(W\): ([\d.]+)"),
+            "sampled": "rocm-smi, once, while the benchmark step was running back to back"}
+
+
 PMC_TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_gemm_mfma_base_3f3t_64x128_pmc_traffic.txt")
 
 
@@ -235,6 +275,7 @@ def main():
                      "gemm_ms_per_step": round(g_ms, 4), "gemm_gflop_per_step": round(g_flops / 1e9, 1),
                      "timed_with": "HIP events around every launch on the library's stream; the interval also holds "
                      "the fixed-order split-k summing kernel of a product and the dispatch latency of the launch"},
+        "clocks": clocks_under_load(model, cb, f, k, False, opt),
         "kernel_classes": classes,
         "profiled_ms_per_step": round(sum(v["ms"] for v in prof.values()), 4),
     }
