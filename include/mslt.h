@@ -15,8 +15,11 @@
  *     fails validation enqueues no GPU work and leaves every arena untouched.
  *   - The library never allocates or frees device memory.  The caller (normally PyTorch) owns
  *     four device arenas whose sizes mslt_query_sizes() reports, and a HIP stream; all GPU work
- *     is enqueued on that stream.  Host memory passed in is read or written before the call
- *     returns.  "DEVICE" / "HOST" below say where a pointer must live.
+ *     is ordered with that stream: part of a step runs on a second stream the model creates
+ *     (default priority), which forks from the caller's stream and joins it again by events
+ *     inside the same call, so work the caller enqueues on its stream before or after a call is
+ *     ordered with all of the call's work.  Host memory passed in is read or written before the
+ *     call returns.  "DEVICE" / "HOST" below say where a pointer must live.
  *   - Weight matrices are [out, in] row-major fp32 in the canonical tensor order reported by
  *     mslt_tensor_table(): embedding block, encoder layers bottom to top, head.
  *   - precision 0: fp32 storage and arithmetic everywhere.  precision 1: bf16 activations and
