@@ -186,6 +186,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-compare", action="store_true", help="skip the final-stage vs full-step comparison")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-clocks", action="store_true",
+                    help="skip the burst of steps during which rocm-smi is queried (keeps a profiler run short)")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time the BERT-Base final stage (64x128, 16x512), BERT-Large final stage and the "
                          "BERT-Large stage sweep at 32x512 (several minutes)")
@@ -275,7 +277,7 @@ def main():
                      "gemm_ms_per_step": round(g_ms, 4), "gemm_gflop_per_step": round(g_flops / 1e9, 1),
                      "timed_with": "HIP events around every launch on the library's stream; the interval also holds "
                      "the fixed-order split-k summing kernel of a product and the dispatch latency of the launch"},
-        "clocks": clocks_under_load(model, cb, f, k, False, opt),
+        "clocks": None if (args.no_clocks or args.copy_calibration) else clocks_under_load(model, cb, f, k, False, opt),
         "kernel_classes": classes,
         "profiled_ms_per_step": round(sum(v["ms"] for v in prof.values()), 4),
     }

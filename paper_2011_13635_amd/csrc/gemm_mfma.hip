@@ -267,7 +267,22 @@ __global__ void __launch_bounds__(2 * BM) k_gemm_mfma(MfmaParams p) {
   const int tiles = p.tiles_m * p.tiles_n;
   const int split = pid / tiles;
   const int tile = pid - split * tiles;
-  const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+  // Consecutive tiles run at the same time on one XCD and share its L2: order them in bands of
+  // GROUP_M tile rows, column by column inside a band, so that the concurrent set is a block of
+  // about GROUP_M x 64/GROUP_M tiles (few distinct operand panels) instead of one long tile row.
+#ifndef MSLT_GROUP_M
+#define MSLT_GROUP_M 8
+#endif
+  int tm, tn;
+  {
+    constexpr int G = MSLT_GROUP_M;
+    const int band = tile / (G * p.tiles_n);
+    const int first = band * G;
+    const int rows = p.tiles_m - first < G ? p.tiles_m - first : G;
+    const int in_band = tile - band * G * p.tiles_n;
+    tm = first + in_band % rows;
+    tn = in_band / rows;
+  }
   const int m0 = tm * BM, n0 = tn * BN;
   // split s takes k tiles [s*nkt/splitk, (s+1)*nkt/splitk): sizes differ by at most one tile
   const int nkt = p.K / BK;
