@@ -472,10 +472,10 @@ bool gemm_mfma_supported(const GemmDesc& d) {
 // output (N <= 1024: output projection, second feed-forward layer and the data gradients that end in
 // the hidden size): there a 128-row tiling leaves the last round of workgroups partly empty, and with
 // a second kernel chain running beside it fewer, larger workgroups finish sooner.  Measured in the
-// step (same box, alternating): NT products 0.4 % (hidden 768) and 2.1 % (hidden 1024) of the step; NN
-// products gain only at hidden 1024 (0.4 %) and lose 1 % at 768, where two resident 128-row
-// workgroups per CU overlap their prologues and epilogues better.  Wide outputs stay at 128 rows
-// (the tall tile costs 3.5 % of the step there).
+// step (same box, alternating), this rule against 128-row tiles everywhere: 3 % of the step at
+// hidden 768, 1.5 % at hidden 1024; NN products gain only at hidden 1024 and lose 1 % at 768, where
+// two resident 128-row workgroups per CU overlap their prologues and epilogues better.  Wide outputs
+// stay at 128 rows (the tall tile costs 3.5 % of the step there).
 int gemm_mfma_tile_m(const GemmDesc& d) {
   if (d.M % 256) return 128;
   if (d.K >= 4096 && (d.M / 256) * (d.N / BN) >= 256) return 256;
