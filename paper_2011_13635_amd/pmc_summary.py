@@ -13,6 +13,7 @@ from __future__ import annotations
 import csv
 import hashlib
 import os
+import re
 import sys
 
 CSRC = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
@@ -21,9 +22,16 @@ COPY_BYTES = 256 * 1024 * 1024
 
 
 def kernel_source_hash() -> str:
+    """Hash of the kernel's code: comments and blank space do not count."""
     h = hashlib.sha256()
     for path in KERNEL_SOURCES:
-        h.update(open(path, "rb").read())
+        text = open(path, encoding="utf-8").read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        for line in text.splitlines():
+            line = re.sub(r"//.*", "", line)
+            line = "".join(line.split())
+            if line:
+                h.update(line.encode() + b"\n")
     return h.hexdigest()
 
 
