@@ -195,6 +195,33 @@ def test_attention_special_cases():
     assert np.allclose(X2, x2, atol=1e-13)
 
 
+def test_attention_score_scale_two_keys_by_hand():
+    # BERT's scaled dot-product attention (Section 4.1 takes the network by citation): scores are
+    # q.k / sqrt(d_h).  One head of width 4, two keys, identity query/key projections, all numbers
+    # typed out: q1 = k1 = (1, 2, 0, -1), q2 = k2 = (0.5, -1, 3, 2).
+    sh = synth.ModelShape(n_layers=1, hidden=4, n_heads=1, ffn=8, vocab=20, max_pos=8)
+    W = O.to_f64(synth.make_weights(sh, seed=5, std=0.3, perturb=0.1))
+    W["layer0.wq"] = np.eye(4)
+    W["layer0.wk"] = np.eye(4)
+    W["layer0.bq"] = np.zeros(4)
+    W["layer0.bk"] = np.zeros(4)
+    X = np.array([[1.0, 2.0, 0.0, -1.0], [0.5, -1.0, 3.0, 2.0]])
+    _, c = O.layer_forward(sh, W, 0, X, np.zeros((1, 2)), 1, 2, O.Ops())
+    # dot products: q1.k1 = 6, q1.k2 = q2.k1 = -3.5, q2.k2 = 14.25; d_h = 4, so they are halved
+    s11, s12, s22 = 6.0 / 2.0, -3.5 / 2.0, 14.25 / 2.0
+    p11 = 1.0 / (1.0 + math.exp(s12 - s11))
+    p22 = 1.0 / (1.0 + math.exp(s12 - s22))
+    want = np.array([[p11, 1.0 - p11], [1.0 - p22, p22]])
+    assert np.allclose(c["P"][0, 0], want, rtol=0, atol=1e-14)
+    # the unscaled scores and a division by d_h instead of its root give visibly different rows
+    for wrong in (1.0, 0.25):
+        q11 = 1.0 / (1.0 + math.exp(wrong * (-3.5 - 6.0)))
+        assert abs(q11 - c["P"][0, 0, 0, 0]) > 1e-4
+    # and the context is that mixture of the two value rows
+    V = X @ W["layer0.wv"].T + W["layer0.bv"]
+    assert np.allclose(c["C"], want @ V, atol=1e-13)
+
+
 def test_stage_step_equals_slice_of_full_step():
     # Section 3.1/3.2: the trainable tensors get the gradients plain back-propagation gives them;
     # the frozen prefix only supplies the input of the top layers.
