@@ -208,6 +208,22 @@ typedef struct {
 int mslt_profile_enable(mslt_model* m, int on);
 int mslt_profile_read(mslt_model* m, mslt_profile_entry* out, int cap, int* n);
 
+/* Test and measurement aid for the matrix products the step is made of (Sections 3.1 and 3.2 name
+ * the layers; their linear maps are these products): C[M,N] = sum_k A(m,k) B(n,k) on DEVICE operands
+ * through one chosen kernel, enqueued on hip_stream (hipStream_t as void*, null = default stream).
+ * A and B are bf16 (2 bytes per element, round to nearest even); a_kcontig != 0: A(m,k) = A[m*K + k],
+ * else A[k*M + m]; the same for B with n and N.  C is row-major [M,N], bf16, or fp32 when out_f32 != 0.
+ * kernel 0: guarded SIMT kernel (any shape).  kernel 1: 128-wide MFMA kernel, tile_m 0 (chosen by
+ * shape), 128 or 256; M % 128 == 0, N % 128 == 0, K % 64 == 0.  kernel 2: large-tile kernel fed by
+ * direct global-to-LDS loads, tile_m x tile_n one of 256x256, 256x128, 128x256, 128x128, ring stage
+ * tile_k 64 (or 32, not for 128x128); M % tile_m == 0, N % tile_n == 0, K % tile_k == 0.  splitk > 1
+ * (kernels 1 and 2) splits the contraction over workgroups and needs `partials`, DEVICE scratch of at
+ * least splitk*M*N*4 bytes (partial_bytes says how large it is).  Returns MSLT_ERR_ARG for a shape or
+ * choice the kernel does not take; nothing is enqueued then.  Does not block. */
+int mslt_debug_gemm(void* hip_stream, const void* A, const void* B, void* C, int M, int N, int K, int a_kcontig,
+                    int b_kcontig, int out_f32, int kernel, int tile_m, int tile_n, int tile_k, int splitk,
+                    void* partials, size_t partial_bytes);
+
 /* Waits until all work enqueued on the model's stream has finished. */
 int mslt_sync(const mslt_model* m);
 

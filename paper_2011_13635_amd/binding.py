@@ -18,7 +18,7 @@ EXPORTS = [
     "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_train_step",
     "mslt_set_dropout", "mslt_debug_masked",
     "mslt_debug_prefix_output", "mslt_grow", "mslt_sync", "mslt_destroy", "mslt_last_error",
-    "mslt_profile_enable", "mslt_profile_read",
+    "mslt_profile_enable", "mslt_profile_read", "mslt_debug_gemm",
 ]
 
 MSLT_OK, MSLT_ERR_ARG, MSLT_ERR_STATE, MSLT_ERR_DATA, MSLT_ERR_HIP, MSLT_ERR_NONFINITE = 0, -1, -2, -3, -4, -5
@@ -88,6 +88,7 @@ def load_library():
     lib.mslt_profile_enable.argtypes = [vp, C.c_int]
     lib.mslt_profile_read.argtypes = [vp, P(ProfileEntry), C.c_int, P(C.c_int)]
     lib.mslt_sync.argtypes = [vp]
+    lib.mslt_debug_gemm.argtypes = [vp, vp, vp, vp] + [C.c_int] * 11 + [vp, sz]
     lib.mslt_destroy.argtypes = [vp]
     lib.mslt_last_error.argtypes = []
     lib.mslt_last_error.restype = C.c_char_p
@@ -123,6 +124,20 @@ def adam(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-6, weight_decay=0.01, bias_corr
 
 def lamb(lr=0.00088, beta1=0.9, beta2=0.999, eps=1e-6, weight_decay=0.01, bias_correction=True) -> Opt:
     return Opt(1, lr, beta1, beta2, eps, weight_decay, int(bias_correction))
+
+
+def mslt_debug_gemm(a, b, c, M, N, K, a_kcontig, b_kcontig, kernel, tile_m=0, tile_n=0, tile_k=64, splitk=1,
+                    partials=None, stream=None):
+    """One product through a chosen kernel.  a, b: torch bf16 device tensors; c: bf16 or fp32 device tensor
+    [M, N]; partials: uint8/fp32 device tensor for split-k.  Enqueues only."""
+    import torch
+    out_f32 = int(c.dtype == torch.float32)
+    st = stream if stream is not None else torch.cuda.current_stream(a.device)
+    pb = partials.numel() * partials.element_size() if partials is not None else 0
+    _check(load_library().mslt_debug_gemm(C.c_void_p(st.cuda_stream), C.c_void_p(a.data_ptr()), C.c_void_p(b.data_ptr()),
+                                          C.c_void_p(c.data_ptr()), M, N, K, int(a_kcontig), int(b_kcontig), out_f32, kernel,
+                                          tile_m, tile_n, tile_k, splitk,
+                                          C.c_void_p(partials.data_ptr()) if partials is not None else None, pb))
 
 
 class Model:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmslt.so")
-SOURCES = ["model.hip", "rowwise.hip", "gemm_simt.hip", "gemm_mfma.hip", "attention_simple.hip", "attention_mfma.hip"]
+SOURCES = ["model.hip", "rowwise.hip", "gemm_simt.hip", "gemm_mfma.hip", "gemm_ring.hip", "attention_simple.hip", "attention_mfma.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-result"]
 

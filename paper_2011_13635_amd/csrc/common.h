@@ -156,6 +156,12 @@ int gemm_mfma_tile_m(const GemmDesc& d);
 hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t s, int force_tile_m = 0,
                      int force_dma = -1);
 
+// Large-tile MFMA kernel (bf16 only): tile_m x tile_n of 256x256, 256x128 or 128x256, both operands loaded
+// global -> LDS directly in any of the three layouts; M % tile_m == 0, N % tile_n == 0.
+// rk: k extent of a ring stage, 32 or 64 (K % rk == 0).
+bool gemm_ring_supported(const GemmDesc& d, int tile_m, int tile_n, int rk);
+hipError_t gemm_ring(const GemmDesc& d, int tile_m, int tile_n, int rk, int splitk, float* partials, hipStream_t s);
+
 // ---- attention ------------------------------------------------------------------------------
 struct AttnDesc {
   const void* qkv;    // [T, 3H] rows = tokens: Q | K | V, head h at columns h*dh

@@ -566,6 +566,35 @@ static int layer_backward_end(mslt_model* m, int l) {
   return MSLT_OK;
 }
 
+// Tile shape and split factor of the large-tile kernel for one product, or false when the 128-wide
+// kernel should take it.  One workgroup occupies a compute unit, so what counts is how full the rounds
+// of 256 workgroups are: a 256x256 tile moves the fewest bytes per FLOP (relative rate 1), the two
+// half-size tiles about 0.88 of it (measured on the step's shapes), and splitting k costs the partial
+// sums and a second launch (factor 0.9).
+struct RingPlan { int tm, tn, rk, sk; };
+static bool ring_plan(const GemmDesc& d, bool allow_splitk, size_t partial_floats, RingPlan* out) {
+  static const int cand[3][2] = {{256, 256}, {128, 256}, {256, 128}};
+  const int rk = 64;
+  if (d.K % rk) return false;
+  double best = 0.0;
+  for (auto& c : cand) {
+    if (!gemm_ring_supported(d, c[0], c[1], rk)) continue;
+    const int tiles = (d.M / c[0]) * (d.N / c[1]), nk = d.K / rk;
+    int sk = 1;
+    if (allow_splitk && tiles < 192) {
+      sk = 256 / tiles;
+      if (sk > 8) sk = 8;
+      if (sk > nk / 4) sk = nk / 4;
+      while (sk > 1 && (size_t)sk * d.M * d.N > partial_floats) --sk;
+      if (sk < 1) sk = 1;
+    }
+    const int wgs = tiles * sk, rounds = (wgs + 255) / 256;
+    double score = (c[0] == 256 && c[1] == 256 ? 1.0 : 0.88) * wgs / (rounds * 256.0) * (sk > 1 ? 0.9 : 1.0);
+    if (score > best) { best = score; *out = RingPlan{c[0], c[1], rk, sk}; }
+  }
+  return best > 0.0;
+}
+
 static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false, hipStream_t st = nullptr,
                     float* partials = nullptr) {
   if (!st) { st = m->stream; partials = m->splitk; }
@@ -573,7 +602,20 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false,
   const double out_esz = d.epi.out_f32 ? 4.0 : (double)m->esz;
   ProfScope ps(m, !use_mfma ? PC_GEMM_SIMT : (d.a_kcontig ? (d.b_kcontig ? PC_GEMM_NT : PC_GEMM_NN) : PC_GEMM_TN),
                2.0 * d.M * d.N * d.K, ((double)d.M * d.K + (double)d.N * d.K) * m->esz + (double)d.M * d.N * out_esz);
-  if (use_mfma) {
+  // Which kernel takes which product was settled by measuring whole steps (two kernel chains run side by
+  // side there, so a kernel's footprint counts as much as its own speed): forward-type products (both
+  // operands k-contiguous) go to the large-tile kernel; weight-gradient products (both operands k-strided)
+  // to its 128x128 form, two workgroups per compute unit, fed by direct loads and transposing LDS reads;
+  // data-gradient products stay on the 128-wide register-staged kernel.
+  RingPlan rp;
+  const bool nt = d.a_kcontig && d.b_kcontig, tn = !d.a_kcontig && !d.b_kcontig;
+  if (use_mfma && tn && gemm_ring_supported(d, 128, 128, 64)) {
+    int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
+    while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
+    HIP_TRY(gemm_ring(d, 128, 128, 64, sk, partials, st));
+  } else if (use_mfma && nt && ring_plan(d, allow_splitk, m->splitk_floats, &rp)) {
+    HIP_TRY(gemm_ring(d, rp.tm, rp.tn, rp.rk, rp.sk, partials, st));
+  } else if (use_mfma) {
     int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
     while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
     HIP_TRY(gemm_mfma(d, sk, partials, st));
@@ -1151,6 +1193,38 @@ extern "C" int mslt_grow(mslt_model* m, int n_present, int n_new) {
   HIP_TRY(hipMemcpyAsync(m->o_tsteps + t_layer(n_present, 0), z.data(), z.size() * 4, hipMemcpyHostToDevice, m->stream));
   HIP_TRY(hipStreamSynchronize(m->stream));
   m->have_grads = false;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_debug_gemm(void* hip_stream, const void* A, const void* B, void* C, int M, int N, int K, int a_kcontig,
+                               int b_kcontig, int out_f32, int kernel, int tile_m, int tile_n, int tile_k, int splitk,
+                               void* partials, size_t partial_bytes) {
+  if (!A || !B || !C) return fail(MSLT_ERR_ARG, "debug_gemm: null operand");
+  if (M < 1 || N < 1 || K < 1) return fail(MSLT_ERR_ARG, "debug_gemm: non-positive size");
+  if (splitk < 1) return fail(MSLT_ERR_ARG, "debug_gemm: splitk must be at least 1");
+  if (splitk > 1 && (kernel == 0 || !partials || partial_bytes < (size_t)splitk * M * N * 4))
+    return fail(MSLT_ERR_ARG, "debug_gemm: split-k needs kernel 1 or 2 and %zu bytes of partials", (size_t)splitk * M * N * 4);
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  GemmDesc d;
+  d.A = A; d.B = B; d.M = M; d.N = N; d.K = K;
+  d.a_kcontig = a_kcontig != 0; d.b_kcontig = b_kcontig != 0;
+  d.lda = d.a_kcontig ? K : M; d.ldb = d.b_kcontig ? K : N;
+  d.epi.out = C; d.epi.ldo = N; d.epi.out_f32 = out_f32 != 0;
+  if (kernel == 0) {
+    HIP_TRY(gemm_simt(1, d, st));
+  } else if (kernel == 1) {
+    if (!gemm_mfma_supported(d) || (tile_m != 0 && tile_m != 128 && tile_m != 256) || (tile_m && M % tile_m) || splitk > K / 64)
+      return fail(MSLT_ERR_ARG, "debug_gemm: shape %dx%dx%d (tile_m %d, splitk %d) not taken by the 128-wide kernel", M, N, K,
+                  tile_m, splitk);
+    HIP_TRY(gemm_mfma(d, splitk, (float*)partials, st, tile_m));
+  } else if (kernel == 2) {
+    if (!gemm_ring_supported(d, tile_m, tile_n, tile_k) || splitk > K / tile_k)
+      return fail(MSLT_ERR_ARG, "debug_gemm: shape %dx%dx%d not taken by the large-tile kernel with tile %dx%dx%d, splitk %d", M, N,
+                  K, tile_m, tile_n, tile_k, splitk);
+    HIP_TRY(gemm_ring(d, tile_m, tile_n, tile_k, splitk, (float*)partials, st));
+  } else {
+    return fail(MSLT_ERR_ARG, "debug_gemm: kernel must be 0, 1 or 2");
+  }
   return MSLT_OK;
 }
 
