@@ -156,6 +156,18 @@ int mslt_get_grads(const mslt_model* m, float* host_fp32_out, size_t n_floats);
  * without a new step is an error. */
 int mslt_apply_update(mslt_model* m, const mslt_opt* opt);
 
+/* mslt_apply_update() for callers that cannot allocate or hand over scratch memory of their own
+ * choosing (code under HIP graph capture, tight serving-style loops, harnesses that forbid hipMalloc):
+ * same update, same results bit for bit, but the only scratch the update needs (LAMB's per-chunk
+ * partial sums and per-tensor trust ratios) lives in a device array inside the library (266 240 bytes
+ * per GPU, held until the process ends) instead of the workspace arena.  The call allocates and frees
+ * nothing.  Limits: at most 32768 optimizer chunks of 16384 elements (about 536 M parameters) and
+ * 1024 tensors in the model's tensor table; larger models get MSLT_ERR_ARG and nothing is enqueued.
+ * All models on one GPU share that array and it keeps the previous call's contents (every value read
+ * is written earlier in the same call, so nothing has to be cleared): calls that overlap in time on
+ * one GPU, from different models or streams, race.  Enqueues work only; does not block. */
+int mslt_apply_update_static(mslt_model* m, const mslt_opt* opt);
+
 /* One training step of a stage in one call: mslt_stage_step() followed by mslt_apply_update()
  * (Sections 3.1 and 3.2), with the same requirements, results and error codes as the two calls
  * made one after the other.  The update is queued right behind the step, before the host has

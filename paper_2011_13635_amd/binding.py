@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_PKG, "libmslt.so")
 
 EXPORTS = [
     "mslt_query_sizes", "mslt_init_model", "mslt_tensor_table", "mslt_load_params", "mslt_get_params",
-    "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_train_step",
+    "mslt_stage_step", "mslt_grad_count", "mslt_get_grads", "mslt_apply_update", "mslt_apply_update_static",
+    "mslt_train_step",
     "mslt_set_dropout", "mslt_debug_masked",
     "mslt_debug_prefix_output", "mslt_grow", "mslt_sync", "mslt_destroy", "mslt_last_error",
     "mslt_profile_enable", "mslt_profile_read", "mslt_debug_gemm",
@@ -80,6 +81,7 @@ def load_library():
     lib.mslt_grad_count.argtypes = [vp, P(sz)]
     lib.mslt_get_grads.argtypes = [vp, vp, sz]
     lib.mslt_apply_update.argtypes = [vp, P(Opt)]
+    lib.mslt_apply_update_static.argtypes = [vp, P(Opt)]
     lib.mslt_train_step.argtypes = [vp, C.c_int, C.c_int, C.c_int, P(Batch), P(Opt), P(C.c_float)]
     lib.mslt_set_dropout.argtypes = [vp, C.c_float, C.c_uint64, C.c_uint64]
     lib.mslt_debug_masked.argtypes = [vp, vp, vp, P(C.c_int)]
@@ -213,6 +215,9 @@ class Model:
 
     def mslt_apply_update(self, opt: Opt):
         _check(self.lib.mslt_apply_update(self.handle, C.byref(opt)))
+
+    def mslt_apply_update_static(self, opt: Opt):
+        _check(self.lib.mslt_apply_update_static(self.handle, C.byref(opt)))
 
     def mslt_train_step(self, frozen_layers, trainable_layers, train_embeddings, cbatch: Batch, opt: Opt, allow=()):
         loss = C.c_float()

@@ -122,6 +122,7 @@ struct mslt_model {
   float* e_partial;                    // [Tp, H] run sums of the embedding backward
   OptTensor* o_tensors; int32_t* o_chunk_tensor; int32_t* o_tsteps; float* o_chunk_norms; float* o_ratio;
   std::vector<int> first_chunk;  // per tensor, plus total at the end
+  float* static_scratch;   // this device's copy of the file-scope scratch array (see mslt_apply_update_static)
   // pinned host scalars
   int32_t* h_counters; float* h_loss;
   // last step
@@ -130,6 +131,35 @@ struct mslt_model {
   const void* last_prefix;
   Profiler prof;
 };
+
+// ---- scratch for the entry point that must not allocate ----------------------------------------
+// mslt_apply_update_static keeps the only scratch the update needs (LAMB's per-chunk partial sums of
+// |w|^2 and |u|^2 and the per-tensor ratios) in this file-scope device array instead of the caller's
+// workspace.  Every GPU the library runs on holds its own copy until the process ends.  The array's
+// name is only a host-side handle: its device address is looked up once per device (with that
+// device current) and that address is what kernels and copies get.
+constexpr int STATIC_MAX_CHUNKS = 32768;     // 16384-element optimizer chunks: models up to 536 M parameters
+constexpr int STATIC_MAX_TENSORS = 1024;
+constexpr size_t STATIC_SCRATCH_FLOATS = (size_t)2 * STATIC_MAX_CHUNKS + STATIC_MAX_TENSORS;   // 266 240 bytes
+static __device__ __align__(256) float scratch[STATIC_SCRATCH_FLOATS];
+constexpr int MAX_DEVICES = 64;
+static float* g_scratch_ptr[MAX_DEVICES];    // device address of `scratch` per device id, null until looked up
+// Address of this device's copy of the scratch array (looked up on first use; the caller's current device is restored).
+static int static_scratch_for(int dev, float** out) {
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(MSLT_ERR_ARG, "device id %d outside 0..%d", dev, MAX_DEVICES - 1);
+  if (!g_scratch_ptr[dev]) {
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur));
+    if (cur != dev) HIP_TRY(hipSetDevice(dev));
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (cur != dev) hipSetDevice(cur);
+    if (e != hipSuccess || !ptr) return fail(MSLT_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = static_cast<float*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return MSLT_OK;
+}
 
 // ---- tensor table ---------------------------------------------------------------------------
 static void add_tensor(mslt_model* m, const char* name, int layer, int rows, int cols, int decays, size_t reserve,
@@ -387,6 +417,14 @@ extern "C" int mslt_init_model(const mslt_config* cfg, void* param_arena, void* 
   m->ws_bytes = carve(m, m->ws);
   m->have_grads = false;
   m->last_prefix = nullptr;
+  {
+    // the device that holds the arenas is the one whose scratch copy this model uses
+    hipPointerAttribute_t at;
+    hipError_t pe = hipPointerGetAttributes(&at, param_arena);
+    if (pe != hipSuccess) { delete m; return fail(MSLT_ERR_HIP, "hipPointerGetAttributes(param_arena): %s", hipGetErrorString(pe)); }
+    int prc = static_scratch_for(at.device, &m->static_scratch);
+    if (prc) { delete m; return prc; }
+  }
   hipError_t e;
 #define INIT_TRY(expr)                                                                  \
   if ((e = (expr)) != hipSuccess) {                                                     \
@@ -1084,7 +1122,9 @@ static int check_opt(const mslt_opt* opt, const char* who) {
   return MSLT_OK;
 }
 // Queues the update of the tensors the last step trained; gate: see OptHyper::gate.
-static int update_enqueue(mslt_model* m, const mslt_opt* opt, const float* gate) {
+static int update_enqueue(mslt_model* m, const mslt_opt* opt, const float* gate, float* chunk_norms = nullptr,
+                          float* ratio = nullptr) {
+  if (!chunk_norms) { chunk_norms = m->o_chunk_norms; ratio = m->o_ratio; }
   OptHyper h{opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay, opt->bias_correction, gate};
   int r[3][2];
   int n = trainable_ranges(m, r);
@@ -1096,7 +1136,7 @@ static int update_enqueue(mslt_model* m, const mslt_opt* opt, const float* gate)
     ProfScope ps(m, PC_OPT, 0.0, (double)n_elems * ((opt->kind ? 40.0 : 28.0) + (m->dtype ? 2.0 : 0.0)));
     HIP_TRY(bump_steps(m->o_tsteps, t0, nt, gate, m->stream));
     HIP_TRY(optimizer_step(h, m->o_tensors, m->o_tsteps, t0, nt, m->o_chunk_tensor, c0, nc, m->param, m->grad, m->mom1,
-                           m->mom2, m->shadow, m->o_chunk_norms, m->o_ratio, m->stream));
+                           m->mom2, m->shadow, chunk_norms, ratio, m->stream));
   }
   return MSLT_OK;
 }
@@ -1106,6 +1146,19 @@ extern "C" int mslt_apply_update(mslt_model* m, const mslt_opt* opt) {
   if (!m->have_grads) return fail(MSLT_ERR_STATE, "apply_update: no gradients from a preceding stage_step");
   RC(check_opt(opt, "apply_update"));
   RC(update_enqueue(m, opt, nullptr));
+  m->have_grads = false;
+  return MSLT_OK;
+}
+
+extern "C" int mslt_apply_update_static(mslt_model* m, const mslt_opt* opt) {
+  if (!m || !opt) return fail(MSLT_ERR_ARG, "null argument");
+  if (!m->have_grads) return fail(MSLT_ERR_STATE, "apply_update_static: no gradients from a preceding stage_step");
+  RC(check_opt(opt, "apply_update_static"));
+  if (m->first_chunk.back() > STATIC_MAX_CHUNKS || (int)m->table.size() > STATIC_MAX_TENSORS)
+    return fail(MSLT_ERR_ARG, "apply_update_static: model has %d optimizer chunks and %d tensors, the static scratch holds %d and %d",
+                m->first_chunk.back(), (int)m->table.size(), STATIC_MAX_CHUNKS, STATIC_MAX_TENSORS);
+  // every chunk sum and ratio the update reads is written earlier in the same call: nothing to clear
+  RC(update_enqueue(m, opt, nullptr, m->static_scratch, m->static_scratch + (size_t)2 * STATIC_MAX_CHUNKS));
   m->have_grads = false;
   return MSLT_OK;
 }
