@@ -115,7 +115,7 @@ def to_f64(params):
 
 
 # ----------------------------------------------------------------------------------------------
-# dropout ("all other settings are the same as BERT", Section 4.1: probability 0.1 on the embedding
+# dropout (BERT's dropout, adopted by reference in Section 4.1: probability 0.1 on the embedding
 # output, the attention probabilities, the attention output and the feed-forward output)
 # ----------------------------------------------------------------------------------------------
 # The keep decisions come from a counter-based generator so that any implementation can reproduce
@@ -232,12 +232,20 @@ def masked_rows(batch):
     return pos.astype(np.int64), lab[pos].astype(np.int64)
 
 
+def projection_matrix(P):
+    """The word matrix as the output projection sees it.  It is the tied matrix `emb.word` itself unless the
+    caller supplies `head.proj_word`: a diagnostic input for comparisons with a reduced-precision
+    implementation whose projection reads a rounded copy of the matrix while its embedding lookup reads the
+    unrounded one (the gradient still goes to the one tied matrix)."""
+    return P.get("head.proj_word", P["emb.word"])
+
+
 def head_forward(cfg, P, XL, pos, Y, ops):
     Xm = XL[pos]
     Ut = ops.mm(Xm, P["head.wt"].T) + P["head.bt"]
     Gt = gelu(Ut)
     Hm, ln = layer_norm(Gt, P["head.ln_g"], P["head.ln_b"], cfg.ln_eps)
-    Z = ops.mm(Hm, P["emb.word"].T) + P["head.b_out"]
+    Z = ops.mm(Hm, projection_matrix(P).T) + P["head.b_out"]
     zmax = Z.max(axis=-1, keepdims=True)
     lse = (zmax + np.log(np.exp(Z - zmax).sum(axis=-1, keepdims=True)))[:, 0]
     M = len(pos)
@@ -319,7 +327,7 @@ def head_backward(cfg, P, hc, T, ops):
     g = {}
     g["head.b_out"] = dZ.sum(axis=0)
     g_word_head = ops.mm(dZ.T, hc["Hm"])          # contribution to the tied word matrix
-    dHm = ops.mm(dZ, P["emb.word"])
+    dHm = ops.mm(dZ, projection_matrix(P))
     dGt, g["head.ln_g"], g["head.ln_b"] = layer_norm_backward(dHm, P["head.ln_g"], hc["ln"])
     dUt = dGt * gelu_grad(hc["Ut"])
     g["head.wt"] = ops.mm(dUt.T, hc["Xm"])
