@@ -12,7 +12,11 @@
  * Conventions
  *   - Every function returns 0 on success and a negative mslt_status on error; the message of
  *     the last error of the calling thread is available from mslt_last_error().  A call that
- *     fails validation enqueues no GPU work and leaves every arena untouched.
+ *     fails validation of its arguments (MSLT_ERR_ARG, MSLT_ERR_STATE) enqueues no GPU work and
+ *     leaves every arena untouched.  A step refused for its batch content (MSLT_ERR_DATA) leaves
+ *     parameters, gradients of earlier steps' tensors, moments and step counts untouched, but it
+ *     has used the workspace arena and ends the validity of the previous step's results: the
+ *     gradient read-back, the update and both debug read-backs need a new successful step.
  *   - The library never allocates or frees device memory.  The caller (normally PyTorch) owns
  *     four device arenas whose sizes mslt_query_sizes() reports, and a HIP stream; all GPU work
  *     is ordered with that stream: part of a step runs on a second stream the model creates
@@ -73,6 +77,11 @@ typedef struct {
                           nsp.w [2,H], nsp.b [2] after the masked-LM head in the tensor table; they train in every
                           stage, the step's loss is the sum of the two mean cross-entropies, and every step's batch
                           must bring nsp_labels */
+  int max_trainable_layers; /* largest number of layers one step may train; 0 = n_layers_max.  Only trainable layers keep
+                          intermediates for the backward pass (Section 3.2: the layers below only take part in the
+                          forward computation), so the workspace holds that many per-layer stashes: a model that
+                          only ever runs stages of N/k layers can be given N/k here (BERT-Large, 24 layers, batch
+                          32 x 512: 6 instead of 24 saves about 10 GB); a step that asks for more is refused */
 } mslt_config;
 
 /* One masked-LM batch.  DEVICE pointers to int32 arrays of batch*seq entries, row-major
@@ -134,10 +143,13 @@ int mslt_get_params(const mslt_model* m, float* host_fp32_out, size_t n_floats);
 /* One stage step (Section 3.2): forward through layers [0, frozen+trainable), masked-LM loss,
  * backward through the head and the top `trainable_layers` layers only.  Layers above
  * frozen+trainable are not executed (the stack of an earlier stage is shallower).
- * Requirements: trainable_layers >= 1, frozen_layers >= 0, frozen+trainable <= n_layers_max,
+ * Requirements: trainable_layers >= 1 (and <= max_trainable_layers when that is set), frozen_layers >= 0,
+ * frozen+trainable <= n_layers_max,
  * train_embeddings may be 1 only if frozen_layers == 0, batch <= max_batch, seq <= max_seq,
  * at least one and at most max_predictions predicted positions, ids inside their tables
- * (checked on the device before any other work; violations return MSLT_ERR_DATA).
+ * (checked on the device; the encoder forward is queued meanwhile, reading the tables with clamped
+ * indices, and nothing that a later call can observe is written before the verdict; violations
+ * return MSLT_ERR_DATA).
  * Gradients of exactly the trainable tensors are left in the gradient arena.  *loss_out (HOST)
  * receives the mean loss over predicted positions; the call waits for the stream for this. */
 int mslt_stage_step(mslt_model* m, int frozen_layers, int trainable_layers, int train_embeddings,
@@ -153,7 +165,8 @@ int mslt_get_grads(const mslt_model* m, float* host_fp32_out, size_t n_floats);
  * (Section 3.2: only the new top layers and the output layer are updated; everything is updated
  * in the first stage and in retraining) and refreshes their bf16 shadows.  Frozen tensors, their
  * moments and step counts are not touched.  Enqueues work only; does not block.  A second call
- * without a new step is an error. */
+ * without a new step is an error.  After a step that returned MSLT_ERR_NONFINITE the call is
+ * accepted but its kernels change nothing (they test that step's loss on the device). */
 int mslt_apply_update(mslt_model* m, const mslt_opt* opt);
 
 /* mslt_apply_update() for callers that cannot allocate or hand over scratch memory of their own
@@ -179,7 +192,7 @@ int mslt_apply_update_static(mslt_model* m, const mslt_opt* opt);
 int mslt_train_step(mslt_model* m, int frozen_layers, int trainable_layers, int train_embeddings,
                     const mslt_batch* batch, const mslt_opt* opt, float* loss_out);
 
-/* Dropout for the steps that follow ("all other settings are the same as BERT", Section 4.1:
+/* Dropout for the steps that follow (BERT's dropout, which Section 4.1 adopts by reference:
  * probability 0.1 on the embedding output, the attention probabilities, the attention output and
  * the feed-forward output, in frozen and trainable layers alike).  p in [0, 1); p = 0 (the state
  * after mslt_init_model) switches it off.  The keep decisions are counter-based and reproducible:

@@ -36,7 +36,7 @@ class Config(C.Structure):
                 ("vocab", C.c_int), ("max_pos", C.c_int), ("type_vocab", C.c_int), ("max_batch", C.c_int),
                 ("max_seq", C.c_int), ("max_predictions", C.c_int), ("precision", C.c_int),
                 ("ln_eps", C.c_float), ("mask_bias", C.c_float), ("layers_per_group", C.c_int),
-                ("with_nsp", C.c_int)]
+                ("with_nsp", C.c_int), ("max_trainable_layers", C.c_int)]
 
 
 class Batch(C.Structure):
@@ -107,11 +107,11 @@ def _check(rc, allow=()):
     return rc
 
 
-def make_config(shape, max_batch, max_seq, precision, max_predictions=0) -> Config:
+def make_config(shape, max_batch, max_seq, precision, max_predictions=0, max_trainable_layers=0) -> Config:
     """Config from a synth.ModelShape-like object (n_layers, hidden, n_heads, ffn, vocab, ...)."""
     return Config(shape.n_layers, shape.hidden, shape.n_heads, shape.ffn, shape.vocab, shape.max_pos,
                   shape.type_vocab, max_batch, max_seq, max_predictions, precision, shape.ln_eps, shape.mask_bias,
-                  getattr(shape, "layers_per_group", 1), int(getattr(shape, "nsp", False)))
+                  getattr(shape, "layers_per_group", 1), int(getattr(shape, "nsp", False)), max_trainable_layers)
 
 
 def mslt_query_sizes(cfg: Config):

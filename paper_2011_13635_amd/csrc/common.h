@@ -129,6 +129,7 @@ struct Epilogue {
   void* out2 = nullptr;     // EPI_GELU: GELU'(pre-activation) for the backward pass (st_dgelu format), may be null
   const void* aux = nullptr;  // EPI_MUL: the stored GELU derivative D[m,n] (ld_dgelu format); EPI_ADD: addend R[m,n]
   int ldaux = 0;
+  int aux_f32 = 0;          // EPI_ADD: the addend is fp32 whatever the activation type (wide residual gradients)
   DropSpec drop;            // dropout of (acc + bias) before the activation / addend; element index m * drop_ld + n
   int drop_ld = 0;          // logical row width of the dropped tensor (a multiple of 4)
   int accumulate = 0;       // fp32 output only: out += result (gradient of a parameter set shared by several layers)
@@ -232,9 +233,12 @@ struct LnBwdDrop {
   int accumulate = 0;   // dgamma, dbeta and the column sums are added to what the outputs hold
 };
 // dz from dy, xhat, rstd, gamma; dgamma, dbeta and (if dzsum != null) the column sums of dz (of dzm
-// with output dropout) via partials in scratch (ln_bwd_scratch_floats(rows, H) floats)
+// with output dropout) via partials in scratch (ln_bwd_scratch_floats(rows, H) floats).
+// dy_f32: dy is fp32 whatever the activation type; dz32 (or null): a second, unrounded fp32 copy of dz
+// (the residual branch of the backward pass carries fp32 in bf16 mode, see model.hip).
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
-                  float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s);
+                  float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s,
+                  int dy_f32 = 0, float* dz32 = nullptr);
 // column sums of Y[rows, N] (leading dimension ld) into out[N]; scratch holds ceil(rows/64)*N floats
 hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s,
                   int accumulate = 0);   // accumulate: out += sums
@@ -250,10 +254,11 @@ struct GatherArgs { GatherDesc d[GATHER_MAX]; };
 hipError_t gather_rows_multi(const GatherDesc* descs, int n, const int32_t* pos, int M, int Mpad, hipStream_t s);
 hipError_t scatter_rows(int dtype, const void* dxm, const int32_t* inv, int rows_total, int T, int H, void* out,
                         hipStream_t s);
-// cross-entropy over fp32 logits [Mpad, ldz]: writes dZ (activation type, zero in padded rows and
-// columns), per-row loss and lse; loss_out = mean over M rows in fixed order.
+// cross-entropy over logits [Mpad, ldz] of the activation type: writes dZ (same type, zero in padded rows
+// and columns; dz may be the logits buffer itself), per-row loss and lse; loss_out = mean over the
+// labelled rows in fixed order.
 // (rows whose label is negative are only there for the next-sentence head: zero dZ, no loss; Mn = rows with a label)
-hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mn, int Mpad, int V,
+hipError_t ce_fwd_bwd(int dtype, const void* logits, int ldz, const int32_t* lab, int M, int Mn, int Mpad, int V,
                       void* dz, float* row_loss, float* lse, float* loss_out, hipStream_t s);
 // next-sentence head: small row-wise pieces around its three products
 hipError_t gather_first_tokens(int dtype, const void* x, int S, int H, int n_seq, void* out, hipStream_t s);

@@ -32,7 +32,7 @@ static __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
 }
 // true when the epilogue reads the per-element operand (stored GELU derivative or addend)
 static __device__ __forceinline__ bool epilogue_reads_aux(const Epilogue& e) {
-  return e.act == EPI_MUL || e.act == EPI_ADD;
+  return e.act == EPI_MUL || (e.act == EPI_ADD && !e.aux_f32);   // an fp32 addend is read where it is used
 }
 static __device__ __forceinline__ uint4 load_aux8(const Epilogue& e, int m, int n) {
   return *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(e.aux) + (size_t)m * e.ldaux + n);
@@ -76,10 +76,17 @@ static __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n
       v[2 * i + 1] *= dec_dgelu(w[i] >> 16);
     }
   } else if (e.act == EPI_ADD) {
-    float u[8];
-    unpack8(raw, u);
+    if (e.aux_f32) {
+      const float* a = reinterpret_cast<const float*>(e.aux) + (size_t)m * e.ldaux + n;
+      const float4 a0 = *reinterpret_cast<const float4*>(a), a1 = *reinterpret_cast<const float4*>(a + 4);
+      v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w;
+      v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
+    } else {
+      float u[8];
+      unpack8(raw, u);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] += u[i];
+      for (int i = 0; i < 8; ++i) v[i] += u[i];
+    }
   }
   if (e.out_f32) {
     float* p = reinterpret_cast<float*>(e.out) + o;

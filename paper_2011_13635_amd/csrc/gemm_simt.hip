@@ -19,7 +19,8 @@ __device__ inline void epilogue_store(const Epilogue& e, int m, int n, float acc
   } else if (e.act == EPI_MUL) {
     v *= ld_dgelu(reinterpret_cast<const AT*>(e.aux) + (size_t)m * e.ldaux + n);
   } else if (e.act == EPI_ADD) {
-    v += ldf(reinterpret_cast<const AT*>(e.aux) + (size_t)m * e.ldaux + n);
+    v += e.aux_f32 ? reinterpret_cast<const float*>(e.aux)[(size_t)m * e.ldaux + n]
+                   : ldf(reinterpret_cast<const AT*>(e.aux) + (size_t)m * e.ldaux + n);
   }
   if (e.out_f32)
     reinterpret_cast<float*>(e.out)[o] = e.accumulate ? reinterpret_cast<float*>(e.out)[o] + v : v;

@@ -93,8 +93,13 @@ struct mslt_model {
   void *x0, *xhat0; float* rstd0;
   void *xa, *xb;                       // frozen-prefix ping-pong
   void *s_qkv, *s_ctx, *s_x1, *s_g, *s_y;  // scratch of the forward-only path (+ s_y: pre-LN GEMM output)
-  std::vector<LayerStash> stash;
+  std::vector<LayerStash> stash;       // one per layer that can train in one step (n_stash); layer l of a step uses stash[l - frozen]
+  int n_stash, stash_base;             // stash_base: frozen layer count of the step being queued / of the last step
   void *dxa, *dxb, *d_d, *d_u, *d_x1, *d_z1, *d_c, *d_qkv, *d_z0;
+  // bf16 mode: the residual branch of the backward pass (layer-output gradient, dz2 and dz1 as addends, dx1) is
+  // carried in fp32, so that its rounding does not pile up from layer to layer; the GEMM operands stay bf16
+  bool wide;
+  float *d_d32, *d_z1_32;
   float *delta;
   int32_t *pos, *lab, *inv, *counters;
   void *xm, *ut, *gt, *xhat_t, *hm, *dz, *d_hm, *d_gt, *d_ut, *d_xm;
@@ -279,9 +284,9 @@ static size_t carve(mslt_model* m, char* base) {
   m->xa = b.take<void>(TH); m->xb = b.take<void>(TH);
   m->s_qkv = b.take<void>(3 * TH); m->s_ctx = b.take<void>(TH); m->s_x1 = b.take<void>(TH);
   m->s_g = b.take<void>(TF); m->s_y = b.take<void>(TH);
-  m->stash.resize(m->L);
+  m->stash.resize(m->n_stash);
   size_t lse_bytes = (size_t)m->cfg.max_batch * m->nh * m->cfg.max_seq * 4;
-  for (int l = 0; l < m->L; ++l) {
+  for (int l = 0; l < m->n_stash; ++l) {
     LayerStash& s = m->stash[l];
     s.xout = b.take<void>(TH); s.qkv = b.take<void>(3 * TH); s.ctx = b.take<void>(TH);
     s.xhat1 = b.take<void>(TH); s.x1 = b.take<void>(TH); s.u = b.take<void>(TF); s.g = b.take<void>(TF);
@@ -289,7 +294,8 @@ static size_t carve(mslt_model* m, char* base) {
     s.lse = b.take<float>(lse_bytes); s.rstd1 = b.take<float>(Tp * 4); s.rstd2 = b.take<float>(Tp * 4);
     s.ctx32 = m->dtype ? b.take<float>(Tp * H * 4) : nullptr;
   }
-  m->dxa = b.take<void>(TH); m->dxb = b.take<void>(TH);
+  const size_t TH32 = m->wide ? Tp * H * 4 : TH;
+  m->dxa = b.take<void>(TH32); m->dxb = b.take<void>(TH32);
   for (int i = 0; i < 2; ++i) {
     m->gset[i].d_d = b.take<void>(TH); m->gset[i].d_u = b.take<void>(TF);
     m->gset[i].d_z1 = b.take<void>(TH); m->gset[i].d_qkv = b.take<void>(3 * TH);
@@ -297,18 +303,21 @@ static size_t carve(mslt_model* m, char* base) {
   }
   m->d_d = m->gset[0].d_d; m->d_u = m->gset[0].d_u; m->d_z1 = m->gset[0].d_z1; m->d_qkv = m->gset[0].d_qkv;
   m->d_dm = m->gset[0].d_dm; m->d_z1m = m->gset[0].d_z1m;
-  m->d_x1 = b.take<void>(TH); m->d_c = b.take<void>(TH);
+  m->d_x1 = b.take<void>(TH32); m->d_c = b.take<void>(TH);
+  m->d_d32 = m->wide ? b.take<float>(TH32) : nullptr;
+  m->d_z1_32 = m->wide ? b.take<float>(TH32) : nullptr;
   m->d_z0 = b.take<void>(TH);
   m->delta = b.take<float>(lse_bytes);
   m->pos = b.take<int32_t>((size_t)m->cap * 4); m->lab = b.take<int32_t>((size_t)m->cap * 4);
   m->inv = b.take<int32_t>(Tp * 4); m->counters = b.take<int32_t>(64);
   m->xm = b.take<void>(MH); m->ut = b.take<void>(MH); m->gt = b.take<void>(MH); m->xhat_t = b.take<void>(MH);
-  m->hm = b.take<void>(MH); m->dz = b.take<void>(Mp * Vp * e); m->d_hm = b.take<void>(MH); m->d_gt = b.take<void>(MH);
+  m->hm = b.take<void>(MH); m->d_hm = b.take<void>(MH); m->d_gt = b.take<void>(MH);
   m->d_ut = b.take<void>(MH); m->d_xm = b.take<void>(MH);
   m->c_g = b.take<void>(Mp * F * e); m->c_u = b.take<void>(Mp * F * e); m->c_du = b.take<void>(Mp * F * e);
   m->c_dz2m = b.take<void>(MH); m->c_dz1m = b.take<void>(MH);
   m->c_xhat2 = b.take<void>(MH); m->c_dz2 = b.take<void>(MH); m->c_dc = b.take<void>(MH);
-  m->rstd_t = b.take<float>(Mp * 4); m->logits = b.take<float>(Mp * Vp * 4); m->row_loss = b.take<float>(Mp * 4);
+  m->rstd_t = b.take<float>(Mp * 4); m->logits = b.take<float>(Mp * Vp * 4); m->dz = m->logits;   // dZ overwrites the logits in place
+  m->row_loss = b.take<float>(Mp * 4);
   m->lse_t = b.take<float>(Mp * 4); m->loss = b.take<float>(64);
   {
     const size_t BH = rup((size_t)m->cfg.max_batch, 128) * H * e;
@@ -351,7 +360,7 @@ static size_t carve(mslt_model* m, char* base) {
 static int check_config(const mslt_config* c) {
   if (!c) return fail(MSLT_ERR_ARG, "config is null");
   if (c->n_layers_max < 1 || c->hidden < 4 || c->n_heads < 1 || c->ffn < 4 || c->vocab < 2 || c->max_pos < 1 ||
-      c->type_vocab < 1 || c->max_batch < 1 || c->max_seq < 1 || c->max_predictions < 0)
+      c->type_vocab < 1 || c->max_batch < 1 || c->max_seq < 1 || c->max_predictions < 0 || c->max_trainable_layers < 0)
     return fail(MSLT_ERR_ARG, "config: non-positive dimension");
   if (c->hidden % 4 || c->ffn % 4) return fail(MSLT_ERR_ARG, "config: hidden and ffn must be multiples of 4");
   if (c->hidden > 2048) return fail(MSLT_ERR_ARG, "config: hidden above 2048 is not supported");
@@ -364,6 +373,8 @@ static int check_config(const mslt_config* c) {
   if (!(c->ln_eps >= 0.f)) return fail(MSLT_ERR_ARG, "config: ln_eps must be >= 0");
   if (c->layers_per_group < 0 || (c->layers_per_group > 1 && c->n_layers_max % c->layers_per_group))
     return fail(MSLT_ERR_ARG, "config: n_layers_max must be a multiple of layers_per_group");
+  if (c->layers_per_group > 1 && c->max_trainable_layers % c->layers_per_group)
+    return fail(MSLT_ERR_ARG, "config: max_trainable_layers must be a multiple of layers_per_group");
   return MSLT_OK;
 }
 
@@ -377,11 +388,15 @@ static void setup_dims(mslt_model* m, const mslt_config* cfg) {
   m->lpg = cfg->layers_per_group > 1 ? cfg->layers_per_group : 1;
   m->Lp = m->L / m->lpg;
   m->Vp = (int)rup(cfg->vocab, 128);
+  // frozen layers keep nothing (Section 3.2): the stash is sized by how many layers one step may train
+  m->n_stash = cfg->max_trainable_layers > 0 && cfg->max_trainable_layers < m->L ? cfg->max_trainable_layers : m->L;
+  m->stash_base = 0;
   int T = cfg->max_batch * cfg->max_seq;
   m->cap = cfg->max_predictions > 0 && cfg->max_predictions < T ? cfg->max_predictions : T;
   m->Tp = (int)rup(T, 128);
   m->Mp = (int)rup(m->cap, 128);
   m->mfma = cfg->precision == 1 && cfg->hidden % 128 == 0 && cfg->ffn % 128 == 0;
+  m->wide = cfg->precision == 1;
   build_table(m);
 }
 
@@ -694,12 +709,14 @@ static int linear_fwd(mslt_model* m, const void* X, int rows, int K, const void*
   return run_gemm(m, d, false, st);
 }
 // dX[rows,K] = dY[rows,N] W[N,K]  (+ addend | * gelu'(U))
+// aux_f32 / out_f32: the addend / the result is fp32 whatever the activation type (wide residual gradients)
 static int linear_bwd_input(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* W, int K, void* dX,
-                            int act, const void* aux, bool allow_splitk = true) {
+                            int act, const void* aux, bool allow_splitk = true, int aux_f32 = 0, int out_f32 = 0) {
   GemmDesc d;
   d.A = dY; d.lda = ldy; d.a_kcontig = 1; d.M = rows;
   d.B = W; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = N;
   d.epi.out = dX; d.epi.ldo = K; d.epi.act = act; d.epi.aux = aux; d.epi.ldaux = K;
+  d.epi.aux_f32 = aux_f32; d.epi.out_f32 = out_f32;
   return run_gemm(m, d, allow_splitk);
 }
 // dW[N,K] = dY[rows,N]^T X[rows,K]   (fp32 out, contraction over rows)
@@ -783,12 +800,15 @@ static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, flo
   return MSLT_OK;
 }
 // dzsum (may be null): column sums of dz = bias gradient of the linear layer feeding this LayerNorm
+// dy_f32: dy is fp32; dz32 (or null): fp32 copy of dz (both only in bf16 mode, see mslt_model::wide)
 static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz,
-                       float* dg, float* db, float* dzsum, int rows, const LnBwdDrop& dd_in = LnBwdDrop()) {
-  ProfScope ps(m, PC_LN_BWD, 0.0, (dd_in.out.thr ? 4.0 : 3.0) * rows * m->H * m->esz);
+                       float* dg, float* db, float* dzsum, int rows, const LnBwdDrop& dd_in = LnBwdDrop(), int dy_f32 = 0,
+                       float* dz32 = nullptr) {
+  ProfScope ps(m, PC_LN_BWD, 0.0, ((dd_in.out.thr ? 3.0 : 2.0) * m->esz + (dy_f32 ? 4.0 : (double)m->esz) + (dz32 ? 4.0 : 0.0)) *
+                                      rows * m->H);
   LnBwdDrop dd = dd_in;
   dd.accumulate = m->acc_now;
-  HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, dd, m->stream));
+  HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, dd, m->stream, dy_f32, dz32));
   return MSLT_OK;
 }
 
@@ -803,6 +823,9 @@ struct UpperRows {
   void *dz2m, *dz1m;                             // dz2, dz1 times the dropout keep factors (used when dropout is on)
   const int32_t* rowmap;                         // token row of each compacted row, or null
   int n_mapped;
+  // wide residual branch (dense rows in bf16 mode): dXout and dx1 are fp32, dz2_32 / dz1_32 receive fp32 copies
+  int wide;
+  float *dz2_32, *dz1_32;
 };
 static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const UpperRows& r) {
   const int H = m->H, F = m->F, R = r.rows;
@@ -814,16 +837,17 @@ static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const U
   const void* dy2 = d2.out.thr ? r.dz2m : r.dz2;
   const void* dy1 = d1.out.thr ? r.dz1m : r.dz1;
   RC(ln_backward(m, dXout, r.xhat2, r.rstd2, Wf(m, t_app(m, l, L_LN2G)), r.dz2, Gf(m, t_app(m, l, L_LN2G)),
-                 Gf(m, t_app(m, l, L_LN2B)), Gf(m, t_app(m, l, L_B2)), R, d2));
+                 Gf(m, t_app(m, l, L_LN2B)), Gf(m, t_app(m, l, L_B2)), R, d2, r.wide, r.dz2_32));
   // one fork for the three side products of the feed-forward part (W2's waits for the data gradient
   // of the second linear layer: the side stream has a backlog anyway, and every fork stalls this stream)
   RC(linear_bwd_input(m, dy2, R, H, H, Wg(m, t_app(m, l, L_W2)), F, r.du, EPI_MUL, r.u));
   RC(linear_bwd_weight(m, dy2, R, H, H, r.g, F, Gf(m, t_app(m, l, L_W2))));
   RC(linear_bwd_weight(m, r.du, R, F, F, r.x1, H, Gf(m, t_app(m, l, L_W1)), true));
   RC(bias_grad(m, r.du, F, R, F, Gf(m, t_app(m, l, L_B1)), true));
-  RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_app(m, l, L_W1)), H, r.dx1, EPI_ADD, r.dz2));
+  RC(linear_bwd_input(m, r.du, R, F, F, Wg(m, t_app(m, l, L_W1)), H, r.dx1, EPI_ADD, r.wide ? (const void*)r.dz2_32 : r.dz2, true,
+                      r.wide, r.wide));
   RC(ln_backward(m, r.dx1, r.xhat1, r.rstd1, Wf(m, t_app(m, l, L_LN1G)), r.dz1, Gf(m, t_app(m, l, L_LN1G)),
-                 Gf(m, t_app(m, l, L_LN1B)), Gf(m, t_app(m, l, L_BO)), R, d1));
+                 Gf(m, t_app(m, l, L_LN1B)), Gf(m, t_app(m, l, L_BO)), R, d1, r.wide, r.dz1_32));
   RC(linear_bwd_weight(m, dy1, R, H, H, r.ctx, H, Gf(m, t_app(m, l, L_WO))));
   RC(linear_bwd_input(m, dy1, R, H, H, Wg(m, t_app(m, l, L_WO)), H, r.dc, EPI_NONE, nullptr));
   return MSLT_OK;
@@ -831,9 +855,11 @@ static int layer_backward_upper(mslt_model* m, int l, const void* dXout, const U
 // Attention backward and the QKV projection backward, from dC and dz1 (both [Tr, H], all token rows).
 // dXin: where to put the gradient w.r.t. the layer input, or null when nothing below needs it
 // (the block below is frozen: Section 3.1).
-static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, void* dXin) {
+// resid: dz1, the residual addend of dXin (fp32 if resid_f32); dXin itself is fp32 in bf16 mode (mslt_model::wide).
+static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, void* dXin,
+                                const void* resid, int resid_f32) {
   const int H = m->H;
-  const LayerStash& st = m->stash[l];
+  const LayerStash& st = m->stash[l - m->stash_base];
   hipStream_t s = m->stream;
   AttnBwdDesc a{st.qkv, st.ctx, m->d_c, st.lse, m->delta, m->d_qkv, bt->attn_mask, bt->batch, bt->seq, m->nh, m->dh,
                 m->cfg.mask_bias, dspec(m, l, SITE_ATTN_PROBS), st.ctx32};
@@ -849,18 +875,19 @@ static int layer_backward_lower(mslt_model* m, int l, const mslt_batch* bt, int 
   }
   RC(linear_bwd_weight(m, m->d_qkv, Tr, 3 * H, 3 * H, Xin, H, Gf(m, t_app(m, l, L_WQ))));
   RC(bias_grad(m, m->d_qkv, 3 * H, Tr, 3 * H, Gf(m, t_app(m, l, L_BQ)), true));
-  if (dXin) RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_app(m, l, L_WQ)), H, dXin, EPI_ADD, m->d_z1));
+  if (dXin)
+    RC(linear_bwd_input(m, m->d_qkv, Tr, 3 * H, 3 * H, Wg(m, t_app(m, l, L_WQ)), H, dXin, EPI_ADD, resid, true, resid_f32, m->wide));
   return layer_backward_end(m, l);
 }
 // dXout: gradient w.r.t. the layer output on all token rows.
 static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, const void* Xin, const void* dXout,
                           void* dXin) {
-  const LayerStash& st = m->stash[l];
+  const LayerStash& st = m->stash[l - m->stash_base];
   RC(layer_backward_begin(m, l));
   UpperRows r{st.xhat2, st.g, st.u, st.x1, st.xhat1, st.ctx, st.rstd2, st.rstd1, m->d_d, m->d_u, m->d_x1, m->d_z1, m->d_c, Tr,
-              m->d_dm, m->d_z1m, nullptr, 0};
+              m->d_dm, m->d_z1m, nullptr, 0, m->wide, m->d_d32, m->d_z1_32};
   RC(layer_backward_upper(m, l, dXout, r));
-  return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin);
+  return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin, m->wide ? (const void*)m->d_z1_32 : m->d_z1, m->wide);
 }
 // Top trainable layer: the gradient of its output is non-zero only in the M predicted rows, and
 // everything above the attention is row-local, so that part runs on the compacted rows (exact, not
@@ -868,7 +895,7 @@ static int layer_backward(mslt_model* m, int l, const mslt_batch* bt, int T, int
 static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T, int Tr, int M, int Mr, const void* Xin,
                               const void* dXm, void* dXin) {
   const int H = m->H, F = m->F;
-  const LayerStash& st = m->stash[l];
+  const LayerStash& st = m->stash[l - m->stash_base];
   hipStream_t s = m->stream;
   RC(layer_backward_begin(m, l));
   {
@@ -879,14 +906,14 @@ static int layer_backward_top(mslt_model* m, int l, const mslt_batch* bt, int T,
     HIP_TRY(gather_rows_multi(g, 8, m->pos, M, Mr, s));
   }
   UpperRows r{m->c_xhat2, m->c_g, m->c_u, m->ut, m->gt, m->xhat_t, m->rstd_t, m->lse_t,
-              m->c_dz2, m->c_du, m->d_hm, m->d_gt, m->c_dc, Mr, m->c_dz2m, m->c_dz1m, m->pos, M};
+              m->c_dz2, m->c_du, m->d_hm, m->d_gt, m->c_dc, Mr, m->c_dz2m, m->c_dz1m, m->pos, M, 0, nullptr, nullptr};
   RC(layer_backward_upper(m, l, dXm, r));
   {
     ProfScope ps(m, PC_HEAD_MISC, 0.0, 2.0 * ((double)Tr + M) * H * m->esz);
     HIP_TRY(scatter_rows(m->dtype, m->c_dc, m->inv, Tr, T, H, m->d_c, s));
     HIP_TRY(scatter_rows(m->dtype, m->d_gt, m->inv, Tr, T, H, m->d_z1, s));
   }
-  return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin);
+  return layer_backward_lower(m, l, bt, T, Tr, Xin, dXin, m->d_z1, 0);
 }
 
 // ---- the stage step -------------------------------------------------------------------------
@@ -895,6 +922,8 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   if (!m || !bt) return fail(MSLT_ERR_ARG, "null argument");
   if (k < 1 || f < 0 || f + k > m->L)
     return fail(MSLT_ERR_ARG, "stage_step: bad layer split frozen=%d trainable=%d (layers %d)", f, k, m->L);
+  if (k > m->n_stash)
+    return fail(MSLT_ERR_ARG, "stage_step: %d trainable layers exceed max_trainable_layers %d of the configuration", k, m->n_stash);
   if (train_emb != 0 && train_emb != 1) return fail(MSLT_ERR_ARG, "stage_step: train_embeddings must be 0 or 1");
   if (train_emb && f != 0) return fail(MSLT_ERR_ARG, "stage_step: embeddings train only when nothing is frozen");
   if (f % m->lpg || k % m->lpg)
@@ -910,6 +939,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   const int H = m->H, B = bt->batch, S = bt->seq, T = B * S;
   m->have_grads = false;
   m->acc_now = 0;
+  m->stash_base = f;
 
   // S0: batch check and compaction of the predicted positions (only index scratch is written)
   HIP_TRY(batch_scan(bt->input_ids, bt->token_type_ids, bt->attn_mask, bt->labels, T, m->V, m->cfg.type_vocab, m->cap,
@@ -959,8 +989,8 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   m->last_prefix = x;
   // S3: trainable layers, with stash
   for (int l = f; l < f + k; ++l) {
-    RC(forward(l, x, m->stash[l].xout, &m->stash[l]));
-    x = m->stash[l].xout;
+    RC(forward(l, x, m->stash[l - f].xout, &m->stash[l - f]));
+    x = m->stash[l - f].xout;
   }
   if (halves) RC(side_join(m));
   HIP_TRY(hipEventSynchronize(m->ev_scan));
@@ -968,6 +998,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   // Mn: those of them that carry a masked-LM label
   const int M = m->h_counters[0], bad = m->h_counters[1], Mn = m->h_counters[2];
   if (bad || Mn < 1 || M > m->cap) {
+    m->last_prefix = nullptr;           // the workspace now holds the rejected batch's activations
     HIP_TRY(hipStreamSynchronize(s));   // let the queued forward drain before reporting
     if (bad)
       return fail(MSLT_ERR_DATA, "stage_step: batch content out of range (bits %d: 1 id, 2 type, 4 label, 8 mask, 16 nsp label)", bad);
@@ -985,9 +1016,9 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   RC(linear_fwd(m, m->xm, Mr, H, Wg(m, th + H_WT), H, Wf(m, th + H_BT), m->gt, 0, H, EPI_GELU, m->ut));
   LnStash sh{m->xhat_t, m->rstd_t};
   RC(ln_forward(m, m->gt, nullptr, Wf(m, th + H_LNG), Wf(m, th + H_LNB), m->hm, sh, Mr));
-  RC(linear_fwd(m, m->hm, Mr, H, Wg(m, T_WORD), Vr, Wf(m, th + H_BOUT), m->logits, 1, m->Vp, EPI_NONE, nullptr));
+  RC(linear_fwd(m, m->hm, Mr, H, Wg(m, T_WORD), Vr, Wf(m, th + H_BOUT), m->logits, 0, m->Vp, EPI_NONE, nullptr));
   {
-    ProfScope ps(m, PC_CE, 0.0, (double)M * m->V * 4.0 + (double)Mr * m->Vp * m->esz);
+    ProfScope ps(m, PC_CE, 0.0, (double)M * m->V * m->esz + (double)Mr * m->Vp * m->esz);
     HIP_TRY(ce_fwd_bwd(m->dtype, m->logits, m->Vp, m->lab, M, Mn, Mr, m->V, m->dz, m->row_loss, m->lse_t, m->loss, s));
   }
   if (m->nsp) {
@@ -1031,7 +1062,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   // and scatters inside; the layers below get dense gradients.
   void* dx = m->dxa;
   for (int l = f + k - 1; l >= f; --l) {
-    const void* xin = (l == f) ? m->last_prefix : m->stash[l - 1].xout;
+    const void* xin = (l == f) ? m->last_prefix : m->stash[l - 1 - f].xout;
     bool need_dx = (l > f) || train_emb;
     void* dxin = need_dx ? (dx == m->dxa ? m->dxb : m->dxa) : nullptr;
     if (l == f + k - 1)
@@ -1045,7 +1076,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   if (train_emb) {
     LnBwdDrop de;
     de.in = dspec(m, 0, SITE_EMBEDDING);
-    RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), nullptr, T, de));
+    RC(ln_backward(m, dx, m->xhat0, m->rstd0, Wf(m, T_ELN_G), m->d_z0, Gf(m, T_ELN_G), Gf(m, T_ELN_B), nullptr, T, de, m->wide));
     ProfScope ps(m, PC_EMBED_BWD, 0.0, (double)T * H * (m->esz + 8.0));
     HIP_TRY(embed_bwd(m->dtype, m->d_z0, bt->input_ids, bt->token_type_ids, B, S, H, m->V, m->cfg.type_vocab,
                       Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order, m->e_blockcnt,
@@ -1145,7 +1176,9 @@ extern "C" int mslt_apply_update(mslt_model* m, const mslt_opt* opt) {
   if (!m || !opt) return fail(MSLT_ERR_ARG, "null argument");
   if (!m->have_grads) return fail(MSLT_ERR_STATE, "apply_update: no gradients from a preceding stage_step");
   RC(check_opt(opt, "apply_update"));
-  RC(update_enqueue(m, opt, nullptr));
+  // gated on the device by the loss of the step whose gradients these are: after a step that returned
+  // MSLT_ERR_NONFINITE the update kernels do nothing, as in mslt_train_step
+  RC(update_enqueue(m, opt, m->loss));
   m->have_grads = false;
   return MSLT_OK;
 }
@@ -1158,7 +1191,7 @@ extern "C" int mslt_apply_update_static(mslt_model* m, const mslt_opt* opt) {
     return fail(MSLT_ERR_ARG, "apply_update_static: model has %d optimizer chunks and %d tensors, the static scratch holds %d and %d",
                 m->first_chunk.back(), (int)m->table.size(), STATIC_MAX_CHUNKS, STATIC_MAX_TENSORS);
   // every chunk sum and ratio the update reads is written earlier in the same call: nothing to clear
-  RC(update_enqueue(m, opt, nullptr, m->static_scratch, m->static_scratch + (size_t)2 * STATIC_MAX_CHUNKS));
+  RC(update_enqueue(m, opt, m->loss, m->static_scratch, m->static_scratch + (size_t)2 * STATIC_MAX_CHUNKS));
   m->have_grads = false;
   return MSLT_OK;
 }

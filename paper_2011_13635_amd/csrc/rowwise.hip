@@ -353,10 +353,11 @@ size_t ln_bwd_scratch_floats(int rows, int H) {
 }
 
 // DROP: the dropout variants are a second compiled copy, so that the plain kernel carries none of their code
-template <typename AT, int NV, int R, bool DROP>
-__global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const AT* __restrict__ xhat,
+// DYT: type of dy (the activation type, or float for the wide residual gradient); dz32: optional fp32 copy of dz
+template <typename AT, typename DYT, int NV, int R, bool DROP>
+__global__ void __launch_bounds__(256) k_ln_bwd(const DYT* __restrict__ dy, const AT* __restrict__ xhat,
                                                 const float* __restrict__ rstd, const float* __restrict__ g,
-                                                AT* __restrict__ dz, float* __restrict__ part_g,
+                                                AT* __restrict__ dz, float* __restrict__ dz32, float* __restrict__ part_g,
                                                 float* __restrict__ part_b, float* __restrict__ part_z, int rows,
                                                 int H, LnBwdDrop dd) {
   __shared__ float red[3][256 * NV];
@@ -426,6 +427,7 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
           float4 o = make_float4((y.x - m1 - xx.x * m2) * rs[rr], (y.y - m1 - xx.y * m2) * rs[rr],
                                  (y.z - m1 - xx.z * m2) * rs[rr], (y.w - m1 - xx.w * m2) * rs[rr]);
           store4(dz + (size_t)row * H + c, o);
+          if (dz32) *reinterpret_cast<float4*>(dz32 + (size_t)row * H + c) = o;
           if (DROP && dd.out.thr) {
             o = mul4(o, drop4(dd.out, tok * H + c));
             store4(reinterpret_cast<AT*>(dd.dzm) + (size_t)row * H + c, o);
@@ -463,9 +465,9 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const AT* __restrict__ dy, const
     __syncthreads();
   }
 }
-template <typename AT>
-static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, const float* g, AT* dz, float* dg, float* db,
-                           float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s) {
+template <typename AT, typename DYT>
+static hipError_t ln_bwd_t(const DYT* dy, const AT* xhat, const float* rstd, const float* g, AT* dz, float* dz32, float* dg,
+                           float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s) {
   if (dd.out.thr && dd.dzm == nullptr) return hipErrorInvalidValue;
   if ((dd.out.thr || dd.in.thr) && H % 4) return hipErrorInvalidValue;
   int R = lnb_rows_per_wave(H);
@@ -474,10 +476,10 @@ static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, cons
   float* pb = pg + (size_t)nb * H;
   float* pz = pb + (size_t)nb * H;
   const bool drop = dd.in.thr || dd.out.thr;
-#define MSLT_LNB(NV, R)                                                                                         \
-  do {                                                                                                          \
-    if (drop) k_ln_bwd<AT, NV, R, true><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd);  \
-    else k_ln_bwd<AT, NV, R, false><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, pg, pb, pz, rows, H, dd);      \
+#define MSLT_LNB(NV, R)                                                                                                   \
+  do {                                                                                                                    \
+    if (drop) k_ln_bwd<AT, DYT, NV, R, true><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, dz32, pg, pb, pz, rows, H, dd);  \
+    else k_ln_bwd<AT, DYT, NV, R, false><<<dim3(nb), dim3(256), 0, s>>>(dy, xhat, rstd, g, dz, dz32, pg, pb, pz, rows, H, dd);      \
   } while (0)
   switch (ln_nv(H)) {
     case 2: MSLT_LNB(2, 4); break;
@@ -492,10 +494,15 @@ static hipError_t ln_bwd_t(const AT* dy, const AT* xhat, const float* rstd, cons
   return hipGetLastError();
 }
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
-                  float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s) {
+                  float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s, int dy_f32,
+                  float* dz32) {
   if (dtype == 0)
-    return ln_bwd_t<float>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, dg, db, dzsum, scratch, rows, H, dd, s);
-  return ln_bwd_t<bf16>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dg, db, dzsum, scratch, rows, H, dd, s);
+    return ln_bwd_t<float, float>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, dz32, dg, db, dzsum, scratch, rows,
+                                  H, dd, s);
+  if (dy_f32)
+    return ln_bwd_t<bf16, float>((const float*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dz32, dg, db, dzsum, scratch, rows, H,
+                                 dd, s);
+  return ln_bwd_t<bf16, bf16>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dz32, dg, db, dzsum, scratch, rows, H, dd, s);
 }
 
 // ---- column sums (bias gradients) -----------------------------------------------------------
@@ -677,9 +684,14 @@ __device__ inline float block_reduce_max_256(float v, float* sh) {
   return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
 }
 
+// Cross-entropy over the logits of the predicted rows, forward and backward in one pass per row.  The
+// logits are of the activation type (bf16 logits halve the traffic of the largest tensor of the head;
+// their rounding, 2^-9 relative per logit, averages out in the log-sum-exp and is an order below the
+// rounding of dZ itself).  dz may be the logits buffer itself: a row is overwritten only after the
+// kernel has taken everything it needs from it.
 template <typename AT>
-__global__ void __launch_bounds__(256) k_ce(const float* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
-                                            int M, int Mn, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
+__global__ void __launch_bounds__(256) k_ce(const AT* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
+                                            int M, int Mn, int V, AT* dz, float* __restrict__ row_loss,
                                             float* __restrict__ lse_out) {
   __shared__ float sh[4];
   int j = blockIdx.x;
@@ -689,33 +701,36 @@ __global__ void __launch_bounds__(256) k_ce(const float* __restrict__ logits, in
     if (j < M && threadIdx.x == 0) { row_loss[j] = 0.f; lse_out[j] = 0.f; }
     return;
   }
-  const float* z = logits + (size_t)j * ldz;
+  const AT* z = logits + (size_t)j * ldz;
   float mx = -INFINITY;
-  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, z[c]);
+  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, ldf(z + c));
   mx = block_reduce_max_256(mx, sh);
   float se = 0.f;
-  for (int c = threadIdx.x; c < V; c += 256) se += __expf(z[c] - mx);
+  for (int c = threadIdx.x; c < V; c += 256) se += __expf(ldf(z + c) - mx);
   se = block_reduce_sum_256(se, sh);
   float lse = mx + __logf(se);
   int y = lab[j];
+  const float zy = ldf(z + y);     // before the row is overwritten (dz may alias the logits)
+  __syncthreads();
   float invM = 1.0f / (float)Mn;
   for (int c = threadIdx.x; c < ldz; c += 256) {
     float v = 0.f;
-    if (c < V) v = (__expf(z[c] - lse) - (c == y ? 1.0f : 0.0f)) * invM;
+    if (c < V) v = (__expf(ldf(z + c) - lse) - (c == y ? 1.0f : 0.0f)) * invM;
     stf(d + c, v);
   }
   if (threadIdx.x == 0) {
-    row_loss[j] = lse - z[y];
+    row_loss[j] = lse - zy;
     lse_out[j] = lse;
   }
 }
-// Same, with the row of logits resident in LDS (V*4 bytes of dynamic LDS): one global read of the
+// Same, with the row of logits resident in LDS (V elements of dynamic LDS): one global read of the
 // logits and one write of dZ per row, 1024 threads per row.
 template <typename AT>
-__global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
-                                                 int M, int Mn, int V, AT* __restrict__ dz, float* __restrict__ row_loss,
+__global__ void __launch_bounds__(1024) k_ce_lds(const AT* __restrict__ logits, int ldz, const int32_t* __restrict__ lab,
+                                                 int M, int Mn, int V, AT* dz, float* __restrict__ row_loss,
                                                  float* __restrict__ lse_out) {
-  extern __shared__ __attribute__((aligned(16))) float row[];
+  extern __shared__ __attribute__((aligned(16))) unsigned char row_raw[];
+  AT* row = reinterpret_cast<AT*>(row_raw);
   __shared__ float sh[16];
   const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   AT* d = dz + (size_t)j * ldz;
@@ -724,17 +739,17 @@ __global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logit
     if (j < M && tid == 0) { row_loss[j] = 0.f; lse_out[j] = 0.f; }
     return;
   }
-  const float* z = logits + (size_t)j * ldz;
+  const AT* z = logits + (size_t)j * ldz;
   const int V4 = V & ~3;
   float mx = -INFINITY;
   for (int c = tid * 4; c < V4; c += 4096) {
     float4 v = load4(z + c);
-    *reinterpret_cast<float4*>(row + c) = v;
+    store4(row + c, v);              // exact: the values are of type AT already
     mx = fmaxf(mx, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
   }
   for (int c = V4 + tid; c < V; c += 1024) {
-    float v = z[c];
-    row[c] = v;
+    float v = ldf(z + c);
+    stf(row + c, v);
     mx = fmaxf(mx, v);
   }
   mx = wave_max(mx);
@@ -744,7 +759,7 @@ __global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logit
 #pragma unroll
   for (int w = 1; w < 16; ++w) mx = fmaxf(mx, sh[w]);
   float se = 0.f;
-  for (int c = tid; c < V; c += 1024) se += __expf(row[c] - mx);
+  for (int c = tid; c < V; c += 1024) se += __expf(ldf(row + c) - mx);
   se = wave_sum(se);
   __syncthreads();
   if (lane == 0) sh[wave] = se;
@@ -760,12 +775,12 @@ __global__ void __launch_bounds__(1024) k_ce_lds(const float* __restrict__ logit
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       int cc = c + i;
-      o[i] = cc < V ? (__expf(row[cc] - lse) - (cc == y ? 1.0f : 0.0f)) * invM : 0.f;
+      o[i] = cc < V ? (__expf(ldf(row + cc) - lse) - (cc == y ? 1.0f : 0.0f)) * invM : 0.f;
     }
     store4(d + c, make_float4(o[0], o[1], o[2], o[3]));
   }
   if (tid == 0) {
-    row_loss[j] = lse - row[y];
+    row_loss[j] = lse - ldf(row + y);
     lse_out[j] = lse;
   }
 }
@@ -781,9 +796,9 @@ __global__ void __launch_bounds__(256) k_mean_rows(const float* __restrict__ v, 
   }
   if (threadIdx.x == 0) *out = sh[0] / (float)Mn;     // mean over the rows that carry a label
 }
-hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* lab, int M, int Mn, int Mpad, int V,
+hipError_t ce_fwd_bwd(int dtype, const void* logits, int ldz, const int32_t* lab, int M, int Mn, int Mpad, int V,
                       void* dz, float* row_loss, float* lse, float* loss_out, hipStream_t s) {
-  const size_t row_bytes = (size_t)V * 4;
+  const size_t row_bytes = (size_t)V * (dtype ? 2 : 4);
   hipError_t e;
   if (row_bytes <= 150 * 1024 && ldz % 4 == 0) {
     static bool attr_set = false;
@@ -795,13 +810,13 @@ hipError_t ce_fwd_bwd(int dtype, const float* logits, int ldz, const int32_t* la
       attr_set = true;
     }
     if (dtype == 0)
-      k_ce_lds<float><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, Mn, V, (float*)dz, row_loss, lse);
+      k_ce_lds<float><<<dim3(Mpad), dim3(1024), row_bytes, s>>>((const float*)logits, ldz, lab, M, Mn, V, (float*)dz, row_loss, lse);
     else
-      k_ce_lds<bf16><<<dim3(Mpad), dim3(1024), row_bytes, s>>>(logits, ldz, lab, M, Mn, V, (bf16*)dz, row_loss, lse);
+      k_ce_lds<bf16><<<dim3(Mpad), dim3(1024), row_bytes, s>>>((const bf16*)logits, ldz, lab, M, Mn, V, (bf16*)dz, row_loss, lse);
   } else if (dtype == 0) {
-    k_ce<float><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, Mn, V, (float*)dz, row_loss, lse);
+    k_ce<float><<<dim3(Mpad), dim3(256), 0, s>>>((const float*)logits, ldz, lab, M, Mn, V, (float*)dz, row_loss, lse);
   } else {
-    k_ce<bf16><<<dim3(Mpad), dim3(256), 0, s>>>(logits, ldz, lab, M, Mn, V, (bf16*)dz, row_loss, lse);
+    k_ce<bf16><<<dim3(Mpad), dim3(256), 0, s>>>((const bf16*)logits, ldz, lab, M, Mn, V, (bf16*)dz, row_loss, lse);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;

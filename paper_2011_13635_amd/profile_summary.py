@@ -39,13 +39,13 @@ def table(rows, command: str = "", per_step: int = 0) -> str:
     lines.append(f"{'calls':>7} {'total_us':>11} {'avg_us':>9} {'min_us':>9} {'max_us':>9} {'%':>6}  kernel")
     for name, n, tot, avg, mn, mx in rows:
         lines.append(f"{n:7d} {tot / 1e3:11.1f} {avg / 1e3:9.2f} {mn / 1e3:9.2f} {mx / 1e3:9.2f} {100 * tot / total:6.2f}  {name}")
-    # the MFMA GEMM is one templated kernel: its variants together, for comparison with bench.py's avg_launch_us
-    g = [r for r in rows if "k_gemm_mfma" in r[0]]
+    # the MFMA GEMMs are two templated kernels: their variants together, for comparison with bench.py's avg_launch_us
+    g = [r for r in rows if "k_gemm_mfma" in r[0] or "k_gemm_ring" in r[0]]
     if g:
         n, tot = sum(r[1] for r in g), sum(r[2] for r in g)
-        lines.append(f"k_gemm_mfma, all variants: {n} dispatches, avg {tot / n / 1e3:.2f} us, {100 * tot / total:.2f} % of kernel time")
+        lines.append(f"GEMM kernels (k_gemm_ring + k_gemm_mfma), all variants: {n} dispatches, avg {tot / n / 1e3:.2f} us, {100 * tot / total:.2f} % of kernel time")
         if per_step:
-            lines.append(f"k_gemm_mfma per step: {n / per_step:.1f} dispatches, {tot / per_step / 1e6:.4f} ms"
+            lines.append(f"GEMM kernels per step: {n / per_step:.1f} dispatches, {tot / per_step / 1e6:.4f} ms"
                          f" (+ k_splitk_reduce {sum(r[2] for r in rows if 'k_splitk_reduce' in r[0]) / per_step / 1e6:.4f} ms)")
     return "\n".join(lines) + "\n"
 

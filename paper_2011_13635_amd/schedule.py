@@ -1,4 +1,5 @@
-"""The whole multi-stage schedule driven through the C ABI (Section 3.2, Figure 1; counts of Section 4.1).
+"""The whole multi-stage schedule driven through the C ABI (Section 3.2, Figure 1; k and the layers per stage
+from Section 4.1, step counts and warm-up from Section 4.2).
 
 The training of an N-layer encoder is cut into k stages.  Stage 1 trains a stack of N/k layers completely
 (embeddings included).  Every later stage grows the stack by N/k layers, initialised as copies of the N/k
@@ -36,7 +37,8 @@ def mslt_schedule(n_layers: int, k: int, steps_per_stage: int, retrain_steps: in
                   retrain_lr: Optional[float] = None) -> List[Stage]:
     """Stages of Section 3.2 for an n_layers encoder trained in k stages plus joint retraining.
 
-    With the counts of Section 4.1 (k = 4, 200 000 steps per stage, 200 000 retraining steps) this gives
+    With k = 4 (Section 4.1) and the step counts of Section 4.2 (200 000 steps per stage, 200 000 retraining
+    steps) this gives
     3 layers per stage for BERT-Base and 6 for BERT-Large, 1 000 000 steps in total.
     """
     if k < 1 or n_layers % k:

@@ -9,6 +9,31 @@ from paper_2011_13635_amd import binding, synth
 TOL = {0: 1e-4, 1: 2e-2}
 
 
+# second bf16-mode tolerance: against the oracle fed with the very bf16-rounded matrices the matrix cores consume,
+# which leaves only the arithmetic of the kernels (rounded activations and gradients, summation order)
+KERNEL_TOL = 1.2e-2
+
+
+def bf16_round(a):
+    """fp32 -> bf16 -> fp32, round to nearest even (numpy bit arithmetic)."""
+    a32 = np.ascontiguousarray(a, dtype=np.float32)
+    u = a32.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a32.shape)
+
+
+def rounded_weights(W):
+    """The parameters as the library's bf16 mode reads them: the matrices that feed the matrix cores rounded to
+    bf16 (encoder and head matrices, and the word matrix in its role as output projection), everything else
+    (biases, LayerNorm parameters, the embedding tables of the lookup) as the fp32 masters."""
+    out = dict(W)
+    for n, v in W.items():
+        if v.ndim == 2 and not n.startswith("emb."):
+            out[n] = bf16_round(v)
+    out["head.proj_word"] = bf16_round(W["emb.word"])
+    return out
+
+
 def make_model(shape, B, S, precision, max_predictions=0):
     cfg = binding.make_config(shape, B, S, precision, max_predictions)
     return binding.Model(cfg)
@@ -38,7 +63,7 @@ def rel_errors(g_gpu, g_ref):
 
 
 def run_case(shape, B, S, f, k, emb, precision, ragged=False, seed=0, std=0.02, perturb=0.0, full_backprop=True,
-             model=None, weights=None, dropout=None):
+             model=None, weights=None, dropout=None, rounded_oracle=False):
     """Returns dict with loss / grads of both sides for one step on seeded inputs."""
     W = weights if weights is not None else synth.make_weights(shape, seed=seed, std=std, perturb=perturb)
     batch = synth.make_batch(shape, B, S, seed=seed + 1, ragged=ragged)
@@ -56,8 +81,12 @@ def run_case(shape, B, S, f, k, emb, precision, ragged=False, seed=0, std=0.02, 
     pos, lab = model.mslt_debug_masked()
     prefix = model.mslt_debug_prefix_output(B, S)
     ref_loss, ref_g, info = O.stage_step(shape, W, batch, f, k, emb, full_backprop=full_backprop, drop=drop)
-    return {"model": model, "W": W, "batch": batch, "cb": cb, "loss": loss, "grads": g, "pos": pos, "lab": lab,
-            "prefix": prefix, "ref_loss": ref_loss, "ref_grads": ref_g, "ref_info": info}
+    out = {"model": model, "W": W, "batch": batch, "cb": cb, "loss": loss, "grads": g, "pos": pos, "lab": lab,
+           "prefix": prefix, "ref_loss": ref_loss, "ref_grads": ref_g, "ref_info": info}
+    if rounded_oracle:     # the same step of the oracle on the matrices as bf16 mode reads them
+        out["rnd_loss"], out["rnd_grads"], _ = O.stage_step(shape, rounded_weights(W), batch, f, k, emb,
+                                                            full_backprop=full_backprop, drop=drop)
+    return out
 
 
 def assert_parity(r, precision, label=""):
@@ -76,4 +105,10 @@ def assert_parity(r, precision, label=""):
     ref_p = r["ref_info"]["prefix_out"]
     perr = np.abs(r["prefix"] - ref_p).max() / np.abs(ref_p).max()
     assert perr < tol, (label, "prefix", perr)
+    if "rnd_grads" in r:
+        kerrs = rel_errors(r["grads"], r["rnd_grads"])
+        kworst = max(kerrs, key=kerrs.get)
+        assert kerrs[kworst] < KERNEL_TOL, (label, "against the oracle on rounded matrices", kworst, kerrs[kworst])
+        assert abs(r["loss"] - r["rnd_loss"]) / abs(r["rnd_loss"]) < KERNEL_TOL, (label, "loss, rounded matrices")
+        return lerr, errs[worst], worst, kerrs[kworst], kworst
     return lerr, errs[worst], worst

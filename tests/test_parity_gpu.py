@@ -38,14 +38,16 @@ def test_tiny_splits_perturbed_ragged(precision, f, k, emb):
     r["model"].close()
 
 
+@pytest.mark.parametrize("B,S", [(3, 10), (11, 13)])
 @pytest.mark.parametrize("precision", [0, 1])
-def test_unaligned_shapes_full_step(precision):
+def test_unaligned_shapes_full_step(precision, B, S):
     sh = small_shape(2)
     std, perturb = (0.2, 0.2) if precision == 0 else (0.05, 0.05)
-    # 11 x 13 tokens: on a 3 x 10 batch the max-norm error of the small attention gradients in bf16 mode is set
-    # by a handful of roundings and scatters between 1e-2 and 2.2e-2 from seed to seed; 143 tokens average that out
-    r = run_case(sh, 11, 13, 0, 2, True, precision, ragged=True, seed=5, std=std, perturb=perturb)
-    print("unaligned", precision, assert_parity(r, precision, "unaligned"))
+    # 3 x 10 and 11 x 13 tokens.  In bf16 mode the max-norm error of the small attention gradients on the 30-token
+    # batch is set by a handful of roundings: 0.9e-2 to 2.0e-2 over seeds 5 to 8 against the 2e-2 tolerance, 0.9e-2
+    # to 1.6e-2 on the 143-token batch (more tokens average the roundings out)
+    r = run_case(sh, B, S, 0, 2, True, precision, ragged=True, seed=5, std=std, perturb=perturb)
+    print("unaligned", precision, B, S, assert_parity(r, precision, "unaligned"))
     r["model"].close()
 
 

@@ -33,7 +33,7 @@ def test_base_full_step_with_embeddings():
 
 def test_base_stage2_benchmark_configuration():
     sh = synth.bert_base_shape(6)
-    r = run_case(sh, 64, 128, 3, 3, False, 1, full_backprop=False)
+    r = run_case(sh, 64, 128, 3, 3, False, 1, full_backprop=False, rounded_oracle=True)
     print("base 3/3 64x128", assert_parity(r, 1, "base-bench"))
     assert len(r["pos"]) == 64 * 19
     r["model"].close()
@@ -87,18 +87,40 @@ def test_base_final_stage_full_size():
     # final stage of the BERT-Base schedule at full size: 12 layers, bottom 9 frozen, top 3 trainable,
     # batch 64 x seq 128; every gradient element against the oracle
     sh = synth.bert_base_shape(12)
-    r = run_case(sh, 64, 128, 9, 3, False, 1, full_backprop=False)
+    r = run_case(sh, 64, 128, 9, 3, False, 1, perturb=0.05, full_backprop=False, rounded_oracle=True)
     print("base 9/3 64x128", assert_parity(r, 1, "base-final"))
     r["model"].close()
 
 
-@pytest.mark.gpu
-def test_large_final_stage_full_size():
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_large_final_stage_full_size(seed):
     # final stage of the BERT-Large schedule at full size: 24 layers, bottom 18 frozen, top 6 trainable,
-    # batch 64 x seq 128 (the oracle needs about a minute and 10 GB for this one)
+    # batch 64 x seq 128, on three seeds.  Two references: the oracle on the fp32 master weights (the 2e-2 of
+    # bf16 mode; rounding the matrices to bf16 alone already moves the query/key gradients of the lowest
+    # trainable layer by 1.3e-2 to 1.7e-2 of their largest entry) and, on the first seed, the oracle on the
+    # bf16-rounded matrices the matrix cores read (what is left is the kernels' own arithmetic: 1.2e-2).
     sh = synth.bert_large_shape(24)
-    r = run_case(sh, 64, 128, 18, 6, False, 1, full_backprop=False)
-    print("large 18/6 64x128", assert_parity(r, 1, "large-final"))
+    r = run_case(sh, 64, 128, 18, 6, False, 1, seed=seed, perturb=0.05 if seed == 2 else 0.0, full_backprop=False,
+                 rounded_oracle=(seed == 0))
+    print("large 18/6 64x128 seed", seed, assert_parity(r, 1, "large-final"))
+    if seed == 0:
+        # the LAMB update of this step (Section 4.1: LAMB, learning rate 0.00088), element by element: the oracle's
+        # optimizer on the library's own fp32 gradients
+        from oracle import mslt_oracle as O
+        from paper_2011_13635_amd import binding
+        m = r["model"]
+        names = synth.trainable_names(sh, 18, 6, False)
+        before = synth.unpack_weights(sh, m.mslt_get_params())
+        m.mslt_apply_update(binding.lamb(lr=0.00088))
+        after = synth.unpack_weights(sh, m.mslt_get_params())
+        W64 = O.to_f64({n: before[n] for n in names})
+        new_ref, _ = O.optimizer_update(W64, {n: r["grads"][n] for n in names}, O.new_opt_state(W64), kind="lamb", lr=0.00088)
+        for n in before:
+            if n not in names:
+                assert np.array_equal(before[n], after[n]), n
+                continue
+            dw, dref = after[n].astype(np.float64) - W64[n], new_ref[n] - W64[n]
+            assert np.abs(dw - dref).max() <= 2e-4 * np.abs(dref).max() + 2.0 ** -22 * np.abs(W64[n]).max(), n
     r["model"].close()
 
 
@@ -106,7 +128,7 @@ def test_base_final_stage_full_size_long_sequences():
     # final stage of the BERT-Base schedule on the long sequences of the last tenth of training (Section 4.2):
     # 12 layers, bottom 9 frozen, top 3 trainable, batch 16 x seq 512; every gradient element against the oracle
     sh = synth.bert_base_shape(12)
-    r = run_case(sh, 16, 512, 9, 3, False, 1, seed=5, full_backprop=False)
+    r = run_case(sh, 16, 512, 9, 3, False, 1, seed=5, perturb=0.05, full_backprop=False)
     print("base 9/3 16x512", assert_parity(r, 1, "base-final-long"))
     r["model"].close()
 
