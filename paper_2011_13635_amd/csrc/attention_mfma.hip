@@ -138,103 +138,201 @@ __device__ __forceinline__ void load_ctx8(const bf16* __restrict__ ctx, const fl
 }
 
 // ---- forward --------------------------------------------------------------------------------
+// The K and V^T tiles of one step (one key tile of one work item) as they sit in registers between the
+// global loads and the LDS writes: issued one step ahead, so that the loads of step i+1 are in flight
+// while step i computes.
+struct KvRegs {
+  u32x4_t k[4], v[4];
+  float bias;
+};
+__device__ __forceinline__ void fetch_kv(KvRegs& r, const bf16* __restrict__ kbase, const bf16* __restrict__ vbase,
+                                         size_t ld, const int32_t* __restrict__ am_row, float mask_bias, int tid) {
+  const int c = tid & 7, rr = tid >> 3;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) r.k[p] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)(rr + 32 * p) * ld + 8 * c);
+  const bf16* q = vbase + (size_t)(4 * rr) * ld + 8 * c;     // rows 4rr..4rr+3, d 8c..8c+7
+#pragma unroll
+  for (int p = 0; p < 4; ++p) r.v[p] = *reinterpret_cast<const u32x4_t*>(q + p * ld);
+  r.bias = (tid < TILE) ? (am_row[tid] ? 0.f : mask_bias) : 0.f;
+}
+__device__ __forceinline__ void commit_kv(const KvRegs& r, bf16* __restrict__ Ks, bf16* __restrict__ Vt,
+                                          float* __restrict__ bias, int tid) {
+  const int c = tid & 7, rr = tid >> 3;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    int row = rr + 32 * p;
+    *reinterpret_cast<u32x4_t*>(Ks + row * DH + 8 * (c ^ swz8(row))) = r.k[p];
+  }
+  const int pos = perm_pos(4 * rr), d = 8 * c;
+  const uint32_t LO = 0x05040100u, HI = 0x07060302u;
+  put4(Vt, d + 0, pos, r.v[0].x, r.v[1].x, r.v[2].x, r.v[3].x, LO);
+  put4(Vt, d + 1, pos, r.v[0].x, r.v[1].x, r.v[2].x, r.v[3].x, HI);
+  put4(Vt, d + 2, pos, r.v[0].y, r.v[1].y, r.v[2].y, r.v[3].y, LO);
+  put4(Vt, d + 3, pos, r.v[0].y, r.v[1].y, r.v[2].y, r.v[3].y, HI);
+  put4(Vt, d + 4, pos, r.v[0].z, r.v[1].z, r.v[2].z, r.v[3].z, LO);
+  put4(Vt, d + 5, pos, r.v[0].z, r.v[1].z, r.v[2].z, r.v[3].z, HI);
+  put4(Vt, d + 6, pos, r.v[0].w, r.v[1].w, r.v[2].w, r.v[3].w, LO);
+  put4(Vt, d + 7, pos, r.v[0].w, r.v[1].w, r.v[2].w, r.v[3].w, HI);
+  if (tid < TILE) bias[tid] = r.bias;
+}
+
+constexpr int FWD_BUF_ELEMS = TILE * DH + DH * TLD;                     // K rows + V^T of one step
+constexpr int FWD_LDS_BYTES = 2 * (FWD_BUF_ELEMS * 2 + TILE * 4);       // two steps
+
+// One workgroup takes `per_wg` consecutive work items (item = 128 queries of one (batch, head), numbered
+// query tile fastest, then head, then batch) and walks their key tiles as one sequence of steps over two
+// LDS buffers: while step i runs on one buffer, the K/V rows (and, at an item's first step, the Q
+// fragments) of step i+1 are already on their way from memory.
 template <bool DROP>
-__global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+__global__ void __launch_bounds__(256, 2) k_attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
                                                        float* __restrict__ lse, const int32_t* __restrict__ am, int S,
                                                        int nh, float scale, float mask_bias, DropSpec drop,
-                                                       float* __restrict__ ctx32) {
-  __shared__ __attribute__((aligned(16))) bf16 Ks[TILE * DH];
-  __shared__ __attribute__((aligned(16))) bf16 Vt[DH * TLD];
-  __shared__ __attribute__((aligned(16))) float bias[TILE];
+                                                       float* __restrict__ ctx32, int n_items, int per_wg) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char fwd_lds[];
+  bf16* const tiles = reinterpret_cast<bf16*>(fwd_lds);
+  float* const biases = reinterpret_cast<float*>(fwd_lds + 2 * FWD_BUF_ELEMS * 2);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
-  const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const int H = nh * DH;
+  const int H = nh * DH, nkt = S / TILE;
   const size_t ld = 3 * (size_t)H;
-  const bf16* base = qkv + (size_t)b * S * ld + h * DH;
-  const int q = qt * TILE + wave * 32 + n;  // this lane's query inside the sequence
+  const int first = blockIdx.x * per_wg;
+  const int count = min(per_wg, n_items - first);
+  if (count <= 0) return;
+  const int steps = count * nkt;
+  // scores, running maximum and sum live in the base-2 domain: exp(x) = 2^(x log2 e) with the factor folded
+  // into the score scale and the mask bias, so that a probability costs one subtraction and one v_exp_f32
+  constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+  const float scale2 = scale * LOG2E;
+  mask_bias *= LOG2E;
+
+  // addresses of a step
+  auto item_of = [&](int step, int& b, int& h, int& qt, int& kt) {
+    const int it = first + step / nkt;
+    kt = step % nkt;
+    qt = it % nkt;
+    h = (it / nkt) % nh;
+    b = it / (nkt * nh);
+  };
+  KvRegs regs;
+  bf16x8_t qn[4];
+  auto fetch = [&](int step) {
+    int b, h, qt, kt;
+    item_of(step, b, h, qt, kt);
+    const bf16* base = qkv + (size_t)b * S * ld + h * DH;
+    fetch_kv(regs, base + H + (size_t)kt * TILE * ld, base + 2 * H + (size_t)kt * TILE * ld, ld,
+             am + (size_t)b * S + kt * TILE, mask_bias, tid);
+    if (kt == 0) {
+      const int q = qt * TILE + wave * 32 + n;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        qn[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)q * ld + 16 * ks + 8 * half);
+    }
+  };
+
+  fetch(0);
+  commit_kv(regs, tiles, tiles + TILE * DH, biases, tid);
+  __syncthreads();
 
   bf16x8_t qf[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)q * ld + 16 * ks + 8 * half);
-
   float m_run = -INFINITY, l_run = 0.f;
   f32x16_t o0 = zero16(), o1 = zero16();
-  for (int kt = 0; kt < S / TILE; ++kt) {
-    if (kt > 0) __syncthreads();
-    load_tile_rows(Ks, base + H + (size_t)kt * TILE * ld, ld, tid);
-    load_tile_transposed(Vt, base + 2 * H + (size_t)kt * TILE * ld, ld, tid);
-    if (tid < TILE) bias[tid] = am[b * S + kt * TILE + tid] ? 0.f : mask_bias;
-    __syncthreads();
-
-    f32x16_t s[4];
+#pragma unroll 1
+  for (int step = 0; step < steps; ++step) {
+    int b, h, qt, kt;
+    item_of(step, b, h, qt, kt);
+    const bf16* Ks = tiles + (step & 1) * FWD_BUF_ELEMS;
+    const bf16* Vt = Ks + TILE * DH;
+    const float* bias = biases + (step & 1) * TILE;
+    const int q = qt * TILE + wave * 32 + n;  // this lane's query inside the sequence
+    if (kt == 0) {
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-      s[kb] = zero16();
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) s[kb] = MFMA(frag_rows(Ks, kb * 32 + n, 2 * ks + half), qf[ks], s[kb]);
+      for (int ks = 0; ks < 4; ++ks) qf[ks] = qn[ks];
+      m_run = -INFINITY;
+      l_run = 0.f;
+      o0 = zero16();
+      o1 = zero16();
     }
-    float tmax = -INFINITY;
+    if (step + 1 < steps) fetch(step + 1);
+
+    // the tile's keys go through the running softmax in two halves of 64: half the score registers
+#pragma unroll 1
+    for (int kh = 0; kh < 2; ++kh) {
+      f32x16_t s[2];
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
+      for (int j = 0; j < 2; ++j) {
+        s[j] = zero16();
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        float4 bb = *reinterpret_cast<const float4*>(&bias[kb * 32 + 8 * g + 4 * half]);
-        s[kb][4 * g + 0] = s[kb][4 * g + 0] * scale + bb.x;
-        s[kb][4 * g + 1] = s[kb][4 * g + 1] * scale + bb.y;
-        s[kb][4 * g + 2] = s[kb][4 * g + 2] * scale + bb.z;
-        s[kb][4 * g + 3] = s[kb][4 * g + 3] * scale + bb.w;
-        tmax = fmaxf(tmax, fmaxf(fmaxf(s[kb][4 * g], s[kb][4 * g + 1]), fmaxf(s[kb][4 * g + 2], s[kb][4 * g + 3])));
+        for (int ks = 0; ks < 4; ++ks) s[j] = MFMA(frag_rows(Ks, (2 * kh + j) * 32 + n, 2 * ks + half), qf[ks], s[j]);
       }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    float m_new = fmaxf(m_run, tmax);
-    float alpha = __expf(m_run - m_new);   // 0 on the first tile (m_run = -inf)
-    float psum = 0.f;
+      float tmax = -INFINITY;
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __expf(s[kb][r] - m_new);
-        s[kb][r] = p;
-        psum += p;
-      }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    if constexpr (DROP) {   // the row sum above is of the undropped probabilities; the product below uses the kept ones
-      const uint64_t rowbase = (((uint64_t)b * nh + h) * S + q) * S + (uint64_t)kt * TILE;
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb)
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const uint64_t r = drop_quad(drop, (rowbase + kb * 32 + 8 * g + 4 * half) >> 2);
+          float4 bb = *reinterpret_cast<const float4*>(&bias[(2 * kh + j) * 32 + 8 * g + 4 * half]);
+          s[j][4 * g + 0] = s[j][4 * g + 0] * scale2 + bb.x;
+          s[j][4 * g + 1] = s[j][4 * g + 1] * scale2 + bb.y;
+          s[j][4 * g + 2] = s[j][4 * g + 2] * scale2 + bb.z;
+          s[j][4 * g + 3] = s[j][4 * g + 3] * scale2 + bb.w;
+          tmax = fmaxf(tmax, fmaxf(fmaxf(s[j][4 * g], s[j][4 * g + 1]), fmaxf(s[j][4 * g + 2], s[j][4 * g + 3])));
+        }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      float m_new = fmaxf(m_run, tmax);
+      float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on an item's first half tile (m_run = -inf)
+      float psum = 0.f;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) s[kb][4 * g + j] *= drop_field(drop, r, j);
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(s[j][r] - m_new);
+          s[j][r] = p;
+          psum += p;
+        }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+      if constexpr (DROP) {   // the row sum above is of the undropped probabilities; the product below uses the kept ones
+        const uint64_t rowbase = (((uint64_t)b * nh + h) * S + q) * S + (uint64_t)kt * TILE;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const uint64_t r = drop_quad(drop, (rowbase + (2 * kh + j) * 32 + 8 * g + 4 * half) >> 2);
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) s[j][4 * g + jj] *= drop_field(drop, r, jj);
+          }
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        o0[r] *= alpha;
+        o1[r] *= alpha;
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          bf16x8_t pf = pack_frag(s[j], c);
+          o0 = MFMA(frag_transposed(Vt, n, 2 * kh + j, c, half), pf, o0);
+          o1 = MFMA(frag_transposed(Vt, 32 + n, 2 * kh + j, c, half), pf, o1);
         }
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      o0[r] *= alpha;
-      o1[r] *= alpha;
-    }
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        bf16x8_t pf = pack_frag(s[kb], c);
-        o0 = MFMA(frag_transposed(Vt, n, kb, c, half), pf, o0);
-        o1 = MFMA(frag_transposed(Vt, 32 + n, kb, c, half), pf, o1);
+    if (kt == nkt - 1) {
+      float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+      float inv = 1.0f / l_tot;
+      bf16* out = ctx + ((size_t)b * S + qt * TILE + wave * 32) * H + h * DH;
+      store_acc_T(out, H, n, half, o0, inv);
+      store_acc_T(out + 32, H, n, half, o1, inv);
+      if (ctx32 != nullptr) {
+        float* out32 = ctx32 + ((size_t)b * S + qt * TILE + wave * 32) * H + h * DH;
+        store_acc_T_f32(out32, H, n, half, o0, inv);
+        store_acc_T_f32(out32 + 32, H, n, half, o1, inv);
       }
+      if (lse != nullptr && half == 0) lse[((size_t)b * nh + h) * S + q] = (m_run + __builtin_amdgcn_logf(l_tot)) * LN2;
+    }
+    if (step + 1 < steps) {
+      bf16* Kn = tiles + ((step + 1) & 1) * FWD_BUF_ELEMS;
+      commit_kv(regs, Kn, Kn + TILE * DH, biases + ((step + 1) & 1) * TILE, tid);
+    }
+    __syncthreads();
   }
-  float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  float inv = 1.0f / l_tot;
-  bf16* out = ctx + ((size_t)b * S + qt * TILE + wave * 32) * H + h * DH;
-  store_acc_T(out, H, n, half, o0, inv);
-  store_acc_T(out + 32, H, n, half, o1, inv);
-  if (ctx32 != nullptr) {
-    float* out32 = ctx32 + ((size_t)b * S + qt * TILE + wave * 32) * H + h * DH;
-    store_acc_T_f32(out32, H, n, half, o0, inv);
-    store_acc_T_f32(out32 + 32, H, n, half, o1, inv);
-  }
-  if (lse != nullptr && half == 0) lse[((size_t)b * nh + h) * S + q] = m_run + __logf(l_tot);
 }
 
 // ---- backward, query side: delta and dQ -----------------------------------------------------
@@ -570,17 +668,30 @@ constexpr int KV_LDS_BYTES = (2 * TILE * DH + 2 * DH * TLD) * 2 + 2 * TILE * 4;
 
 bool attention_mfma_supported(int S, int dh) { return dh == DH && S >= TILE && S % TILE == 0; }
 
+template <bool DROP>
+static hipError_t attention_fwd_mfma_t(const AttnDesc& a, hipStream_t s) {
+  static bool attr_set = false;     // one flag per instantiation
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_fwd_mfma<DROP>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, FWD_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  // two workgroups fit a compute unit (LDS and registers); up to that many, one item each keeps the most
+  // units busy, beyond it a workgroup walks several items so that loads run ahead of the arithmetic
+  const int n_items = a.B * a.nh * (a.S / TILE);
+  const int slots = 2 * 256;
+  const int per_wg = (n_items + slots - 1) / slots;
+  const int n_wg = (n_items + per_wg - 1) / per_wg;
+  k_attn_fwd_mfma<DROP><<<dim3(n_wg), dim3(256), FWD_LDS_BYTES, s>>>(
+      (const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh, 1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop,
+      a.ctx_f32, n_items, per_wg);
+  return hipGetLastError();
+}
 hipError_t attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
   if (!attention_mfma_supported(a.S, a.dh)) return hipErrorInvalidValue;
-  dim3 grid(a.S / TILE, a.nh, a.B);
   // dropout is a compile-time variant so that the plain kernels carry none of its registers
-  if (a.drop.thr)
-    k_attn_fwd_mfma<true><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
-                                                     1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop, a.ctx_f32);
-  else
-    k_attn_fwd_mfma<false><<<grid, dim3(256), 0, s>>>((const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.attn_mask, a.S, a.nh,
-                                                      1.0f / sqrtf((float)a.dh), a.mask_bias, a.drop, a.ctx_f32);
-  return hipGetLastError();
+  return a.drop.thr ? attention_fwd_mfma_t<true>(a, s) : attention_fwd_mfma_t<false>(a, s);
 }
 
 template <bool DROP>

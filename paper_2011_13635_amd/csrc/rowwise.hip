@@ -1084,18 +1084,24 @@ __global__ void __launch_bounds__(256) k_opt_pass1(OptHyper h, const OptTensor* 
     }
   }
 }
-__global__ void k_lamb_ratio(const OptTensor* __restrict__ tensors, int tensor0, int n_tensors,
-                             const float* __restrict__ chunk_norms, float* __restrict__ ratio) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
+// one wavefront per tensor: lane j adds chunks j, j+64, ... in that order, then the lanes are added in a fixed
+// butterfly order, so the ratio is the same in every run
+__global__ void __launch_bounds__(64) k_lamb_ratio(const OptTensor* __restrict__ tensors, int tensor0, int n_tensors,
+                                                   const float* __restrict__ chunk_norms, float* __restrict__ ratio) {
+  const int i = blockIdx.x, lane = threadIdx.x;
   if (i >= n_tensors) return;
   OptTensor tn = tensors[tensor0 + i];
   float sw = 0.f, su = 0.f;
-  for (int c = 0; c < tn.n_chunks; ++c) {
+  for (int c = lane; c < tn.n_chunks; c += 64) {
     sw += chunk_norms[2 * (size_t)(tn.first_chunk + c)];
     su += chunk_norms[2 * (size_t)(tn.first_chunk + c) + 1];
   }
-  float wn = sqrtf(sw), un = sqrtf(su);
-  ratio[tensor0 + i] = (wn > 0.f && un > 0.f) ? wn / un : 1.0f;
+  sw = wave_sum(sw);
+  su = wave_sum(su);
+  if (lane == 0) {
+    float wn = sqrtf(sw), un = sqrtf(su);
+    ratio[tensor0 + i] = (wn > 0.f && un > 0.f) ? wn / un : 1.0f;
+  }
 }
 __global__ void __launch_bounds__(256) k_lamb_pass2(OptHyper h, const OptTensor* __restrict__ tensors,
                                                     const int32_t* __restrict__ tsteps,
@@ -1131,7 +1137,7 @@ hipError_t optimizer_step(const OptHyper& h, const OptTensor* tensors, const int
                                                    chunk_norms);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || h.kind == 0) return e;
-  k_lamb_ratio<<<dim3((n_tensors + 63) / 64), dim3(64), 0, s>>>(tensors, tensor0, n_tensors, chunk_norms, ratio);
+  k_lamb_ratio<<<dim3(n_tensors), dim3(64), 0, s>>>(tensors, tensor0, n_tensors, chunk_norms, ratio);
   k_lamb_pass2<<<dim3(n_chunks), dim3(256), 0, s>>>(h, tensors, tsteps, chunk_tensor, chunk0, w, m, v, shadow, ratio);
   return hipGetLastError();
 }
