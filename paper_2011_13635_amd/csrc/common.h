@@ -161,7 +161,10 @@ hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t
 // global -> LDS directly in any of the three layouts; M % tile_m == 0, N % tile_n == 0.
 // rk: k extent of a ring stage, 32 or 64 (K % rk == 0).
 bool gemm_ring_supported(const GemmDesc& d, int tile_m, int tile_n, int rk);
-hipError_t gemm_ring(const GemmDesc& d, int tile_m, int tile_n, int rk, int splitk, float* partials, hipStream_t s);
+// keep_partials: with splitk > 1, leave the partial sums in `partials` and skip the kernel that adds them (the
+// caller adds them later, see ReduceJob); only for a plain fp32 result (no bias, activation, addend or dropout)
+hipError_t gemm_ring(const GemmDesc& d, int tile_m, int tile_n, int rk, int splitk, float* partials, hipStream_t s,
+                     bool keep_partials = false);
 
 // ---- attention ------------------------------------------------------------------------------
 struct AttnDesc {
@@ -232,16 +235,34 @@ struct LnBwdDrop {
   int n_mapped = 0;
   int accumulate = 0;   // dgamma, dbeta and the column sums are added to what the outputs hold
 };
+// A sum of partial results that may be carried out later, many at a time in one launch (reduce_batch):
+// out[c] (+)= sum over p < n_partials of partial[p*N + c], partials added in index order.  `flat` picks the
+// work split for few partials of many elements (split-k partial products); otherwise the split is the one for
+// many partials of a row (column sums).  Two jobs of one batch must not write the same output.
+struct ReduceJob {
+  const float* partial;
+  float* out;
+  uint32_t n_partials, N;
+  uint32_t first_block;    // set by reduce_batch
+  uint32_t flags;          // 1 = add to what out holds, 2 = flat
+};
+inline ReduceJob reduce_job(const float* partial, float* out, int n_partials, size_t N, bool accumulate, bool flat) {
+  return ReduceJob{partial, out, (uint32_t)n_partials, (uint32_t)N, 0u, (accumulate ? 1u : 0u) | (flat ? 2u : 0u)};
+}
+hipError_t reduce_batch(ReduceJob* jobs, int n, hipStream_t s);
+
 // dz from dy, xhat, rstd, gamma; dgamma, dbeta and (if dzsum != null) the column sums of dz (of dzm
 // with output dropout) via partials in scratch (ln_bwd_scratch_floats(rows, H) floats).
 // dy_f32: dy is fp32 whatever the activation type; dz32 (or null): a second, unrounded fp32 copy of dz
 // (the residual branch of the backward pass carries fp32 in bf16 mode, see model.hip).
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
                   float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s,
-                  int dy_f32 = 0, float* dz32 = nullptr);
+                  int dy_f32 = 0, float* dz32 = nullptr, ReduceJob* later = nullptr, int* n_later = nullptr);
 // column sums of Y[rows, N] (leading dimension ld) into out[N]; scratch holds ceil(rows/64)*N floats
+// later (ln_bwd: room for 3, *n_later receives the count): the sums of the partials are not launched but
+// described there for reduce_batch; scratch must then stay untouched until that batch has run
 hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s,
-                  int accumulate = 0);   // accumulate: out += sums
+                  int accumulate = 0, ReduceJob* later = nullptr);   // accumulate: out += sums
 size_t colsum_scratch_floats(int rows, int N);
 size_t ln_bwd_scratch_floats(int rows, int H);
 

@@ -418,8 +418,11 @@ bool gemm_ring_supported(const GemmDesc& d, int tile_m, int tile_n, int rk) {
   return true;
 }
 
-hipError_t gemm_ring(const GemmDesc& d, int tile_m, int tile_n, int rk, int splitk, float* partials, hipStream_t s) {
+hipError_t gemm_ring(const GemmDesc& d, int tile_m, int tile_n, int rk, int splitk, float* partials, hipStream_t s,
+                     bool keep_partials) {
   if (!gemm_ring_supported(d, tile_m, tile_n, rk)) return hipErrorInvalidValue;
+  if (keep_partials && (!d.epi.out_f32 || d.epi.bias || d.epi.act != EPI_NONE || d.epi.drop.thr || d.epi.out2))
+    return hipErrorInvalidValue;
   if (splitk < 1 || splitk > d.K / rk) return hipErrorInvalidValue;
   if (splitk > 1 && partials == nullptr) return hipErrorInvalidValue;
   ring::Params p;
@@ -443,7 +446,7 @@ hipError_t gemm_ring(const GemmDesc& d, int tile_m, int tile_n, int rk, int spli
     else if (tile_m == 256) e = ring::launch_layout<256, 128, 32>(d, p, grid, s);
     else e = ring::launch_layout<128, 256, 32>(d, p, grid, s);
   }
-  if (e != hipSuccess || splitk == 1) return e;
+  if (e != hipSuccess || splitk == 1 || keep_partials) return e;
   size_t n8 = (size_t)d.M * d.N / 8;
   k_splitk_reduce<<<dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s>>>(partials, splitk, d.M, d.N, d.epi);
   return hipGetLastError();

@@ -41,10 +41,11 @@ enum { P_W = N_HEAD, P_B, C_W, C_B, N_HEAD_NSP };
 
 // Optional per-kernel-class timing with HIP events on the model's stream (off by default).
 enum ProfClass { PC_GEMM_NT = 0, PC_GEMM_NN, PC_GEMM_TN, PC_GEMM_SIMT, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD, PC_LN_BWD,
-                 PC_COLSUM, PC_EMBED, PC_HEAD_MISC, PC_CE, PC_EMBED_BWD, PC_OPT, PC_COUNT };
+                 PC_COLSUM, PC_EMBED, PC_HEAD_MISC, PC_CE, PC_EMBED_BWD, PC_OPT, PC_REDUCE, PC_COUNT };
 static const char* kProfNames[PC_COUNT] = {"gemm_mfma_nt", "gemm_mfma_nn", "gemm_mfma_tn", "gemm_simt", "attention_fwd",
                                            "attention_bwd", "layernorm_fwd", "layernorm_bwd", "bias_colsum", "embed_fwd",
-                                           "head_gather_scatter", "cross_entropy", "embed_bwd", "optimizer"};
+                                           "head_gather_scatter", "cross_entropy", "embed_bwd", "optimizer", "gradient_sums"};
+static int pick_splitk(int M, int N, int K);
 struct ProfSpan {
   hipEvent_t a, b;
   int cls;
@@ -123,6 +124,14 @@ struct mslt_model {
   void *c_xhat2, *c_dz2, *c_dc;   // compacted top layer: rows of xhat2, dz2 and dC (buffers of their own: the side
                                   // stream may still be reading the head's when the top layer starts)
   float *splitk2, *red2;
+  // Sums of partial results that only the optimizer reads (parameter gradients: LayerNorm and bias column
+  // sums, split-k partial products of the weight gradients) are not launched one by one: their partials go
+  // to an arena of their own, the jobs are listed here and one launch at the end of the step adds them all.
+  // Off when layers share parameters (a shared tensor is then written by one layer and added to by others,
+  // which the order of single launches keeps and one batch would not).
+  std::vector<ReduceJob> later;
+  float* later_arena = nullptr; size_t later_floats = 0, later_used = 0;
+  bool later_on = false;
   int32_t *e_rank, *e_cnt, *e_start, *e_order, *e_blockcnt;
   float* e_partial;                    // [Tp, H] run sums of the embedding backward
   OptTensor* o_tensors; int32_t* o_chunk_tensor; int32_t* o_tsteps; float* o_chunk_norms; float* o_ratio;
@@ -343,6 +352,22 @@ static size_t carve(mslt_model* m, char* base) {
   m->splitk = b.take<float>(m->splitk_floats * 4);
   m->splitk2 = b.take<float>(m->splitk_floats * 4);
   m->red2 = b.take<float>(red * 4);
+  {
+    // room for one step's partials with every stashed layer trainable at full batch size
+    auto dw = [&](size_t Mo, size_t No, size_t rowsK) -> size_t {
+      if (!m->mfma || Mo % 128 || No % 128 || rowsK % 64) return 0;
+      int sk = pick_splitk((int)Mo, (int)No, (int)rowsK);
+      return sk > 1 ? (size_t)sk * Mo * No : 0;
+    };
+    size_t layer = 2 * ln_bwd_scratch_floats((int)Tp, (int)H) + colsum_scratch_floats((int)Tp, (int)(3 * H + F + 2 * H)) +
+                   dw(3 * H, H, Tp) + dw(H, H, Tp) + dw(F, H, Tp) + dw(H, F, Tp);
+    size_t head = 2 * ln_bwd_scratch_floats((int)rows, (int)H) + colsum_scratch_floats((int)Mp, (int)(Vp + 2 * H)) +
+                  dw(H, H, Mp) + 2 * (dw(3 * H, H, Mp) + dw(H, H, Mp) + dw(F, H, Mp) + dw(H, F, Mp));
+    m->later_floats = rup((size_t)m->n_stash * layer + head, 64);
+    const size_t cap = (size_t)1 << 30;      // 4 GiB; what does not fit is summed at once, as without the arena
+    if (m->later_floats > cap) m->later_floats = cap;
+    m->later_arena = b.take<float>(m->later_floats * 4);
+  }
   m->e_rank = b.take<int32_t>(Tp * 4); m->e_order = b.take<int32_t>(Tp * 4);
   m->e_cnt = b.take<int32_t>(rup(m->V, 4) * 4); m->e_start = b.take<int32_t>(rup(m->V, 4) * 4);
   m->e_partial = b.take<float>(Tp * H * 4);
@@ -547,6 +572,23 @@ extern "C" int mslt_get_params(const mslt_model* m, float* host, size_t n_floats
 }
 
 // ---- GEMM dispatch --------------------------------------------------------------------------
+// space for partial sums that are added at the end of the step, or null when the arena is used up or off
+static float* later_take(mslt_model* m, size_t floats) {
+  floats = rup(floats, 64);
+  if (!m->later_on || m->later_used + floats > m->later_floats) return nullptr;
+  float* p = m->later_arena + m->later_used;
+  m->later_used += floats;
+  return p;
+}
+static int later_flush(mslt_model* m) {
+  if (m->later.empty()) return MSLT_OK;
+  double bytes = 0.0;
+  for (const ReduceJob& j : m->later) bytes += 4.0 * j.N * (j.n_partials + 1.0);
+  ProfScope ps(m, PC_REDUCE, 0.0, bytes);
+  HIP_TRY(reduce_batch(m->later.data(), (int)m->later.size(), m->stream));
+  m->later.clear();
+  return MSLT_OK;
+}
 static int pick_splitk(int M, int N, int K) {
   // Few output tiles and a long contraction: split k.  The factor minimises a small cost model
   // fitted to measured launches (microseconds): one 64-wide k tile of a 128x128 workgroup takes
@@ -648,8 +690,10 @@ static bool ring_plan(const GemmDesc& d, bool allow_splitk, size_t partial_float
   return best > 0.0;
 }
 
+// sum_later: the result is a parameter gradient nothing reads before the optimizer, so a split product may
+// leave its partial sums for the batch at the end of the step
 static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false, hipStream_t st = nullptr,
-                    float* partials = nullptr) {
+                    float* partials = nullptr, bool sum_later = false) {
   if (!st) { st = m->stream; partials = m->splitk; }
   const bool use_mfma = m->mfma && gemm_mfma_supported(d);
   const double out_esz = d.epi.out_f32 ? 4.0 : (double)m->esz;
@@ -664,8 +708,17 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false,
   const bool nt = d.a_kcontig && d.b_kcontig, tn = !d.a_kcontig && !d.b_kcontig;
   if (use_mfma && tn && gemm_ring_supported(d, 128, 128, 64)) {
     int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
-    while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
-    HIP_TRY(gemm_ring(d, 128, 128, 64, sk, partials, st));
+    float* kept = nullptr;
+    if (sk > 1 && sum_later && d.epi.out_f32 && d.epi.ldo == d.N && !d.epi.bias && d.epi.act == EPI_NONE && !d.epi.drop.thr &&
+        !d.epi.out2)
+      kept = later_take(m, (size_t)sk * d.M * d.N);
+    if (kept) {
+      HIP_TRY(gemm_ring(d, 128, 128, 64, sk, kept, st, true));
+      m->later.push_back(reduce_job(kept, (float*)d.epi.out, sk, (size_t)d.M * d.N, d.epi.accumulate != 0, true));
+    } else {
+      while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
+      HIP_TRY(gemm_ring(d, 128, 128, 64, sk, partials, st));
+    }
   } else if (use_mfma && nt && ring_plan(d, allow_splitk, m->splitk_floats, &rp)) {
     HIP_TRY(gemm_ring(d, rp.tm, rp.tn, rp.rk, rp.sk, partials, st));
   } else if (use_mfma) {
@@ -720,15 +773,16 @@ static int linear_bwd_input(mslt_model* m, const void* dY, int rows, int N, int 
   return run_gemm(m, d, allow_splitk);
 }
 // dW[N,K] = dY[rows,N]^T X[rows,K]   (fp32 out, contraction over rows)
+// sum_later = false for a tensor that something else writes or adds to later in the same step
 static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int ldy, const void* X, int K, float* dW,
-                             bool again = false) {
+                             bool again = false, bool sum_later = true) {
   GemmDesc d;
   d.A = dY; d.lda = ldy; d.a_kcontig = 0; d.M = N;
   d.B = X; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = rows;
   d.epi.out = dW; d.epi.ldo = K; d.epi.out_f32 = 1; d.epi.accumulate = m->acc_now;
   hipStream_t st; float *partials, *red;
   RC(side_fork(m, &st, &partials, &red, again));
-  return run_gemm(m, d, true, st, partials);
+  return run_gemm(m, d, true, st, partials, sum_later);
 }
 
 static int ln_forward(mslt_model* m, const void* a, const void* r, const float* g, const float* b, void* out, LnStash st,
@@ -796,6 +850,12 @@ static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, flo
   ProfScope ps(m, PC_COLSUM, (double)rows * N, (double)rows * N * m->esz);
   hipStream_t st; float *partials, *red;
   RC(side_fork(m, &st, &partials, &red, again));
+  if (float* kept = later_take(m, colsum_scratch_floats(rows, N))) {
+    ReduceJob j;
+    HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, kept, st, m->acc_now, &j));
+    m->later.push_back(j);
+    return MSLT_OK;
+  }
   HIP_TRY(colsum(m->dtype, dY, ld, rows, N, out, red, st, m->acc_now));
   return MSLT_OK;
 }
@@ -808,6 +868,13 @@ static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const fl
                                       rows * m->H);
   LnBwdDrop dd = dd_in;
   dd.accumulate = m->acc_now;
+  if (float* kept = later_take(m, ln_bwd_scratch_floats(rows, m->H))) {
+    ReduceJob j[3];
+    int n = 0;
+    HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, kept, rows, m->H, dd, m->stream, dy_f32, dz32, j, &n));
+    m->later.insert(m->later.end(), j, j + n);
+    return MSLT_OK;
+  }
   HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, dd, m->stream, dy_f32, dz32));
   return MSLT_OK;
 }
@@ -940,6 +1007,9 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   m->have_grads = false;
   m->acc_now = 0;
   m->stash_base = f;
+  m->later.clear();          // (a step that failed half-way may have left jobs behind)
+  m->later_used = 0;
+  m->later_on = m->lpg == 1;
 
   // S0: batch check and compaction of the predicted positions (only index scratch is written)
   HIP_TRY(batch_scan(bt->input_ids, bt->token_type_ids, bt->attn_mask, bt->labels, T, m->V, m->cfg.type_vocab, m->cap,
@@ -1034,7 +1104,8 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   // S7: head backward
   // over the padded vocabulary (the padded columns of dZ are zero and the output bias reserves them)
   RC(bias_grad(m, m->dz, m->Vp, Mr, m->Vp, Gf(m, th + H_BOUT)));
-  if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD), true));
+  // (the embedding backward adds the lookup's gradient to the same tensor later in this step)
+  if (train_emb) RC(linear_bwd_weight(m, m->dz, Mr, Vr, m->Vp, m->hm, H, Gf(m, T_WORD), true, false));
   // few output tiles, contraction over the whole vocabulary: split it
   RC(linear_bwd_input(m, m->dz, Mr, Vr, m->Vp, Wg(m, T_WORD), H, m->d_hm, EPI_NONE, nullptr, true));
   RC(ln_backward(m, m->d_hm, m->xhat_t, m->rstd_t, Wf(m, th + H_LNG), m->d_gt, Gf(m, th + H_LNG), Gf(m, th + H_LNB), nullptr, Mr));
@@ -1082,6 +1153,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
                       Gf(m, T_WORD), Gf(m, T_POS), Gf(m, T_TYPE), m->e_rank, m->e_cnt, m->e_start, m->e_order, m->e_blockcnt,
                       m->cfg.max_pos, m->red_scratch, m->e_partial, s));
   }
+  RC(later_flush(m));
   m->last_f = f; m->last_k = k; m->last_emb = train_emb; m->last_B = B; m->last_S = S; m->last_M = M;
   return MSLT_OK;
 }

@@ -342,6 +342,87 @@ static hipError_t reduce_partials(const float* partial, int n_partials, int N, f
   return hipGetLastError();
 }
 
+// ---- many such sums in one launch ------------------------------------------------------------
+// The job table travels in the kernel arguments.  A workgroup finds its job by its index; a row job uses the
+// arithmetic of k_reduce_partials (same order of additions, so the result does not depend on whether a sum
+// was carried out at once or later), a flat job adds the partials of four consecutive elements per thread.
+constexpr int REDUCE_BATCH_JOBS = 112;
+struct ReduceBatch {
+  ReduceJob job[REDUCE_BATCH_JOBS];
+  int n;
+};
+__global__ void __launch_bounds__(1024) k_reduce_batch(ReduceBatch b) {
+  __shared__ float sh[32][33];
+  int lo = 0, hi = b.n - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (b.job[mid].first_block <= blockIdx.x) lo = mid; else hi = mid - 1;
+  }
+  const ReduceJob j = b.job[lo];
+  const uint32_t blk = blockIdx.x - j.first_block;
+  const float* __restrict__ partial = j.partial;
+  const size_t N = j.N;
+  const int n_partials = (int)j.n_partials;
+  if (j.flags & 2u) {
+    const size_t i = ((size_t)blk * 1024 + threadIdx.x) * 4;
+    if (i >= N) return;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = 0; p < n_partials; ++p) {
+      float4 a = *reinterpret_cast<const float4*>(partial + (size_t)p * N + i);
+      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+    }
+    float4* o = reinterpret_cast<float4*>(j.out + i);
+    if (j.flags & 1u) {
+      float4 old = *o;
+      v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+    }
+    *o = v;
+    return;
+  }
+  int cl = threadIdx.x & 31, pl = threadIdx.x >> 5;
+  size_t c = (size_t)blk * 32 + cl;
+  float acc = 0.f;
+  if (c < N) {
+    int p = pl;
+    for (; p + 96 < n_partials; p += 128) {
+      float v0 = partial[(size_t)p * N + c], v1 = partial[(size_t)(p + 32) * N + c];
+      float v2 = partial[(size_t)(p + 64) * N + c], v3 = partial[(size_t)(p + 96) * N + c];
+      acc += v0; acc += v1; acc += v2; acc += v3;
+    }
+    for (; p < n_partials; p += 32) acc += partial[(size_t)p * N + c];
+  }
+  sh[pl][cl] = acc;
+  __syncthreads();
+  if (pl == 0 && c < N) {
+    float v = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < 32; ++jj) v += sh[jj][cl];
+    j.out[c] = (j.flags & 1u) ? j.out[c] + v : v;
+  }
+}
+hipError_t reduce_batch(ReduceJob* jobs, int n, hipStream_t s) {
+  for (int at = 0; at < n; at += REDUCE_BATCH_JOBS) {
+    ReduceBatch b;
+    b.n = n - at < REDUCE_BATCH_JOBS ? n - at : REDUCE_BATCH_JOBS;
+    uint32_t blocks = 0;
+    for (int i = 0; i < b.n; ++i) {
+      ReduceJob& j = jobs[at + i];
+      if (j.flags & 2u) {
+        if (j.N % 4 || ((reinterpret_cast<uintptr_t>(j.partial) | reinterpret_cast<uintptr_t>(j.out)) & 15))
+          return hipErrorInvalidValue;
+      }
+      j.first_block = blocks;
+      blocks += (j.flags & 2u) ? (j.N + 4095) / 4096 : (j.N + 31) / 32;
+      b.job[i] = j;
+    }
+    if (blocks == 0) continue;
+    k_reduce_batch<<<dim3(blocks), dim3(1024), 0, s>>>(b);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 // ---- LayerNorm backward ---------------------------------------------------------------------
 // One wavefront handles R consecutive rows (all loads issued before the row reductions), four
 // wavefronts per workgroup; the workgroup leaves one partial row each of dgamma = sum dy*xhat,
@@ -467,8 +548,10 @@ __global__ void __launch_bounds__(256) k_ln_bwd(const DYT* __restrict__ dy, cons
 }
 template <typename AT, typename DYT>
 static hipError_t ln_bwd_t(const DYT* dy, const AT* xhat, const float* rstd, const float* g, AT* dz, float* dz32, float* dg,
-                           float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s) {
+                           float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s,
+                           ReduceJob* later, int* n_later) {
   if (dd.out.thr && dd.dzm == nullptr) return hipErrorInvalidValue;
+  if (later != nullptr && n_later == nullptr) return hipErrorInvalidValue;
   if ((dd.out.thr || dd.in.thr) && H % 4) return hipErrorInvalidValue;
   int R = lnb_rows_per_wave(H);
   int nb = (rows + 4 * R - 1) / (4 * R);
@@ -489,20 +572,29 @@ static hipError_t ln_bwd_t(const DYT* dy, const AT* xhat, const float* rstd, con
 #undef MSLT_LNB
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (later != nullptr) {
+    int n = 0;
+    later[n++] = reduce_job(pg, dg, nb, (size_t)H, dd.accumulate, false);
+    later[n++] = reduce_job(pb, db, nb, (size_t)H, dd.accumulate, false);
+    if (dzsum) later[n++] = reduce_job(pz, dzsum, nb, (size_t)H, dd.accumulate, false);
+    *n_later = n;
+    return hipSuccess;
+  }
   ReduceArgs a{{pg, pb, pz}, {dg, db, dzsum}, dd.accumulate};
   k_reduce_partials<<<dim3((H + 31) / 32, dzsum ? 3 : 2), dim3(1024), 0, s>>>(a, nb, H);
   return hipGetLastError();
 }
 hipError_t ln_bwd(int dtype, const void* dy, const void* xhat, const float* rstd, const float* g, void* dz, float* dg,
                   float* db, float* dzsum, float* scratch, int rows, int H, const LnBwdDrop& dd, hipStream_t s, int dy_f32,
-                  float* dz32) {
+                  float* dz32, ReduceJob* later, int* n_later) {
   if (dtype == 0)
     return ln_bwd_t<float, float>((const float*)dy, (const float*)xhat, rstd, g, (float*)dz, dz32, dg, db, dzsum, scratch, rows,
-                                  H, dd, s);
+                                  H, dd, s, later, n_later);
   if (dy_f32)
     return ln_bwd_t<bf16, float>((const float*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dz32, dg, db, dzsum, scratch, rows, H,
-                                 dd, s);
-  return ln_bwd_t<bf16, bf16>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dz32, dg, db, dzsum, scratch, rows, H, dd, s);
+                                 dd, s, later, n_later);
+  return ln_bwd_t<bf16, bf16>((const bf16*)dy, (const bf16*)xhat, rstd, g, (bf16*)dz, dz32, dg, db, dzsum, scratch, rows, H, dd, s,
+                              later, n_later);
 }
 
 // ---- column sums (bias gradients) -----------------------------------------------------------
@@ -570,7 +662,7 @@ __global__ void __launch_bounds__(256) k_colsum_partial(const AT* __restrict__ y
   partial[(size_t)blockIdx.y * N + c] = acc;
 }
 hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out, float* scratch, hipStream_t s,
-                  int accumulate) {
+                  int accumulate, ReduceJob* later) {
   bool vec = (N % 8 == 0) && (ld % 8 == 0) && ((reinterpret_cast<uintptr_t>(y) & 31) == 0);
   int nchunks;
   if (vec) {
@@ -590,6 +682,10 @@ hipError_t colsum(int dtype, const void* y, int ld, int rows, int N, float* out,
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (later != nullptr) {
+    *later = reduce_job(scratch, out, nchunks, (size_t)N, accumulate != 0, false);
+    return hipSuccess;
+  }
   return reduce_partials(scratch, nchunks, N, out, s, accumulate);
 }
 

@@ -89,8 +89,13 @@ def run_case(shape, B, S, f, k, emb, precision, ragged=False, seed=0, std=0.02, 
     return out
 
 
-def assert_parity(r, precision, label=""):
+def assert_parity(r, precision, label="", grad_tol=None):
+    """grad_tol: bound on the gradients against the oracle on the fp32 masters when it is not TOL[precision]
+    (a case that also carries the oracle on the rounded matrices, where the quantisation of the matrices alone
+    takes most of 2e-2; the bound against the rounded matrices is then the sharp one)."""
     tol = TOL[precision]
+    gtol = tol if grad_tol is None else grad_tol
+    assert grad_tol is None or "rnd_grads" in r, "a wider bound against the masters needs the rounded-matrices oracle"
     # integer work: bit-exact
     assert np.array_equal(r["pos"], r["ref_info"]["pos"].astype(np.int32)), label
     assert np.array_equal(r["lab"], r["ref_info"]["labels"].astype(np.int32)), label
@@ -99,7 +104,7 @@ def assert_parity(r, precision, label=""):
     assert lerr < tol, (label, "loss", r["loss"], r["ref_loss"], lerr)
     errs = rel_errors(r["grads"], r["ref_grads"])
     worst = max(errs, key=errs.get)
-    assert errs[worst] < tol, (label, worst, errs[worst], sorted(errs.items(), key=lambda kv: -kv[1])[:5])
+    assert errs[worst] < gtol, (label, worst, errs[worst], sorted(errs.items(), key=lambda kv: -kv[1])[:5])
     assert set(r["grads"]) == set(r["ref_grads"])
     # frozen-prefix output
     ref_p = r["ref_info"]["prefix_out"]

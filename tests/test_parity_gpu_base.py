@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2011_13635_amd import synth
-from parity_util import assert_parity, run_case
+from parity_util import TOL, assert_parity, run_case
 
 pytestmark = pytest.mark.gpu
 
@@ -95,14 +95,17 @@ def test_base_final_stage_full_size():
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_large_final_stage_full_size(seed):
     # final stage of the BERT-Large schedule at full size: 24 layers, bottom 18 frozen, top 6 trainable,
-    # batch 64 x seq 128, on three seeds.  Two references: the oracle on the fp32 master weights (the 2e-2 of
-    # bf16 mode; rounding the matrices to bf16 alone already moves the query/key gradients of the lowest
-    # trainable layer by 1.3e-2 to 1.7e-2 of their largest entry) and, on the first seed, the oracle on the
-    # bf16-rounded matrices the matrix cores read (what is left is the kernels' own arithmetic: 1.2e-2).
+    # batch 64 x seq 128, on three seeds.  Two references on every seed.  The sharp one is the oracle on the
+    # matrices as bf16 mode reads them (the fp32 masters rounded to bf16 where they feed the matrix cores): what
+    # is left is the kernels' own arithmetic, asserted at 1.2e-2.  The other is the oracle on the fp32 masters:
+    # rounding the matrices alone already moves the query/key gradients of the lowest trainable layer by 1.3e-2
+    # to 1.7e-2 of their largest entry (oracle against oracle), so the two parts together scatter around 2e-2
+    # from seed to seed (measured 1.8e-2 to 2.0e-2 on layer18.wk / layer18.wq); that comparison is asserted at
+    # 3e-2 for the gradients and at 2e-2 for the loss and the frozen-prefix output.
     sh = synth.bert_large_shape(24)
     r = run_case(sh, 64, 128, 18, 6, False, 1, seed=seed, perturb=0.05 if seed == 2 else 0.0, full_backprop=False,
-                 rounded_oracle=(seed == 0))
-    print("large 18/6 64x128 seed", seed, assert_parity(r, 1, "large-final"))
+                 rounded_oracle=True)
+    print("large 18/6 64x128 seed", seed, assert_parity(r, 1, "large-final", grad_tol=1.5 * TOL[1]))
     if seed == 0:
         # the LAMB update of this step (Section 4.1: LAMB, learning rate 0.00088), element by element: the oracle's
         # optimizer on the library's own fp32 gradients
