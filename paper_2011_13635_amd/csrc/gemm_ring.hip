@@ -145,8 +145,11 @@ constexpr int lds_bytes(int TM, int TN, int RK, int NS) {
 // s_waitcnt immediate: vmcnt <= vm (63: untouched), lgkmcnt <= lgkm (15: untouched), expcnt untouched
 constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | 0x70 | ((vm >> 4) << 14) | (lgkm << 8); }
 
+// One workgroup's tile of one product; wg: the workgroup's index among the product's workgroups (the index
+// of the launch, or of the product's range of a grouped launch, which starts at a multiple of 8 so that
+// wg % 8 is still the XCD the hardware has put the workgroup on).
 template <int TM, int TN, int RK, int NS, bool A_KC, bool B_KC>
-__global__ void __launch_bounds__(64 * n_waves(TM, TN)) k_gemm_ring(Params p) {
+__device__ __forceinline__ void ring_tile(const Params& p, const int wg) {
   constexpr int NWAVES = n_waves(TM, TN);
   constexpr int WN = TN == 256 ? 4 : 2, WM = NWAVES / WN;         // wavefront grid
   constexpr int WTM = TM / WM, WTN = TN / WN;                     // wavefront tile: 128x64 or 64x64
@@ -175,7 +178,8 @@ __global__ void __launch_bounds__(64 * n_waves(TM, TN)) k_gemm_ring(Params p) {
   // contiguous range of tiles, ordered in bands of 8 tile rows, column by column inside a band (the
   // tiles that run together on an XCD then share few operand panels in its L2)
   const int total = p.tiles_m * p.tiles_n * p.splitk;
-  int pid = blockIdx.x;
+  if (wg >= total) return;      // padding of a grouped launch (the whole workgroup leaves)
+  int pid = wg;
   {
     int per = (total + 7) >> 3, tall = total & 7;
     if (tall == 0) tall = 8;
@@ -352,6 +356,26 @@ __global__ void __launch_bounds__(64 * n_waves(TM, TN)) k_gemm_ring(Params p) {
   }
 }
 
+template <int TM, int TN, int RK, int NS, bool A_KC, bool B_KC>
+__global__ void __launch_bounds__(64 * n_waves(TM, TN)) k_gemm_ring(Params p) {
+  ring_tile<TM, TN, RK, NS, A_KC, B_KC>(p, (int)blockIdx.x);
+}
+// Several products of one operand layout in one launch: product g owns the workgroups first[g] .. first[g+1]-1.
+// Products too small to fill the chip one by one (the weight gradients of a layer) then need no split of their
+// contraction, hence no partial sums in memory.
+constexpr int GROUP_MAX = 4;
+struct GroupParams {
+  Params p[GROUP_MAX];
+  int first[GROUP_MAX + 1];
+  int n;
+};
+template <int TM, int TN, int RK, int NS, bool A_KC, bool B_KC>
+__global__ void __launch_bounds__(64 * n_waves(TM, TN)) k_gemm_ring_grouped(GroupParams gp) {
+  int g = 0;
+  while (g + 1 < gp.n && (int)blockIdx.x >= gp.first[g + 1]) ++g;
+  ring_tile<TM, TN, RK, NS, A_KC, B_KC>(gp.p[g], (int)blockIdx.x - gp.first[g]);
+}
+
 // ring depth: what fits the 160 KB of LDS of a compute unit, at most 6 stages
 constexpr int ring_depth(int TM, int TN, int RK) {
   if (TM == 128 && TN == 128) return 64 * 1024 / ((TM + TN) * RK * 2);   // two workgroups per compute unit
@@ -364,6 +388,7 @@ constexpr int ring_depth(int TM, int TN, int RK) {
   template __global__ void k_gemm_ring<TM, TN, RK, ring_depth(TM, TN, RK), true, false>(Params);  \
   template __global__ void k_gemm_ring<TM, TN, RK, ring_depth(TM, TN, RK), false, true>(Params);  \
   template __global__ void k_gemm_ring<TM, TN, RK, ring_depth(TM, TN, RK), false, false>(Params);
+template __global__ void k_gemm_ring_grouped<128, 128, 64, ring_depth(128, 128, 64), false, false>(GroupParams);
 MSLT_RING_INSTANCES(256, 256, 64)
 MSLT_RING_INSTANCES(256, 128, 64)
 MSLT_RING_INSTANCES(128, 256, 64)
@@ -397,6 +422,43 @@ static hipError_t launch_layout(const GemmDesc& d, const Params& p, dim3 grid, h
 }
 
 }  // namespace ring
+
+static void ring_params(const GemmDesc& d, int tile_m, int tile_n, int splitk, float* partials, ring::Params* p) {
+  p->A = reinterpret_cast<const bf16*>(d.A);
+  p->B = reinterpret_cast<const bf16*>(d.B);
+  p->M = d.M; p->N = d.N; p->K = d.K;
+  p->lda = d.lda; p->ldb = d.ldb;
+  p->splitk = splitk;
+  p->tiles_m = d.M / tile_m; p->tiles_n = d.N / tile_n;
+  p->partials = partials;
+  p->epi = d.epi;
+}
+
+int gemm_ring_group_max() { return ring::GROUP_MAX; }
+hipError_t gemm_ring_grouped_tn(const GemmDesc* d, int n, hipStream_t s) {
+  using namespace ring;
+  constexpr int TM = 128, TN = 128, RK = 64, NS = ring_depth(TM, TN, RK), LDS = lds_bytes(TM, TN, RK, NS);
+  if (n < 1 || n > GROUP_MAX) return hipErrorInvalidValue;
+  GroupParams gp;
+  gp.n = n;
+  int at = 0;
+  for (int i = 0; i < n; ++i) {
+    if (d[i].a_kcontig || d[i].b_kcontig || !gemm_ring_supported(d[i], TM, TN, RK)) return hipErrorInvalidValue;
+    ring_params(d[i], TM, TN, 1, nullptr, &gp.p[i]);
+    gp.first[i] = at;
+    at += (gp.p[i].tiles_m * gp.p[i].tiles_n + 7) & ~7;      // every product starts on XCD 0
+  }
+  for (int i = n; i <= GROUP_MAX; ++i) gp.first[i] = at;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_ring_grouped<TM, TN, RK, NS, false, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  k_gemm_ring_grouped<TM, TN, RK, NS, false, false><<<dim3((unsigned)at), dim3(64 * n_waves(TM, TN)), LDS, s>>>(gp);
+  return hipGetLastError();
+}
 
 bool gemm_ring_supported(const GemmDesc& d, int tile_m, int tile_n, int rk) {
   if (rk != 32 && rk != 64) return false;

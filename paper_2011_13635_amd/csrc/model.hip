@@ -129,6 +129,12 @@ struct mslt_model {
   // to an arena of their own, the jobs are listed here and one launch at the end of the step adds them all.
   // Off when layers share parameters (a shared tensor is then written by one layer and added to by others,
   // which the order of single launches keeps and one batch would not).
+  // Inside a layer's backward the weight-gradient products and bias column sums are collected and queued on
+  // the side stream together when the layer is done (one fork; the products as one grouped launch).
+  struct SideColsum { const void* dY; int ld, rows, N; float* out; int accumulate; };
+  std::vector<GemmDesc> side_dw;
+  std::vector<SideColsum> side_cs;
+  bool side_collect = false;
   std::vector<ReduceJob> later;
   float* later_arena = nullptr; size_t later_floats = 0, later_used = 0;
   bool later_on = false;
@@ -651,9 +657,12 @@ static int layer_backward_begin(mslt_model* m, int l) {
   }
   m->d_d = m->gset[p].d_d; m->d_u = m->gset[p].d_u; m->d_z1 = m->gset[p].d_z1; m->d_qkv = m->gset[p].d_qkv;
   m->d_dm = m->gset[p].d_dm; m->d_z1m = m->gset[p].d_z1m;
+  m->side_collect = true;
   return MSLT_OK;
 }
+static int side_flush(mslt_model* m);
 static int layer_backward_end(mslt_model* m, int l) {
+  if (int rc = side_flush(m)) return rc;
   m->acc_now = 0;
   if (!m->side_forked) return MSLT_OK;
   HIP_TRY(hipEventRecord(m->ev_set[l & 1], m->side));
@@ -780,6 +789,10 @@ static int linear_bwd_weight(mslt_model* m, const void* dY, int rows, int N, int
   d.A = dY; d.lda = ldy; d.a_kcontig = 0; d.M = N;
   d.B = X; d.ldb = K; d.b_kcontig = 0; d.N = K; d.K = rows;
   d.epi.out = dW; d.epi.ldo = K; d.epi.out_f32 = 1; d.epi.accumulate = m->acc_now;
+  if (m->side_collect) {
+    m->side_dw.push_back(d);
+    return MSLT_OK;
+  }
   hipStream_t st; float *partials, *red;
   RC(side_fork(m, &st, &partials, &red, again));
   return run_gemm(m, d, true, st, partials, sum_later);
@@ -847,6 +860,10 @@ static int layer_forward(mslt_model* m, int l, const mslt_batch* bt, int Tr, con
 }
 
 static int bias_grad(mslt_model* m, const void* dY, int ld, int rows, int N, float* out, bool again = false) {
+  if (m->side_collect) {
+    m->side_cs.push_back({dY, ld, rows, N, out, m->acc_now});
+    return MSLT_OK;
+  }
   ProfScope ps(m, PC_COLSUM, (double)rows * N, (double)rows * N * m->esz);
   hipStream_t st; float *partials, *red;
   RC(side_fork(m, &st, &partials, &red, again));
@@ -876,6 +893,61 @@ static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const fl
     return MSLT_OK;
   }
   HIP_TRY(ln_bwd(m->dtype, dy, xhat, rstd, g, dz, dg, db, dzsum, m->red_scratch, rows, m->H, dd, m->stream, dy_f32, dz32));
+  return MSLT_OK;
+}
+
+// Queues what a layer's backward has collected.  The weight-gradient products go out as grouped launches of
+// the large-tile kernel's 128x128 form when every one of them fits it (together they fill the chip, so none
+// splits its contraction and no partial sums travel through memory), one by one otherwise.
+static int side_flush(mslt_model* m) {
+  m->side_collect = false;
+  if (m->side_dw.empty() && m->side_cs.empty()) return MSLT_OK;
+  const int acc_keep = m->acc_now;
+  bool grouped = m->mfma && !m->side_dw.empty();
+  for (const GemmDesc& d : m->side_dw) grouped = grouped && gemm_mfma_supported(d) && gemm_ring_supported(d, 128, 128, 64);
+  int wgs = 0;
+  for (const GemmDesc& d : m->side_dw) wgs += (d.M / 128) * (d.N / 128);
+  grouped = grouped && wgs >= 256;       // fewer tiles than compute units: splitting k is the better way to fill them
+  bool forked = false;
+  hipStream_t st; float *partials, *red;
+  if (grouped) {
+    RC(side_fork(m, &st, &partials, &red));
+    forked = true;
+    const int gmax = gemm_ring_group_max();
+    for (size_t at = 0; at < m->side_dw.size(); at += gmax) {
+      const int n = (int)std::min((size_t)gmax, m->side_dw.size() - at);
+      double flops = 0.0, bytes = 0.0;
+      for (int i = 0; i < n; ++i) {
+        const GemmDesc& d = m->side_dw[at + i];
+        flops += 2.0 * d.M * d.N * d.K;
+        bytes += ((double)d.M * d.K + (double)d.N * d.K) * m->esz + (double)d.M * d.N * 4.0;
+      }
+      ProfScope ps(m, PC_GEMM_TN, flops, bytes);
+      HIP_TRY(gemm_ring_grouped_tn(&m->side_dw[at], n, st));
+    }
+  } else {
+    for (const GemmDesc& d : m->side_dw) {
+      RC(side_fork(m, &st, &partials, &red, forked));
+      forked = true;
+      RC(run_gemm(m, d, true, st, partials, true));
+    }
+  }
+  for (const auto& c : m->side_cs) {
+    RC(side_fork(m, &st, &partials, &red, forked));
+    forked = true;
+    m->acc_now = c.accumulate;
+    ProfScope ps(m, PC_COLSUM, (double)c.rows * c.N, (double)c.rows * c.N * m->esz);
+    if (float* kept = later_take(m, colsum_scratch_floats(c.rows, c.N))) {
+      ReduceJob j;
+      HIP_TRY(colsum(m->dtype, c.dY, c.ld, c.rows, c.N, c.out, kept, st, c.accumulate, &j));
+      m->later.push_back(j);
+    } else {
+      HIP_TRY(colsum(m->dtype, c.dY, c.ld, c.rows, c.N, c.out, red, st, c.accumulate));
+    }
+  }
+  m->acc_now = acc_keep;
+  m->side_dw.clear();
+  m->side_cs.clear();
   return MSLT_OK;
 }
 
@@ -1007,6 +1079,7 @@ static int stage_step_enqueue(mslt_model* m, int f, int k, int train_emb, const 
   m->have_grads = false;
   m->acc_now = 0;
   m->stash_base = f;
+  m->side_dw.clear(); m->side_cs.clear(); m->side_collect = false;
   m->later.clear();          // (a step that failed half-way may have left jobs behind)
   m->later_used = 0;
   m->later_on = m->lpg == 1;
