@@ -900,14 +900,21 @@ static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const fl
 // the large-tile kernel's 128x128 form when every one of them fits it (together they fill the chip, so none
 // splits its contraction and no partial sums travel through memory), one by one otherwise.
 static int side_flush(mslt_model* m) {
+  constexpr int GROUP_BIG_MIN = 160;     // 256x256 tiles only when they still cover most compute units
   m->side_collect = false;
   if (m->side_dw.empty() && m->side_cs.empty()) return MSLT_OK;
   const int acc_keep = m->acc_now;
-  bool grouped = m->mfma && !m->side_dw.empty();
-  for (const GemmDesc& d : m->side_dw) grouped = grouped && gemm_mfma_supported(d) && gemm_ring_supported(d, 128, 128, 64);
-  int wgs = 0;
-  for (const GemmDesc& d : m->side_dw) wgs += (d.M / 128) * (d.N / 128);
+  bool grouped = m->mfma && !m->side_dw.empty(), big = true;
+  int wgs = 0, wgs_big = 0;
+  for (const GemmDesc& d : m->side_dw) {
+    grouped = grouped && gemm_mfma_supported(d) && gemm_ring_supported(d, 128, 128, 64);
+    big = big && gemm_ring_supported(d, 256, 256, 64);
+    wgs += (d.M / 128) * (d.N / 128);
+    wgs_big += (d.M / 256) * (d.N / 256);
+  }
   grouped = grouped && wgs >= 256;       // fewer tiles than compute units: splitting k is the better way to fill them
+  // 256x256 tiles move half the bytes per FLOP; worth it when they still cover most of the 256 compute units
+  const int tile = (grouped && big && wgs_big >= GROUP_BIG_MIN && wgs_big <= 256) ? 256 : 128;
   bool forked = false;
   hipStream_t st; float *partials, *red;
   if (grouped) {
@@ -923,7 +930,7 @@ static int side_flush(mslt_model* m) {
         bytes += ((double)d.M * d.K + (double)d.N * d.K) * m->esz + (double)d.M * d.N * 4.0;
       }
       ProfScope ps(m, PC_GEMM_TN, flops, bytes);
-      HIP_TRY(gemm_ring_grouped_tn(&m->side_dw[at], n, st));
+      HIP_TRY(gemm_ring_grouped_tn(&m->side_dw[at], n, tile, st));
     }
   } else {
     for (const GemmDesc& d : m->side_dw) {
