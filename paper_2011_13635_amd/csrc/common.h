@@ -162,9 +162,10 @@ hipError_t gemm_mfma(const GemmDesc& d, int splitk, float* partials, hipStream_t
 // rk: k extent of a ring stage, 32 or 64 (K % rk == 0).
 bool gemm_ring_supported(const GemmDesc& d, int tile_m, int tile_n, int rk);
 // Up to gemm_ring_group_max() products whose operands are both k-strided (weight gradients) as one launch of
-// tile x tile tiles (128 or 256), none of them split; each must pass gemm_ring_supported(d, tile, tile, 64).
+// tile_m x tile_n tiles (128x128, 256x128 or 256x256), none of them split; each must pass
+// gemm_ring_supported(d, tile_m, tile_n, 64).
 int gemm_ring_group_max();
-hipError_t gemm_ring_grouped_tn(const GemmDesc* d, int n, int tile, hipStream_t s);
+hipError_t gemm_ring_grouped_tn(const GemmDesc* d, int n, int tile_m, int tile_n, hipStream_t s);
 // keep_partials: with splitk > 1, leave the partial sums in `partials` and skip the kernel that adds them (the
 // caller adds them later, see ReduceJob); only for a plain fp32 result (no bias, activation, addend or dropout)
 hipError_t gemm_ring(const GemmDesc& d, int tile_m, int tile_n, int rk, int splitk, float* partials, hipStream_t s,

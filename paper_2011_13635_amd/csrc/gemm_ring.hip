@@ -390,6 +390,7 @@ constexpr int ring_depth(int TM, int TN, int RK) {
   template __global__ void k_gemm_ring<TM, TN, RK, ring_depth(TM, TN, RK), false, false>(Params);
 template __global__ void k_gemm_ring_grouped<128, 128, 64, ring_depth(128, 128, 64), false, false>(GroupParams);
 template __global__ void k_gemm_ring_grouped<256, 256, 64, ring_depth(256, 256, 64), false, false>(GroupParams);
+template __global__ void k_gemm_ring_grouped<256, 128, 64, ring_depth(256, 128, 64), false, false>(GroupParams);
 MSLT_RING_INSTANCES(256, 256, 64)
 MSLT_RING_INSTANCES(256, 128, 64)
 MSLT_RING_INSTANCES(128, 256, 64)
@@ -436,10 +437,10 @@ static void ring_params(const GemmDesc& d, int tile_m, int tile_n, int splitk, f
 }
 
 int gemm_ring_group_max() { return ring::GROUP_MAX; }
-template <int TILE>
+template <int TM, int TN>
 static hipError_t grouped_tn(const GemmDesc* d, int n, hipStream_t s) {
   using namespace ring;
-  constexpr int TM = TILE, TN = TILE, RK = 64, NS = ring_depth(TM, TN, RK), LDS = lds_bytes(TM, TN, RK, NS);
+  constexpr int RK = 64, NS = ring_depth(TM, TN, RK), LDS = lds_bytes(TM, TN, RK, NS);
   static_assert(LDS <= 160 * 1024, "LDS of a gfx950 compute unit");
   GroupParams gp;
   gp.n = n;
@@ -461,10 +462,11 @@ static hipError_t grouped_tn(const GemmDesc* d, int n, hipStream_t s) {
   k_gemm_ring_grouped<TM, TN, RK, NS, false, false><<<dim3((unsigned)at), dim3(64 * n_waves(TM, TN)), LDS, s>>>(gp);
   return hipGetLastError();
 }
-hipError_t gemm_ring_grouped_tn(const GemmDesc* d, int n, int tile, hipStream_t s) {
+hipError_t gemm_ring_grouped_tn(const GemmDesc* d, int n, int tile_m, int tile_n, hipStream_t s) {
   if (n < 1 || n > ring::GROUP_MAX) return hipErrorInvalidValue;
-  if (tile == 128) return grouped_tn<128>(d, n, s);
-  if (tile == 256) return grouped_tn<256>(d, n, s);
+  if (tile_m == 128 && tile_n == 128) return grouped_tn<128, 128>(d, n, s);
+  if (tile_m == 256 && tile_n == 128) return grouped_tn<256, 128>(d, n, s);
+  if (tile_m == 256 && tile_n == 256) return grouped_tn<256, 256>(d, n, s);
   return hipErrorInvalidValue;
 }
 

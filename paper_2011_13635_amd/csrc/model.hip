@@ -904,17 +904,25 @@ static int side_flush(mslt_model* m) {
   m->side_collect = false;
   if (m->side_dw.empty() && m->side_cs.empty()) return MSLT_OK;
   const int acc_keep = m->acc_now;
-  bool grouped = m->mfma && !m->side_dw.empty(), big = true;
-  int wgs = 0, wgs_big = 0;
+  // Tile of the grouped launch: 256x256 moves half the bytes per FLOP of 128x128 and 256x128 three quarters,
+  // but one such workgroup fills a compute unit, so a large tile is taken when its tiles still cover most of
+  // the 256 compute units in one round; fewer than 256 small tiles: splitting k fills the chip better.
+  bool grouped = m->mfma && !m->side_dw.empty();
+  int cnt[3] = {0, 0, 0};
+  bool ok[3] = {true, true, true};
+  static const int shape[3][2] = {{256, 256}, {256, 128}, {128, 128}};
   for (const GemmDesc& d : m->side_dw) {
-    grouped = grouped && gemm_mfma_supported(d) && gemm_ring_supported(d, 128, 128, 64);
-    big = big && gemm_ring_supported(d, 256, 256, 64);
-    wgs += (d.M / 128) * (d.N / 128);
-    wgs_big += (d.M / 256) * (d.N / 256);
+    grouped = grouped && gemm_mfma_supported(d);
+    for (int c = 0; c < 3; ++c) {
+      ok[c] = ok[c] && gemm_ring_supported(d, shape[c][0], shape[c][1], 64);
+      cnt[c] += (d.M / shape[c][0]) * (d.N / shape[c][1]);
+    }
   }
-  grouped = grouped && wgs >= 256;       // fewer tiles than compute units: splitting k is the better way to fill them
-  // 256x256 tiles move half the bytes per FLOP; worth it when they still cover most of the 256 compute units
-  const int tile = (grouped && big && wgs_big >= GROUP_BIG_MIN && wgs_big <= 256) ? 256 : 128;
+  int pick = -1;
+  if (ok[0] && cnt[0] >= GROUP_BIG_MIN && cnt[0] <= 256) pick = 0;
+  else if (ok[1] && cnt[1] >= GROUP_BIG_MIN && cnt[1] <= 256) pick = 1;
+  else if (ok[2] && cnt[2] >= 256) pick = 2;
+  grouped = grouped && pick >= 0;
   bool forked = false;
   hipStream_t st; float *partials, *red;
   if (grouped) {
@@ -930,7 +938,7 @@ static int side_flush(mslt_model* m) {
         bytes += ((double)d.M * d.K + (double)d.N * d.K) * m->esz + (double)d.M * d.N * 4.0;
       }
       ProfScope ps(m, PC_GEMM_TN, flops, bytes);
-      HIP_TRY(gemm_ring_grouped_tn(&m->side_dw[at], n, tile, st));
+      HIP_TRY(gemm_ring_grouped_tn(&m->side_dw[at], n, shape[pick][0], shape[pick][1], st));
     }
   } else {
     for (const GemmDesc& d : m->side_dw) {
