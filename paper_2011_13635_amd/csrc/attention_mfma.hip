@@ -418,8 +418,10 @@ __global__ void __launch_bounds__(256) k_attn_bwd_q_mfma(const bf16* __restrict_
 }
 
 // ---- backward, key side: dK and dV ----------------------------------------------------------
+// (two wavefronts per SIMD asked for: the accumulators then stay in VGPRs, where the softmax arithmetic reads
+//  them without v_accvgpr moves, and two workgroups share a compute unit; the dropout variant would spill)
 template <bool DROP>
-__global__ void __launch_bounds__(256) k_attn_bwd_kv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dctx,
+__global__ void __launch_bounds__(256, DROP ? 1 : 2) k_attn_bwd_kv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dctx,
                                                           const float* __restrict__ lse,
                                                           const float* __restrict__ delta, bf16* __restrict__ dqkv,
                                                           const int32_t* __restrict__ am, int S, int nh, float scale,
