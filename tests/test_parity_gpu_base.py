@@ -100,7 +100,8 @@ def test_large_final_stage_full_size(seed):
     # is left is the kernels' own arithmetic, asserted at 1.2e-2.  The other is the oracle on the fp32 masters:
     # rounding the matrices alone already moves the query/key gradients of the lowest trainable layer by 1.3e-2
     # to 1.7e-2 of their largest entry (oracle against oracle), so the two parts together scatter around 2e-2
-    # from seed to seed (measured 1.8e-2 to 2.0e-2 on layer18.wk / layer18.wq); that comparison is asserted at
+    # from seed to seed (measured 1.4e-2 to 2.0e-2, always a W_k of a low trainable layer; 0.5e-2 to 0.6e-2 against
+    # the rounded matrices); that comparison is asserted at
     # 3e-2 for the gradients and at 2e-2 for the loss and the frozen-prefix output.
     sh = synth.bert_large_shape(24)
     r = run_case(sh, 64, 128, 18, 6, False, 1, seed=seed, perturb=0.05 if seed == 2 else 0.0, full_backprop=False,
