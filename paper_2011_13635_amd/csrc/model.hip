@@ -712,9 +712,11 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false,
   // side there, so a kernel's footprint counts as much as its own speed): forward-type products (both
   // operands k-contiguous) go to the large-tile kernel; weight-gradient products (both operands k-strided)
   // to its 128x128 form, two workgroups per compute unit, fed by direct loads and transposing LDS reads;
-  // data-gradient products stay on the 128-wide register-staged kernel.
+  // data-gradient products stay on the 128-wide register-staged kernel, except the one with a wide output (the
+  // gradient of the feed-forward layer's hidden activation), which gains on the large tiles in the step as well.
   RingPlan rp;
   const bool nt = d.a_kcontig && d.b_kcontig, tn = !d.a_kcontig && !d.b_kcontig;
+  const bool nn_wide = d.a_kcontig && !d.b_kcontig && d.N >= 2048 && d.M >= 4096;
   if (use_mfma && tn && gemm_ring_supported(d, 128, 128, 64)) {
     int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
     float* kept = nullptr;
@@ -728,7 +730,7 @@ static int run_gemm(mslt_model* m, const GemmDesc& d, bool allow_splitk = false,
       while (sk > 1 && (size_t)sk * d.M * d.N > m->splitk_floats) --sk;
       HIP_TRY(gemm_ring(d, 128, 128, 64, sk, partials, st));
     }
-  } else if (use_mfma && nt && ring_plan(d, allow_splitk, m->splitk_floats, &rp)) {
+  } else if (use_mfma && (nt || nn_wide) && ring_plan(d, allow_splitk, m->splitk_floats, &rp)) {
     HIP_TRY(gemm_ring(d, rp.tm, rp.tn, rp.rk, rp.sk, partials, st));
   } else if (use_mfma) {
     int sk = allow_splitk ? pick_splitk(d.M, d.N, d.K) : 1;
