@@ -902,7 +902,7 @@ static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const fl
 // the large-tile kernel's 128x128 form when every one of them fits it (together they fill the chip, so none
 // splits its contraction and no partial sums travel through memory), one by one otherwise.
 static int side_flush(mslt_model* m) {
-  constexpr int GROUP_BIG_MIN = 160;     // 256x256 tiles only when they still cover most compute units
+  constexpr int GROUP_BIG_MIN = 160;     // a large tile only when its tiles keep at least 160 of 256 compute units busy per round
   m->side_collect = false;
   if (m->side_dw.empty() && m->side_cs.empty()) return MSLT_OK;
   const int acc_keep = m->acc_now;
@@ -920,9 +920,13 @@ static int side_flush(mslt_model* m) {
       cnt[c] += (d.M / shape[c][0]) * (d.N / shape[c][1]);
     }
   }
+  auto fills = [&](int c) {      // the large tiles run one workgroup per compute unit, in rounds of 256
+    const int rounds = (cnt[c] + 255) / 256;
+    return ok[c] && cnt[c] >= GROUP_BIG_MIN * rounds;
+  };
   int pick = -1;
-  if (ok[0] && cnt[0] >= GROUP_BIG_MIN && cnt[0] <= 256) pick = 0;
-  else if (ok[1] && cnt[1] >= GROUP_BIG_MIN && cnt[1] <= 256) pick = 1;
+  if (fills(0)) pick = 0;
+  else if (fills(1)) pick = 1;
   else if (ok[2] && cnt[2] >= 256) pick = 2;
   grouped = grouped && pick >= 0;
   bool forked = false;
