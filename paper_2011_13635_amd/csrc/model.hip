@@ -46,6 +46,20 @@ static const char* kProfNames[PC_COUNT] = {"gemm_mfma_nt", "gemm_mfma_nn", "gemm
                                            "attention_bwd", "layernorm_fwd", "layernorm_bwd", "bias_colsum", "embed_fwd",
                                            "head_gather_scatter", "cross_entropy", "embed_bwd", "optimizer", "gradient_sums"};
 static int pick_splitk(int M, int N, int K);
+// Tile of the grouped weight-gradient launch of one layer (index into kGroupTile), or -1 when the products go
+// out one by one.  cnt[c]: tiles of all the products together at shape c; ok[c]: every product fits shape c.
+// 256x256 moves half the bytes per FLOP of 128x128 and 256x128 three quarters, but one such workgroup fills a
+// compute unit, so a large tile is taken when its tiles keep at least 160 of the 256 compute units busy in every
+// round; with fewer than 256 small tiles splitting k fills the chip better than grouping.
+static const int kGroupTile[3][2] = {{256, 256}, {256, 128}, {128, 128}};
+static int group_tile_pick(const int (&cnt)[3], const bool (&ok)[3]) {
+  constexpr int BIG_MIN = 160;
+  for (int c = 0; c < 2; ++c) {
+    const int rounds = (cnt[c] + 255) / 256;
+    if (ok[c] && cnt[c] >= BIG_MIN * rounds) return c;
+  }
+  return ok[2] && cnt[2] >= 256 ? 2 : -1;
+}
 struct ProfSpan {
   hipEvent_t a, b;
   int cls;
@@ -365,10 +379,20 @@ static size_t carve(mslt_model* m, char* base) {
       int sk = pick_splitk((int)Mo, (int)No, (int)rowsK);
       return sk > 1 ? (size_t)sk * Mo * No : 0;
     };
+    // (a layer whose four weight-gradient products go out as one grouped launch splits none of them)
+    const size_t mn[4][2] = {{3 * H, H}, {H, H}, {F, H}, {H, F}};
+    int cnt[3] = {0, 0, 0};
+    bool ok[3] = {m->mfma, m->mfma, m->mfma};
+    for (auto& q : mn)
+      for (int c = 0; c < 3; ++c) {
+        ok[c] = ok[c] && q[0] % kGroupTile[c][0] == 0 && q[1] % kGroupTile[c][1] == 0;
+        cnt[c] += (int)((q[0] / kGroupTile[c][0]) * (q[1] / kGroupTile[c][1]));
+      }
+    const bool layers_grouped = group_tile_pick(cnt, ok) >= 0;
     size_t layer = 2 * ln_bwd_scratch_floats((int)Tp, (int)H) + colsum_scratch_floats((int)Tp, (int)(3 * H + F + 2 * H)) +
-                   dw(3 * H, H, Tp) + dw(H, H, Tp) + dw(F, H, Tp) + dw(H, F, Tp);
+                   (layers_grouped ? 0 : dw(3 * H, H, Tp) + dw(H, H, Tp) + dw(F, H, Tp) + dw(H, F, Tp));
     size_t head = 2 * ln_bwd_scratch_floats((int)rows, (int)H) + colsum_scratch_floats((int)Mp, (int)(Vp + 2 * H)) +
-                  dw(H, H, Mp) + 2 * (dw(3 * H, H, Mp) + dw(H, H, Mp) + dw(F, H, Mp) + dw(H, F, Mp));
+                  dw(H, H, Mp) + (layers_grouped ? 0 : 2 * (dw(3 * H, H, Mp) + dw(H, H, Mp) + dw(F, H, Mp) + dw(H, F, Mp)));
     m->later_floats = rup((size_t)m->n_stash * layer + head, 64);
     const size_t cap = (size_t)1 << 30;      // 4 GiB; what does not fit is summed at once, as without the arena
     if (m->later_floats > cap) m->later_floats = cap;
@@ -902,33 +926,21 @@ static int ln_backward(mslt_model* m, const void* dy, const void* xhat, const fl
 // the large-tile kernel's 128x128 form when every one of them fits it (together they fill the chip, so none
 // splits its contraction and no partial sums travel through memory), one by one otherwise.
 static int side_flush(mslt_model* m) {
-  constexpr int GROUP_BIG_MIN = 160;     // a large tile only when its tiles keep at least 160 of 256 compute units busy per round
   m->side_collect = false;
   if (m->side_dw.empty() && m->side_cs.empty()) return MSLT_OK;
   const int acc_keep = m->acc_now;
-  // Tile of the grouped launch: 256x256 moves half the bytes per FLOP of 128x128 and 256x128 three quarters,
-  // but one such workgroup fills a compute unit, so a large tile is taken when its tiles still cover most of
-  // the 256 compute units in one round; fewer than 256 small tiles: splitting k fills the chip better.
   bool grouped = m->mfma && !m->side_dw.empty();
   int cnt[3] = {0, 0, 0};
   bool ok[3] = {true, true, true};
-  static const int shape[3][2] = {{256, 256}, {256, 128}, {128, 128}};
   for (const GemmDesc& d : m->side_dw) {
     grouped = grouped && gemm_mfma_supported(d);
     for (int c = 0; c < 3; ++c) {
-      ok[c] = ok[c] && gemm_ring_supported(d, shape[c][0], shape[c][1], 64);
-      cnt[c] += (d.M / shape[c][0]) * (d.N / shape[c][1]);
+      ok[c] = ok[c] && gemm_ring_supported(d, kGroupTile[c][0], kGroupTile[c][1], 64);
+      cnt[c] += (d.M / kGroupTile[c][0]) * (d.N / kGroupTile[c][1]);
     }
   }
-  auto fills = [&](int c) {      // the large tiles run one workgroup per compute unit, in rounds of 256
-    const int rounds = (cnt[c] + 255) / 256;
-    return ok[c] && cnt[c] >= GROUP_BIG_MIN * rounds;
-  };
-  int pick = -1;
-  if (fills(0)) pick = 0;
-  else if (fills(1)) pick = 1;
-  else if (ok[2] && cnt[2] >= 256) pick = 2;
-  grouped = grouped && pick >= 0;
+  const int pick = grouped ? group_tile_pick(cnt, ok) : -1;
+  grouped = pick >= 0;
   bool forked = false;
   hipStream_t st; float *partials, *red;
   if (grouped) {
@@ -944,7 +956,7 @@ static int side_flush(mslt_model* m) {
         bytes += ((double)d.M * d.K + (double)d.N * d.K) * m->esz + (double)d.M * d.N * 4.0;
       }
       ProfScope ps(m, PC_GEMM_TN, flops, bytes);
-      HIP_TRY(gemm_ring_grouped_tn(&m->side_dw[at], n, shape[pick][0], shape[pick][1], st));
+      HIP_TRY(gemm_ring_grouped_tn(&m->side_dw[at], n, kGroupTile[pick][0], kGroupTile[pick][1], st));
     }
   } else {
     for (const GemmDesc& d : m->side_dw) {
