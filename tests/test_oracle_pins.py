@@ -119,6 +119,14 @@ def test_softmax_and_layernorm_invariants():
     # textbook values for one row: z = (1,2,3,4): mean 2.5, biased var 1.25
     y, _ = O.layer_norm(np.array([[1.0, 2, 3, 4]]), np.array([2.0, 2, 2, 2]), np.array([1.0, 1, 1, 1]), 0.0)
     assert np.allclose(y, 1 + 2 * np.array([-1.5, -0.5, 0.5, 1.5]) / math.sqrt(1.25))
+    # where epsilon sits: a two-element row (-1e-6, +1e-6) has mean 0 and biased variance 1e-12, the size of BERT's
+    # epsilon itself (BERT by citation, Section 4.1), so with epsilon added to the variance under the root the
+    # normalised values are -+1/sqrt(2); added to the standard deviation instead they would be -+1 (to 1e-6), with
+    # no epsilon exactly -+1, and with the unbiased variance -+1/sqrt(3)
+    y, _ = O.layer_norm(np.array([[-1e-6, 1e-6]]), np.ones(2), np.zeros(2), 1e-12)
+    assert np.allclose(y, [[-math.sqrt(0.5), math.sqrt(0.5)]], rtol=1e-12)
+    # ... and the model configurations carry that epsilon
+    assert synth.tiny_shape(1).ln_eps == 1e-12 and synth.bert_large_shape(24).ln_eps == 1e-12
     # backward invariants
     dy = rng.randn(7, 33)
     g = rng.randn(33)
