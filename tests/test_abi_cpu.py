@@ -35,6 +35,25 @@ def test_query_sizes_scale_with_config():
     assert p % 256 == 0 and w % 256 == 0
 
 
+def test_workspace_follows_the_number_of_layers_that_can_train():
+    # Section 3.2: the bottom layers only take part in the forward computation, so the per-layer stash of
+    # activations is needed for max_trainable_layers layers only (0 = every layer); parameters, gradients and
+    # moments do not depend on it
+    sh = synth.bert_large_shape(24)
+    full = binding.mslt_query_sizes(binding.make_config(sh, 32, 512, 1))
+    six = binding.mslt_query_sizes(binding.make_config(sh, 32, 512, 1, max_trainable_layers=6))
+    twelve = binding.mslt_query_sizes(binding.make_config(sh, 32, 512, 1, max_trainable_layers=12))
+    assert full[:3] == six[:3] == twelve[:3]
+    assert six[3] < twelve[3] < full[3]
+    # the stash of one layer is the same size whichever range it comes from
+    assert abs((full[3] - twelve[3]) / 12 - (twelve[3] - six[3]) / 6) < 0.01 * (twelve[3] - six[3]) / 6
+    assert binding.mslt_query_sizes(binding.make_config(sh, 32, 512, 1, max_trainable_layers=24)) == full
+    cfg = binding.make_config(sh, 32, 512, 1)
+    cfg.max_trainable_layers = -1
+    with pytest.raises(binding.MsltError):
+        binding.mslt_query_sizes(cfg)
+
+
 @pytest.mark.parametrize("field,value", [("hidden", 130), ("hidden", 4096), ("n_heads", 5), ("precision", 2),
                                          ("type_vocab", 9), ("max_seq", 1024), ("n_layers_max", 0), ("vocab", 1)])
 def test_bad_config_is_rejected(field, value):
